@@ -1,0 +1,333 @@
+"""Pins of the float64 oracle against what the paper and the mathematics fix.
+
+Each test checks the oracle against something other than itself: closed forms,
+library routines on the over-parametrised C-class softmax, 50-digit mpmath
+evaluation, central finite differences, an explicit Hessian built per sample by
+a separately written scalar routine, Krylov-subspace minimisation, direct
+linear solves and an independent minimiser.  The paper prints no worked
+numerical example, so none of its values appears here.
+"""
+import math
+
+import mpmath
+import numpy as np
+import pytest
+import scipy.optimize
+import scipy.special
+
+from oracle import brute
+from oracle import nadmm_oracle as orc
+
+
+def make_problem(n=40, p=5, C=4, seed=0, s=1.0, lam=0.3, rho=0.7, xs=0.5, with_zy=True):
+    rng = np.random.default_rng(seed)
+    A = rng.standard_normal((n, p))
+    b = rng.integers(0, C, size=n)
+    z = rng.standard_normal((p, C - 1)) * 0.4 if with_zy else None
+    y = rng.standard_normal((p, C - 1)) * 0.4 if with_zy else None
+    prob = orc.Problem(A, b, C, s=s, lam=lam, rho=rho, z=z, y=y)
+    X = rng.standard_normal((p, C - 1)) * xs
+    return prob, X, rng
+
+
+def full_logits(prob, X):
+    Z = prob.A64 @ X
+    return np.concatenate([Z, np.zeros((prob.n, 1))], axis=1)
+
+
+# ------------------------------------------------------------------ P
+def test_probabilities_sum_to_one_with_reference_class():
+    prob, X, _ = make_problem(n=200, p=7, C=6, xs=2.0)
+    Z = orc.logits(prob, X)
+    M, alpha, E = orc.lse_parts(Z)
+    P = orc.probabilities(prob, X)
+    p_ref = np.exp(-M) / alpha
+    np.testing.assert_allclose(P.sum(1) + p_ref, 1.0, rtol=0, atol=1e-15)
+    assert np.all(M >= 0) and np.all(alpha >= 1.0)
+
+
+def test_probabilities_equal_library_softmax_over_C_classes():
+    prob, X, _ = make_problem(n=300, p=6, C=5, xs=3.0)
+    ref = scipy.special.softmax(full_logits(prob, X), axis=1)[:, : prob.C - 1]
+    np.testing.assert_allclose(orc.probabilities(prob, X), ref, rtol=1e-13, atol=1e-300)
+
+
+def test_lse_identity_on_moderate_logits():
+    prob, X, _ = make_problem(n=100, p=4, C=4, xs=1.0)
+    Z = orc.logits(prob, X)
+    M, alpha, _ = orc.lse_parts(Z)
+    np.testing.assert_allclose(1.0 + np.exp(Z).sum(1), np.exp(M) * alpha, rtol=1e-13)
+
+
+# ------------------------------------------------------------------ loss
+@pytest.mark.parametrize("C", [2, 3, 10])
+def test_loss_closed_form_at_zero(C):
+    prob, _, _ = make_problem(n=123, p=6, C=C, s=0.37)
+    X = np.zeros((prob.p, C - 1))
+    u = -prob.z + prob.y / prob.rho
+    expect = prob.s * prob.n * math.log(C) + 0.5 * prob.rho * np.sum(u * u)
+    assert orc.loss(prob, X) == pytest.approx(expect, rel=1e-14)
+
+
+def test_loss_equals_library_log_softmax():
+    prob, X, _ = make_problem(n=250, p=6, C=5, xs=2.5, s=1.0, lam=0.0, rho=1.0, with_zy=False)
+    ls = scipy.special.log_softmax(full_logits(prob, X), axis=1)
+    data = -ls[np.arange(prob.n), prob.b].sum()
+    pen = 0.5 * prob.rho * np.sum(X * X)
+    assert orc.loss(prob, X) == pytest.approx(data + pen, rel=1e-13)
+
+
+def test_row_losses_against_mpmath_with_huge_logits():
+    # logits up to ~ +-700: no overflow, and agreement with 50-digit arithmetic
+    mpmath.mp.dps = 50
+    rng = np.random.default_rng(3)
+    n, p, C = 12, 3, 4
+    A = rng.standard_normal((n, p)) * 40.0
+    X = rng.standard_normal((p, C - 1)) * 8.0
+    b = rng.integers(0, C, size=n)
+    prob = orc.Problem(A, b, C)
+    Z = A @ X
+    assert np.abs(Z).max() > 300
+    got = orc.row_losses(prob, X)
+    assert np.all(np.isfinite(got))
+    for i in range(n):
+        zs = [mpmath.mpf(float(v)) for v in Z[i]]
+        ref = mpmath.log(1 + sum(mpmath.e ** v for v in zs))
+        if b[i] < C - 1:
+            ref -= zs[b[i]]
+        assert got[i] == pytest.approx(float(ref), rel=1e-13, abs=1e-13)
+
+
+def test_binary_case_is_textbook_logistic_regression():
+    prob, X, rng = make_problem(n=150, p=5, C=2, lam=0.0, rho=1.0, with_zy=False)
+    zlin = prob.A64 @ X[:, 0]
+    t = (prob.b == 0).astype(float)                # label 0 owns the free weight vector
+    data = np.sum(np.logaddexp(0.0, zlin) - t * zlin)
+    assert orc.loss(prob, X) == pytest.approx(data + 0.5 * np.sum(X * X), rel=1e-13)
+    sig = scipy.special.expit(zlin)
+    np.testing.assert_allclose(orc.grad(prob, X)[:, 0], prob.A64.T @ (sig - t) + X[:, 0], rtol=1e-12)
+    v = rng.standard_normal((prob.p, 1))
+    Hv = prob.A64.T @ (sig * (1 - sig) * (prob.A64 @ v[:, 0])) + v[:, 0]
+    np.testing.assert_allclose(orc.hessvec(prob, X, v)[:, 0], Hv, rtol=1e-12)
+
+
+# ------------------------------------------------------------------ gradient
+def test_gradient_closed_form_at_zero():
+    prob, _, _ = make_problem(n=90, p=6, C=5, s=0.5)
+    X = np.zeros((prob.p, prob.C - 1))
+    Y = np.eye(prob.C)[prob.b][:, : prob.C - 1]
+    expect = prob.s * prob.A64.T @ (1.0 / prob.C - Y) - prob.rho * prob.z + prob.y
+    np.testing.assert_allclose(orc.grad(prob, X), expect, rtol=1e-13, atol=1e-14)
+
+
+@pytest.mark.parametrize("C,s", [(2, 1.0), (4, 1.0), (7, 1.0 / 60)])
+def test_gradient_matches_central_differences(C, s):
+    prob, X, rng = make_problem(n=60, p=5, C=C, s=s)
+    G = orc.grad(prob, X)
+    h = 1e-6
+    # coordinate-wise
+    for j in range(prob.p):
+        for c in range(C - 1):
+            E = np.zeros_like(X)
+            E[j, c] = h
+            fd = (orc.loss(prob, X + E) - orc.loss(prob, X - E)) / (2 * h)
+            assert G[j, c] == pytest.approx(fd, rel=2e-7, abs=2e-8)
+    # random directions
+    for _ in range(5):
+        U = rng.standard_normal(X.shape)
+        fd = (orc.loss(prob, X + h * U) - orc.loss(prob, X - h * U)) / (2 * h)
+        assert np.sum(G * U) == pytest.approx(fd, rel=1e-7, abs=1e-8)
+
+
+def test_loss_and_gradient_match_scalar_brute_force():
+    prob, X, _ = make_problem(n=30, p=4, C=4, s=0.8)
+    args = (prob.A64.tolist(), prob.b.tolist(), prob.C, prob.s, prob.lam, prob.rho,
+            prob.z.tolist(), prob.y.tolist(), X.tolist())
+    assert orc.loss(prob, X) == pytest.approx(brute.loss(*args), rel=1e-13)
+    np.testing.assert_allclose(orc.grad(prob, X), brute.grad(*args), rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------ Hv
+def explicit_hessian(prob, X):
+    return brute.hessian(prob.A64.tolist(), prob.C, prob.s, prob.lam, prob.rho, X.tolist())
+
+
+@pytest.mark.parametrize("C", [2, 3, 4])
+def test_hessvec_equals_explicit_hessian_times_vector(C):
+    prob, X, rng = make_problem(n=25, p=4, C=C, s=0.9)
+    H = explicit_hessian(prob, X)
+    np.testing.assert_allclose(H, H.T, rtol=1e-13, atol=1e-14)
+    assert np.linalg.eigvalsh(H).min() >= (prob.lam + prob.rho) * (1 - 1e-12)
+    for _ in range(3):
+        V = rng.standard_normal(X.shape)
+        np.testing.assert_allclose(orc.hessvec(prob, X, V).reshape(-1), H @ V.reshape(-1), rtol=1e-11, atol=1e-12)
+
+
+def test_hessvec_matches_central_differences_of_gradient():
+    prob, X, rng = make_problem(n=80, p=6, C=5, s=1.0 / 80)
+    h = 1e-5
+    for _ in range(4):
+        V = rng.standard_normal(X.shape)
+        fd = (orc.grad(prob, X + h * V) - orc.grad(prob, X - h * V)) / (2 * h)
+        np.testing.assert_allclose(orc.hessvec(prob, X, V), fd, rtol=1e-6, atol=1e-9)
+
+
+def test_hessvec_symmetry_linearity_and_curvature_bound():
+    prob, X, rng = make_problem(n=120, p=7, C=6)
+    V, W = rng.standard_normal(X.shape), rng.standard_normal(X.shape)
+    HV, HW = orc.hessvec(prob, X, V), orc.hessvec(prob, X, W)
+    assert np.sum(W * HV) == pytest.approx(np.sum(V * HW), rel=1e-12)
+    assert np.sum(V * HV) >= (prob.lam + prob.rho) * np.sum(V * V)
+    np.testing.assert_allclose(orc.hessvec(prob, X, 2.0 * V - 3.0 * W), 2.0 * HV - 3.0 * HW, rtol=1e-11, atol=1e-11)
+
+
+def test_hessian_closed_form_at_zero():
+    # At X = 0 every P_ic = 1/C, so H = (s/C)(I - ee^T/C) (x) A^T A + (lam+rho) I
+    prob, _, rng = make_problem(n=70, p=5, C=4, s=0.25)
+    X = np.zeros((prob.p, prob.C - 1))
+    K = prob.C - 1
+    core = (prob.s / prob.C) * (np.eye(K) - np.ones((K, K)) / prob.C)
+    V = rng.standard_normal(X.shape)
+    expect = (prob.A64.T @ prob.A64) @ V @ core + (prob.lam + prob.rho) * V
+    np.testing.assert_allclose(orc.hessvec(prob, X, V), expect, rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------ CG
+def test_cg_iterates_minimise_the_quadratic_over_krylov_spaces():
+    prob, X, _ = make_problem(n=30, p=4, C=3)
+    H = explicit_hessian(prob, X)
+    g = orc.grad(prob, X).reshape(-1)
+    basis = []
+    v = -g.copy()
+    for k in range(1, 6):
+        basis.append(v.copy())
+        v = H @ v
+        B = np.linalg.qr(np.array(basis).T)[0]
+        coef = np.linalg.solve(B.T @ H @ B, -B.T @ g)
+        p_ref = B @ coef
+        p_k, iters, relres = orc.cg(prob, X, g.reshape(X.shape), k, 0.0)
+        assert iters == k
+        np.testing.assert_allclose(p_k.reshape(-1), p_ref, rtol=1e-8, atol=1e-10)
+        assert relres == pytest.approx(np.linalg.norm(H @ p_ref + g) / np.linalg.norm(g), rel=1e-6)
+
+
+def test_cg_with_d_iterations_solves_the_newton_system():
+    prob, X, _ = make_problem(n=40, p=4, C=3)
+    H = explicit_hessian(prob, X)
+    g = orc.grad(prob, X)
+    p_k, _, _ = orc.cg(prob, X, g, 3 * H.shape[0], 1e-14)
+    np.testing.assert_allclose(p_k.reshape(-1), np.linalg.solve(H, -g.reshape(-1)), rtol=1e-9, atol=1e-11)
+
+
+@pytest.mark.parametrize("tol", [1e-3, 1e-4])
+def test_cg_tolerance_mode_satisfies_the_inexactness_condition(tol):
+    prob, X, _ = make_problem(n=200, p=8, C=5, lam=1e-3, rho=0.05, s=1.0 / 200)
+    g = orc.grad(prob, X)
+    p_k, iters, relres = orc.cg(prob, X, g, 500, tol)
+    true_res = np.linalg.norm(orc.hessvec(prob, X, p_k) + g) / np.linalg.norm(g)
+    assert true_res <= tol * (1 + 1e-6)
+    assert relres == pytest.approx(true_res, rel=1e-5)
+    # one iteration fewer does not satisfy it (first iterate to reach the tolerance is returned)
+    p_prev, _, rel_prev = orc.cg(prob, X, g, iters - 1, 0.0)
+    assert rel_prev > tol
+
+
+def test_cg_zero_gradient_returns_zero():
+    prob, X, _ = make_problem()
+    p_k, iters, relres = orc.cg(prob, X, np.zeros_like(X), 5, 0.0)
+    assert iters == 0 and not p_k.any()
+
+
+# ------------------------------------------------------------------ line search
+def armijo_holds(prob, X, p, g, alpha, beta):
+    return orc.loss(prob, X + alpha * p) <= orc.loss(prob, X) + alpha * beta * np.sum(p * g)
+
+
+def test_line_search_returns_first_power_of_gamma_that_satisfies_armijo():
+    prob, X, _ = make_problem(n=60, p=5, C=4, lam=0.01, rho=0.05)
+    g = orc.grad(prob, X)
+    for scale in [1.0, 8.0, 50.0, 400.0]:
+        p = -scale * g                     # overshooting descent direction
+        alpha, f_new, ok, evals = orc.line_search(prob, X, p, g, 1e-4, 0.5, 30)
+        k = round(math.log(alpha, 0.5))
+        assert ok and alpha == 0.5 ** k and evals == k + 1
+        assert f_new == orc.loss(prob, X + alpha * p)
+        assert armijo_holds(prob, X, p, g, alpha, 1e-4)
+        for j in range(k):
+            assert not armijo_holds(prob, X, p, g, 0.5 ** j, 1e-4)
+    assert k > 0
+
+
+def test_line_search_accepts_unit_step_near_the_optimum():
+    prob, X, _ = make_problem(n=80, p=5, C=3)
+    Xs, _ = orc.local_newton(prob, X, 30, 200, 1e-12, 1e-13, 1e-4, 0.5, 10)
+    Xn = Xs + 1e-3
+    g = orc.grad(prob, Xn)
+    p, _, _ = orc.cg(prob, Xn, g, 200, 1e-12)
+    alpha, _, ok, evals = orc.line_search(prob, Xn, p, g, 1e-4, 0.5, 10)
+    assert alpha == 1.0 and ok and evals == 1
+
+
+def test_line_search_iteration_cap_follows_the_pseudo_code_literally():
+    prob, X, _ = make_problem(n=60, p=5, C=4)
+    g = orc.grad(prob, X)
+    p = g.copy()                           # ascent direction: Armijo can never hold
+    for imax in [0, 3, 10]:
+        alpha, f_new, ok, evals = orc.line_search(prob, X, p, g, 1e-4, 0.5, imax)
+        assert not ok
+        assert alpha == 0.5 ** (imax + 1)  # i runs to imax+1 before the break
+        assert evals == imax + 2
+        assert f_new == orc.loss(prob, X + alpha * p)
+
+
+# ------------------------------------------------------------------ Newton iteration
+def test_one_newton_step_with_exact_cg_is_the_newton_step():
+    prob, X, _ = make_problem(n=50, p=4, C=3, xs=0.05)
+    H = explicit_hessian(prob, X)
+    g = orc.grad(prob, X).reshape(-1)
+    X1, st = orc.local_newton(prob, X, 1, 500, 1e-15, 0.0, 1e-4, 0.5, 10)
+    assert st["iters"][0]["alpha"] == 1.0
+    np.testing.assert_allclose(X1.reshape(-1), X.reshape(-1) - np.linalg.solve(H, g), rtol=1e-9, atol=1e-11)
+
+
+def test_newton_loss_is_monotone_and_stats_are_consistent():
+    prob, X, _ = make_problem(n=200, p=6, C=5, lam=1e-3, rho=0.1, s=1.0 / 200, xs=1.5)
+    XT, st = orc.local_newton(prob, X, 6, 10, 0.0, 0.0, 1e-4, 0.5, 10)
+    losses = [it["loss"] for it in st["iters"]] + [st["loss_final"]]
+    assert all(b <= a for a, b in zip(losses, losses[1:]))
+    assert st["newton_iters"] == 6 and st["cg_iters_total"] == 60 and st["armijo_failed"] == 0
+    assert st["loss_initial"] == pytest.approx(orc.loss(prob, X), rel=1e-15)
+    assert st["loss_final"] == pytest.approx(orc.loss(prob, XT), rel=1e-14)
+    # iterates obey X_{t+1} = X_t + alpha_t p_t with p_t the CG output at X_t
+    it = st["iters"][2]
+    p_ref, _, _ = orc.cg(prob, it["X"], orc.grad(prob, it["X"]), 10, 0.0)
+    np.testing.assert_allclose(it["p"], p_ref, rtol=1e-12)
+    np.testing.assert_allclose(st["iters"][3]["X"], it["X"] + it["alpha"] * it["p"], rtol=1e-14)
+
+
+def test_newton_fixed_point_equals_independent_minimiser():
+    prob, X, _ = make_problem(n=150, p=5, C=4, lam=0.02, rho=0.3, s=1.0 / 150)
+    Xs, st = orc.local_newton(prob, X, 50, 200, 1e-10, 1e-11, 1e-4, 0.5, 10)
+    assert st["grad_norm_final"] < 1e-9
+
+    def fun(x):
+        Xm = x.reshape(X.shape)
+        return orc.loss(prob, Xm), orc.grad(prob, Xm).reshape(-1)
+
+    # the objective handed to scipy is pinned above; the minimiser itself is scipy's
+    res = scipy.optimize.minimize(fun, np.zeros(X.size), jac=True, method="L-BFGS-B",
+                                  options=dict(maxiter=5000, ftol=1e-15, gtol=1e-11))
+    np.testing.assert_allclose(Xs.reshape(-1), res.x, rtol=0, atol=2e-7)
+
+
+def test_newton_stops_on_gradient_tolerance():
+    prob, X, _ = make_problem(n=80, p=4, C=3)
+    Xs, st = orc.local_newton(prob, X, 50, 100, 1e-10, 1e-6, 1e-4, 0.5, 10)
+    assert st["newton_iters"] < 50 and st["grad_norm_final"] < 1e-6
+
+
+def test_forced_alphas_override_the_line_search():
+    prob, X, _ = make_problem(n=80, p=4, C=3)
+    X1, st = orc.local_newton(prob, X, 1, 5, 0.0, 0.0, 1e-4, 0.5, 10, forced_alphas=[0.25])
+    it = st["iters"][0]
+    np.testing.assert_allclose(X1, X + 0.25 * it["p"], rtol=1e-15)
