@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the local Newton-CG x-update hot path on one MI355X.
+
+One step = one pass of the whole hot path over the image-like workload
+(n = 60000, p = 784, C = 10, seeded synthetic data resident in HBM):
+    100 Hessian-vector products (random V, cycling 4 pre-generated directions),
+    100 objective+gradient evaluations,
+    1 local Newton-CG solve (10 Newton iterations, 10 CG iterations each, Armijo line search).
+The headline value is Hessian-vector products per second; the other rates are
+reported in "extra".  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak, GB/s
+HV_PER_STEP = 100
+LG_PER_STEP = 100
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="image_like")
+    ap.add_argument("--n", type=int, default=None, help="override the number of rows (testing only)")
+    ap.add_argument("--path", type=int, default=0, help="kernel path: 0 auto, 1 two-pass, 2 fused")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--only", default="", help="comma list of hv,lg,solve: restrict the step (profiling runs)")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, seconds):
+    """The float64 oracle's Hessian-vector product, timed on the host cores as it stands."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    from oracle import nadmm_oracle as orc
+
+    prob = orc.Problem(w.A, w.b, w.C, s=w.s, lam=w.lam, rho=w.rho, z=w.z, y=w.y)
+    X = w.X0.astype(np.float64)
+    V = w.V.astype(np.float64)
+    orc.hessvec(prob, X, V)  # warm-up (page faults, BLAS thread start)
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        orc.hessvec(prob, X, V)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= seconds or reps >= 200:
+            break
+    threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    avail = len(os.sched_getaffinity(0))
+    return {"value": reps / el, "unit": "Hv/s", "cores": min(threads, avail), "kind": "oracle",
+            "sample": f"{reps} float64 numpy Hessian-vector products at the full workload shape "
+                      f"({w.n}x{w.p}, C={w.C}) in {el:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one ADMM worker's data share); "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_1807_07132_amd import nadmm, workloads
+
+    torch.cuda.set_device(0)
+    w = workloads.make(args.workload, 0, args.n)
+    gp = nadmm.Problem.from_workload(w)
+    nadmm.nadmm_set_kernel_path(args.path)
+    path = nadmm.nadmm_query_kernel_path(gp)
+    ws = gp.workspace()
+    rng = np.random.default_rng(1234)
+    Vs = [torch.from_numpy(rng.standard_normal(w.V.shape).astype(np.float32)).cuda() for _ in range(4)]
+    X = torch.from_numpy(w.X0).cuda()
+    hv_out = gp.vec()
+    g_out = gp.vec()
+    loss_out = torch.empty((), dtype=torch.float64, device="cuda")
+    params = nadmm.make_params(w.max_newton, w.max_cg, w.max_ls, 0.0, 0.0, w.beta, w.gamma)
+    Xs = gp.vec()
+    only = set(x for x in args.only.split(",") if x)
+    do = lambda k: not only or k in only
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step():
+        t = {}
+        if do("hv"):
+            e0, e1 = ev(), ev()
+            e0.record()
+            for i in range(HV_PER_STEP):
+                nadmm.nadmm_hessvec(gp, X, Vs[i & 3], out=hv_out, ws=ws)
+            e1.record()
+            t["hv"] = (e0, e1)
+        if do("lg"):
+            e0, e1 = ev(), ev()
+            e0.record()
+            for i in range(LG_PER_STEP):
+                nadmm.nadmm_loss_grad(gp, X, loss_out=loss_out, grad_out=g_out, ws=ws)
+            e1.record()
+            t["lg"] = (e0, e1)
+        if do("solve"):
+            Xs.copy_(X)
+            e0, e1 = ev(), ev()
+            e0.record()
+            nadmm.nadmm_local_newton(gp, Xs, params, want_stats=False, ws=ws)
+            e1.record()
+            t["solve"] = (e0, e1)
+        return t
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    recs = [step() for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms = {k: [r[k][0].elapsed_time(r[k][1]) for r in recs] for k in recs[0]} if recs else {}
+    tot = {k: sum(v) for k, v in ms.items()}
+
+    n, p, NC = w.n, w.p, w.C - 1
+    d = p * NC
+    bytes_hv = 4.0 * n * p + 3 * 4.0 * d
+    bytes_lg = 4.0 * n * p + 4.0 * n + 4 * 4.0 * d
+    extra = {"kernel_path": {1: "two-pass fp32 vector kernels", 2: "fused single pass"}[path]}
+    value = None
+    roof = None
+    if "hv" in tot:
+        per_hv_s = tot["hv"] / 1e3 / (HV_PER_STEP * args.steps)
+        value = 1.0 / per_hv_s
+        ach = bytes_hv / per_hv_s / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                "traffic": None, "kernel": "Hessian-vector product (all kernels of one nadmm_hessvec call)",
+                "us_per_launch": per_hv_s * 1e6, "algorithmic_bytes": bytes_hv}
+        extra["hv_us"] = per_hv_s * 1e6
+    if "lg" in tot:
+        per_lg_s = tot["lg"] / 1e3 / (LG_PER_STEP * args.steps)
+        extra["loss_grad_per_s"] = 1.0 / per_lg_s
+        extra["loss_grad_us"] = per_lg_s * 1e6
+        extra["loss_grad_hbm_frac"] = bytes_lg / per_lg_s / 1e9 / HBM_PEAK_GBS
+    if "solve" in tot:
+        per_solve_s = tot["solve"] / 1e3 / args.steps
+        passes = w.max_newton * (w.max_cg + 2)
+        extra["local_solve_seconds"] = per_solve_s
+        extra["local_solve_passes_over_A"] = passes
+        extra["local_solve_hbm_frac"] = passes * 4.0 * n * p / per_solve_s / 1e9 / HBM_PEAK_GBS
+
+    out = {
+        "metric": "Hv products/s (n=60k,p=784,C=10); loss+grad/s and local Newton-CG solve seconds in extra",
+        "value": value, "unit": "Hv/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / max(args.steps, 1), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n": n, "p": p, "C": w.C, "hv_per_step": HV_PER_STEP,
+                   "loss_grad_per_step": LG_PER_STEP, "newton_iters": w.max_newton, "cg_iters": w.max_cg,
+                   "loss_scale": "1/n", "lambda": w.lam, "rho": w.rho},
+        "roofline": roof, "extra": extra,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

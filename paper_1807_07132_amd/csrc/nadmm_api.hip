@@ -1,0 +1,538 @@
+// C ABI of libnadmm: argument validation, workspace layout and the host-side
+// drivers that enqueue the kernels of one local x-update (Algorithm 3 with the CG
+// of Section 2.4 and the line search of Algorithm 2).  Nothing here synchronises
+// the device except the final copy of the statistics.
+#include <cmath>
+#include <cstring>
+#include <string>
+
+#include "nadmm_internal.h"
+
+namespace nadmm {
+namespace {
+
+int g_path = 0;
+thread_local std::string g_last_hip_error;
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Layout {
+  Shape s;
+  size_t state, g, pdir, r, dvec, q;
+  size_t drows, pcache, zx, zp;
+  size_t partial, loss_part, lpart, pack;
+  size_t total;
+  int gen_row_blocks, gen_slabs, gen_chunks, gen_rpc;
+  int fused_parts;
+  bool fused_ok;
+};
+
+int validate_problem(const nadmm_problem* p, bool need_labels) {
+  if (p == nullptr || p->d_A == nullptr) return NADMM_EINVAL;
+  if (p->n < 1 || p->p < 1 || p->C < 2 || p->lda < (int64_t)p->p) return NADMM_EINVAL;
+  if (!(p->rho > 0.f) || !(p->lambda >= 0.f) || !std::isfinite(p->rho) || !std::isfinite(p->lambda)) return NADMM_EINVAL;
+  if (!std::isfinite(p->loss_scale)) return NADMM_EINVAL;
+  if (need_labels && p->d_labels == nullptr) return NADMM_EINVAL;
+  if (p->C - 1 > NADMM_MAX_FREE_CLASSES) return NADMM_EUNSUPPORTED;
+  if ((int64_t)p->p * (p->C - 1) > ((int64_t)1 << 28)) return NADMM_EUNSUPPORTED;
+  if (p->n > ((int64_t)1 << 40)) return NADMM_EUNSUPPORTED;
+  return NADMM_OK;
+}
+
+void make_layout(const nadmm_problem* p, Layout* L) {
+  Shape s;
+  s.n = p->n;
+  s.p = p->p;
+  s.NC = p->C - 1;
+  s.d = (int64_t)s.p * s.NC;
+  L->s = s;
+  L->gen_row_blocks = generic_row_blocks(s.n);
+  generic_col_grid(s, &L->gen_slabs, &L->gen_chunks, &L->gen_rpc);
+  L->fused_ok = fused_supported(s, p->lda);
+  L->fused_parts = L->fused_ok ? fused_num_partials(s) : 0;
+  const size_t vec = align256((size_t)s.d * sizeof(float));
+  const size_t rows = align256((size_t)s.n * s.NC * sizeof(float));
+  size_t off = 0;
+  L->state = off; off += align256(sizeof(DevState));
+  L->g = off; off += vec;
+  L->pdir = off; off += vec;
+  L->r = off; off += vec;
+  L->dvec = off; off += vec;
+  L->q = off; off += vec;
+  L->drows = off; off += rows;
+  L->pcache = off; off += rows;
+  L->zx = off; off += rows;
+  L->zp = off; off += rows;
+  const int parts = L->gen_chunks > L->fused_parts ? L->gen_chunks : L->fused_parts;
+  L->partial = off; off += align256((size_t)parts * s.d * sizeof(float));
+  const int lblocks = L->gen_row_blocks > L->fused_parts ? L->gen_row_blocks : L->fused_parts;
+  L->loss_part = off; off += align256((size_t)lblocks * sizeof(double));
+  L->lpart = off; off += align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
+  L->pack = off; off += align256(L->fused_ok ? fused_pack_bytes(s) : 0);
+  L->total = off;
+}
+
+int check_ws(const Layout& L, void* ws, size_t bytes) {
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || bytes < L.total) return NADMM_EWORKSPACE;
+  return NADMM_OK;
+}
+
+template <typename T>
+inline T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error = hipGetErrorString(e);
+  return NADMM_EHIP;
+}
+
+#define NADMM_HIP(expr)                          \
+  do {                                           \
+    hipError_t e_ = (expr);                      \
+    if (e_ != hipSuccess) return hip_fail(e_);   \
+  } while (0)
+
+// 1 = two-pass vector kernels, 2 = fused single pass
+int choose_path(const Layout& L, int* path) {
+  if (g_path == 1) { *path = 1; return NADMM_OK; }
+  if (g_path == 2) {
+    if (!L.fused_ok) return NADMM_EUNSUPPORTED;
+    *path = 2;
+    return NADMM_OK;
+  }
+  *path = L.fused_ok ? 2 : 1;
+  return NADMM_OK;
+}
+
+// One sweep over A: rows pass, and (if with_cols) partial sums of A^T rows_out.
+int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArgs ra, bool with_cols,
+          int* nparts, hipStream_t st) {
+  ra.A = prob->d_A;
+  ra.n = prob->n;
+  ra.p = prob->p;
+  ra.lda = prob->lda;
+  ra.NC = L.s.NC;
+  if (path == 2) {
+    NADMM_HIP(launch_fused(ra, with_cols ? at<float>(ws, L.partial) : nullptr, at<void>(ws, L.pack), st));
+    *nparts = L.fused_parts;
+    return NADMM_OK;
+  }
+  NADMM_HIP(launch_generic_rows(ra, st));
+  if (with_cols) {
+    ColArgs ca;
+    ca.A = prob->d_A;
+    ca.n = prob->n;
+    ca.p = prob->p;
+    ca.lda = prob->lda;
+    ca.NC = L.s.NC;
+    ca.rows_in = ra.rows_out;
+    ca.partial = at<float>(ws, L.partial);
+    ca.rows_per_chunk = L.gen_rpc;
+    ca.flag = ra.flag;
+    NADMM_HIP(launch_generic_cols(ca, L.gen_slabs, L.gen_chunks, st));
+    *nparts = L.gen_chunks;
+  }
+  return NADMM_OK;
+}
+
+RowArgs blank_rows() {
+  RowArgs ra;
+  std::memset(&ra, 0, sizeof(ra));
+  return ra;
+}
+
+int reduce(const nadmm_problem* prob, const Layout& L, void* ws, int nparts, int kind, const float* XorV,
+           float* out, const int32_t* flag, hipStream_t st) {
+  ReduceArgs r;
+  std::memset(&r, 0, sizeof(r));
+  r.partial = at<float>(ws, L.partial);
+  r.nparts = nparts;
+  r.d = L.s.d;
+  r.scale = prob->loss_scale;
+  r.kind = kind;
+  r.V = XorV;
+  r.X = XorV;
+  r.z = prob->d_z;
+  r.y = prob->d_y;
+  r.lambda = prob->lambda;
+  r.rho = prob->rho;
+  r.out = out;
+  r.flag = flag;
+  NADMM_HIP(launch_reduce_out(r, st));
+  return NADMM_OK;
+}
+
+// q = H(X) v.  With X == NULL the probabilities cached in the workspace are used.
+int hv_apply(const nadmm_problem* prob, const Layout& L, int path, void* ws, const float* X, bool write_pcache,
+             const float* v, float* out, const int32_t* flag, hipStream_t st) {
+  RowArgs ra = blank_rows();
+  ra.kind = kRowsHv;
+  ra.B0 = X;
+  ra.B1 = v;
+  ra.Pin = X ? nullptr : at<float>(ws, L.pcache);
+  ra.Pout = (X && write_pcache) ? at<float>(ws, L.pcache) : nullptr;
+  ra.rows_out = at<float>(ws, L.drows);
+  ra.flag = flag;
+  int nparts = 0;
+  int rc = sweep(prob, L, path, ws, ra, true, &nparts, st);
+  if (rc != NADMM_OK) return rc;
+  return reduce(prob, L, ws, nparts, 0, v, out, flag, st);
+}
+
+void fill_alphas(float* alphas, int ncand, float gamma) {
+  double a = 1.0;
+  for (int k = 0; k < ncand; ++k) {
+    alphas[k] = (float)a;
+    a *= (double)gamma;
+  }
+}
+
+int validate_ls(float beta, float gamma, int max_ls) {
+  if (!(beta > 0.f && beta < 1.f) || !(gamma > 0.f && gamma < 1.f) || max_ls < 0) return NADMM_EINVAL;
+  if (max_ls > NADMM_MAX_LS) return NADMM_EUNSUPPORTED;
+  return NADMM_OK;
+}
+
+}  // namespace
+}  // namespace nadmm
+
+using namespace nadmm;
+
+extern "C" {
+
+int nadmm_version(void) { return 100; }
+
+const char* nadmm_status_string(int code) {
+  switch (code) {
+    case NADMM_OK: return "ok";
+    case NADMM_EINVAL: return "invalid argument";
+    case NADMM_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case NADMM_EUNSUPPORTED: return "shape or parameter outside the supported range";
+    case NADMM_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* nadmm_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
+int nadmm_set_kernel_path(int path) {
+  if (path < 0 || path > 2) return NADMM_EINVAL;
+  const int prev = g_path;
+  g_path = path;
+  return prev;
+}
+
+int nadmm_query_kernel_path(const nadmm_problem* prob) {
+  int rc = validate_problem(prob, false);
+  if (rc != NADMM_OK) return rc;
+  Layout L;
+  make_layout(prob, &L);
+  int path = 0;
+  rc = choose_path(L, &path);
+  return rc != NADMM_OK ? rc : path;
+}
+
+size_t nadmm_workspace_bytes(const nadmm_problem* prob, const nadmm_params* params) {
+  (void)params;
+  if (validate_problem(prob, false) != NADMM_OK) return 0;
+  Layout L;
+  make_layout(prob, &L);
+  return L.total;
+}
+
+int nadmm_loss_grad(const nadmm_problem* prob, const float* d_X, double* d_loss, float* d_grad, void* d_ws,
+                    size_t ws_bytes, void* stream) {
+  int rc = validate_problem(prob, true);
+  if (rc != NADMM_OK) return rc;
+  if (d_X == nullptr || d_loss == nullptr) return NADMM_EINVAL;
+  Layout L;
+  make_layout(prob, &L);
+  if ((rc = check_ws(L, d_ws, ws_bytes)) != NADMM_OK) return rc;
+  int path = 0;
+  if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+
+  RowArgs ra = blank_rows();
+  ra.kind = d_grad ? kRowsGrad : kRowsLoss;
+  ra.B0 = d_X;
+  ra.labels = prob->d_labels;
+  ra.rows_out = d_grad ? at<float>(d_ws, L.drows) : nullptr;
+  ra.loss_part = at<double>(d_ws, L.loss_part);
+  int nparts = 0;
+  if ((rc = sweep(prob, L, path, d_ws, ra, d_grad != nullptr, &nparts, st)) != NADMM_OK) return rc;
+  if (d_grad && (rc = reduce(prob, L, d_ws, nparts, 1, d_X, d_grad, nullptr, st)) != NADMM_OK) return rc;
+
+  LossFinishArgs lf;
+  lf.loss_part = at<double>(d_ws, L.loss_part);
+  lf.nblocks = path == 2 ? L.fused_parts : L.gen_row_blocks;
+  lf.scale = prob->loss_scale;
+  lf.lambda = prob->lambda;
+  lf.rho = prob->rho;
+  lf.X = d_X;
+  lf.z = prob->d_z;
+  lf.y = prob->d_y;
+  lf.d = L.s.d;
+  lf.loss_out = d_loss;
+  NADMM_HIP(launch_loss_finish(lf, st));
+  return NADMM_OK;
+}
+
+int nadmm_hessvec(const nadmm_problem* prob, const float* d_X, const float* d_V, float* d_HV, void* d_ws,
+                  size_t ws_bytes, void* stream) {
+  int rc = validate_problem(prob, false);
+  if (rc != NADMM_OK) return rc;
+  if (d_X == nullptr || d_V == nullptr || d_HV == nullptr) return NADMM_EINVAL;
+  Layout L;
+  make_layout(prob, &L);
+  if ((rc = check_ws(L, d_ws, ws_bytes)) != NADMM_OK) return rc;
+  int path = 0;
+  if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
+  return hv_apply(prob, L, path, d_ws, d_X, false, d_V, d_HV, nullptr, (hipStream_t)stream);
+}
+
+int nadmm_cg_solve(const nadmm_problem* prob, const float* d_X, const float* d_g, float* d_p, int max_iter,
+                   float tol, int32_t* d_iters, float* d_relres, void* d_ws, size_t ws_bytes, void* stream) {
+  int rc = validate_problem(prob, false);
+  if (rc != NADMM_OK) return rc;
+  if (d_X == nullptr || d_g == nullptr || d_p == nullptr || max_iter < 0 || !(tol >= 0.f)) return NADMM_EINVAL;
+  Layout L;
+  make_layout(prob, &L);
+  if ((rc = check_ws(L, d_ws, ws_bytes)) != NADMM_OK) return rc;
+  int path = 0;
+  if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  DevState* ds = at<DevState>(d_ws, L.state);
+
+  NADMM_HIP(launch_state_init(ds, st));
+  NewtonHeadArgs nh;
+  std::memset(&nh, 0, sizeof(nh));
+  nh.st = ds;
+  nh.g = d_g;
+  nh.pdir = at<float>(d_ws, L.pdir);
+  nh.r = at<float>(d_ws, L.r);
+  nh.dvec = at<float>(d_ws, L.dvec);
+  nh.d = L.s.d;
+  nh.newton_mode = 0;
+  NADMM_HIP(launch_newton_head(nh, st));
+
+  for (int k = 0; k < max_iter; ++k) {
+    rc = hv_apply(prob, L, path, d_ws, k == 0 ? d_X : nullptr, true, at<float>(d_ws, L.dvec), at<float>(d_ws, L.q),
+                  &ds->cg_active, st);
+    if (rc != NADMM_OK) return rc;
+    CgUpdateArgs cu;
+    cu.st = ds;
+    cu.pdir = at<float>(d_ws, L.pdir);
+    cu.r = at<float>(d_ws, L.r);
+    cu.dvec = at<float>(d_ws, L.dvec);
+    cu.q = at<float>(d_ws, L.q);
+    cu.d = L.s.d;
+    cu.tol = tol;
+    NADMM_HIP(launch_cg_update(cu, st));
+  }
+  CgFinishArgs cf;
+  cf.st = ds;
+  cf.pdir = at<float>(d_ws, L.pdir);
+  cf.p_out = d_p;
+  cf.d = L.s.d;
+  cf.iters_out = d_iters;
+  cf.relres_out = d_relres;
+  NADMM_HIP(launch_cg_finish(cf, st));
+  return NADMM_OK;
+}
+
+int nadmm_line_search(const nadmm_problem* prob, const float* d_X, const float* d_p, const float* d_g,
+                      double loss_at_X, float beta, float gamma, int max_ls, float* d_alpha, double* d_loss_new,
+                      int32_t* d_armijo_ok, void* d_ws, size_t ws_bytes, void* stream) {
+  int rc = validate_problem(prob, true);
+  if (rc != NADMM_OK) return rc;
+  if (d_X == nullptr || d_p == nullptr || d_g == nullptr || d_alpha == nullptr) return NADMM_EINVAL;
+  if ((rc = validate_ls(beta, gamma, max_ls)) != NADMM_OK) return rc;
+  Layout L;
+  make_layout(prob, &L);
+  if ((rc = check_ws(L, d_ws, ws_bytes)) != NADMM_OK) return rc;
+  int path = 0;
+  if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  DevState* ds = at<DevState>(d_ws, L.state);
+  NADMM_HIP(launch_state_init(ds, st));
+
+  RowArgs ra = blank_rows();
+  ra.kind = kRowsLogits;
+  ra.B0 = d_X;
+  ra.B1 = d_p;
+  ra.Z0out = at<float>(d_ws, L.zx);
+  ra.Z1out = at<float>(d_ws, L.zp);
+  int nparts = 0;
+  if ((rc = sweep(prob, L, path, d_ws, ra, false, &nparts, st)) != NADMM_OK) return rc;
+
+  const int ncand = max_ls + 2;
+  const bool need_f0 = std::isnan(loss_at_X);
+  LsEvalArgs le;
+  std::memset(&le, 0, sizeof(le));
+  le.Zx = at<float>(d_ws, L.zx);
+  le.Zp = at<float>(d_ws, L.zp);
+  le.labels = prob->d_labels;
+  le.n = prob->n;
+  le.NC = L.s.NC;
+  fill_alphas(le.alphas, ncand, gamma);
+  le.alphas[ncand] = 0.f;
+  le.ncand = ncand + (need_f0 ? 1 : 0);
+  le.lpart = at<double>(d_ws, L.lpart);
+  NADMM_HIP(launch_ls_eval(le, st));
+
+  LsTailArgs lt;
+  std::memset(&lt, 0, sizeof(lt));
+  lt.st = ds;
+  lt.lpart = le.lpart;
+  lt.nblocks = ls_eval_blocks(prob->n);
+  lt.ncand = ncand;
+  lt.zero_slot = need_f0 ? ncand : -1;
+  std::memcpy(lt.alphas, le.alphas, sizeof(lt.alphas));
+  lt.loss_at_X = loss_at_X;
+  lt.use_state_loss = 0;
+  lt.scale = prob->loss_scale;
+  lt.lambda = prob->lambda;
+  lt.rho = prob->rho;
+  lt.beta = beta;
+  lt.X = d_X;
+  lt.z = prob->d_z;
+  lt.y = prob->d_y;
+  lt.pdir = d_p;
+  lt.g = d_g;
+  lt.d = L.s.d;
+  lt.X_apply = nullptr;
+  lt.alpha_out = d_alpha;
+  lt.loss_new_out = d_loss_new;
+  lt.ok_out = d_armijo_ok;
+  lt.iter = -1;
+  NADMM_HIP(launch_ls_tail(lt, st));
+  return NADMM_OK;
+}
+
+int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params* params, nadmm_stats* h_stats,
+                       void* d_ws, size_t ws_bytes, void* stream) {
+  int rc = validate_problem(prob, true);
+  if (rc != NADMM_OK) return rc;
+  if (d_X == nullptr || params == nullptr) return NADMM_EINVAL;
+  if (params->max_newton < 0 || params->max_cg < 0 || !(params->cg_tol >= 0.f) || !(params->grad_tol >= 0.f))
+    return NADMM_EINVAL;
+  if ((rc = validate_ls(params->armijo_beta, params->backtrack_gamma, params->max_ls)) != NADMM_OK) return rc;
+  Layout L;
+  make_layout(prob, &L);
+  if ((rc = check_ws(L, d_ws, ws_bytes)) != NADMM_OK) return rc;
+  int path = 0;
+  if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  DevState* ds = at<DevState>(d_ws, L.state);
+  float* g = at<float>(d_ws, L.g);
+  float* pdir = at<float>(d_ws, L.pdir);
+  float* r = at<float>(d_ws, L.r);
+  float* dvec = at<float>(d_ws, L.dvec);
+  float* q = at<float>(d_ws, L.q);
+
+  NADMM_HIP(launch_state_init(ds, st));
+  const int ncand = params->max_ls + 2;
+
+  for (int t = 0; t < params->max_newton; ++t) {
+    // gradient and objective at X; caches the probabilities and the logits A X
+    RowArgs ra = blank_rows();
+    ra.kind = kRowsGrad;
+    ra.B0 = d_X;
+    ra.labels = prob->d_labels;
+    ra.rows_out = at<float>(d_ws, L.drows);
+    ra.Pout = at<float>(d_ws, L.pcache);
+    ra.Z0out = at<float>(d_ws, L.zx);
+    ra.loss_part = at<double>(d_ws, L.loss_part);
+    ra.flag = &ds->newton_active;
+    int nparts = 0;
+    if ((rc = sweep(prob, L, path, d_ws, ra, true, &nparts, st)) != NADMM_OK) return rc;
+    if ((rc = reduce(prob, L, d_ws, nparts, 1, d_X, g, &ds->newton_active, st)) != NADMM_OK) return rc;
+
+    NewtonHeadArgs nh;
+    std::memset(&nh, 0, sizeof(nh));
+    nh.st = ds;
+    nh.loss_part = at<double>(d_ws, L.loss_part);
+    nh.nblocks = path == 2 ? L.fused_parts : L.gen_row_blocks;
+    nh.scale = prob->loss_scale;
+    nh.lambda = prob->lambda;
+    nh.rho = prob->rho;
+    nh.X = d_X;
+    nh.z = prob->d_z;
+    nh.y = prob->d_y;
+    nh.g = g;
+    nh.pdir = pdir;
+    nh.r = r;
+    nh.dvec = dvec;
+    nh.d = L.s.d;
+    nh.iter = t;
+    nh.grad_tol = params->grad_tol;
+    nh.newton_mode = 1;
+    NADMM_HIP(launch_newton_head(nh, st));
+
+    // CG on H p = -g with the probabilities of this iterate
+    for (int k = 0; k < params->max_cg; ++k) {
+      if ((rc = hv_apply(prob, L, path, d_ws, nullptr, false, dvec, q, &ds->cg_active, st)) != NADMM_OK) return rc;
+      CgUpdateArgs cu;
+      cu.st = ds;
+      cu.pdir = pdir;
+      cu.r = r;
+      cu.dvec = dvec;
+      cu.q = q;
+      cu.d = L.s.d;
+      cu.tol = params->cg_tol;
+      NADMM_HIP(launch_cg_update(cu, st));
+    }
+
+    // Armijo backtracking on Z(alpha) = A X + alpha A p, then X += alpha p
+    RowArgs rz = blank_rows();
+    rz.kind = kRowsLogits;
+    rz.B1 = pdir;
+    rz.Z1out = at<float>(d_ws, L.zp);
+    rz.flag = &ds->newton_active;
+    if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st)) != NADMM_OK) return rc;
+
+    LsEvalArgs le;
+    std::memset(&le, 0, sizeof(le));
+    le.Zx = at<float>(d_ws, L.zx);
+    le.Zp = at<float>(d_ws, L.zp);
+    le.labels = prob->d_labels;
+    le.n = prob->n;
+    le.NC = L.s.NC;
+    fill_alphas(le.alphas, ncand, params->backtrack_gamma);
+    le.ncand = ncand;
+    le.lpart = at<double>(d_ws, L.lpart);
+    le.flag = &ds->newton_active;
+    NADMM_HIP(launch_ls_eval(le, st));
+
+    LsTailArgs lt;
+    std::memset(&lt, 0, sizeof(lt));
+    lt.st = ds;
+    lt.lpart = le.lpart;
+    lt.nblocks = ls_eval_blocks(prob->n);
+    lt.ncand = ncand;
+    lt.zero_slot = -1;
+    std::memcpy(lt.alphas, le.alphas, sizeof(lt.alphas));
+    lt.use_state_loss = 1;
+    lt.scale = prob->loss_scale;
+    lt.lambda = prob->lambda;
+    lt.rho = prob->rho;
+    lt.beta = params->armijo_beta;
+    lt.X = d_X;
+    lt.z = prob->d_z;
+    lt.y = prob->d_y;
+    lt.pdir = pdir;
+    lt.g = g;
+    lt.d = L.s.d;
+    lt.X_apply = d_X;
+    lt.iter = t;
+    lt.flag = &ds->newton_active;
+    NADMM_HIP(launch_ls_tail(lt, st));
+  }
+
+  if (h_stats != nullptr) {
+    NADMM_HIP(hipMemcpyAsync(h_stats, &ds->stats, sizeof(nadmm_stats), hipMemcpyDeviceToHost, st));
+    NADMM_HIP(hipStreamSynchronize(st));
+  }
+  return NADMM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,205 @@
+// Internal declarations shared by the translation units of libnadmm (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "nadmm.h"
+
+namespace nadmm {
+
+constexpr int kWave = 64;
+constexpr int kMaxCand = NADMM_MAX_LS + 2;  // candidate step sizes 1, gamma, ..., gamma^(max_ls+1)
+constexpr int kCandSlots = kMaxCand + 1;    // + one slot for alpha = 0 (objective at X itself)
+
+// Device-resident scalars of the Newton / CG / line-search drivers.  Lives at
+// the start of the workspace; written only by single-workgroup tail kernels.
+struct DevState {
+  double loss;      // Fhat at the current X
+  double gg;        // ||g||^2 at the current X
+  double rr;        // CG: ||r||^2 of the current residual
+  double gg_cg;     // CG: ||g||^2 of the right-hand side
+  double loss_new;  // line search: Fhat(X + alpha p)
+  double loss_initial;
+  float alpha;      // line search result
+  int32_t newton_active;
+  int32_t cg_active;
+  int32_t cg_iters;
+  int32_t armijo_ok;
+  int32_t ls_evals;
+  int32_t pad_[2];
+  nadmm_stats stats;  // copied to the host at the end of nadmm_local_newton
+};
+
+// Row-pass (forward) work description, shared by the two-pass and the fused kernels.
+//   kind 0  Hessian-vector rows:  D = P o W - P o rowsum(P o W)         (Section 2.6)
+//   kind 1  gradient rows:        R = P - Y, row losses                  (Sections 2.1, 2.2)
+//   kind 2  row losses only
+//   kind 3  logits only:          Z0 = A B0 and / or Z1 = A B1
+enum RowKind { kRowsHv = 0, kRowsGrad = 1, kRowsLoss = 2, kRowsLogits = 3 };
+
+struct RowArgs {
+  const float* A;
+  int64_t n;
+  int32_t p;
+  int64_t lda;
+  int32_t NC;          // C-1
+  const float* B0;     // p x NC, operand of the logits Z = A B0 (X); NULL if P comes from Pin
+  const float* B1;     // p x NC, operand of the directional logits W = A B1 (V or p); may be NULL
+  const int32_t* labels;
+  const float* Pin;    // n x NC cached probabilities (kind 0 with B0 == NULL)
+  float* rows_out;     // n x NC: D (kind 0) or R (kind 1); may be NULL
+  float* Pout;         // n x NC: probabilities, optional
+  float* Z0out;        // n x NC: logits A B0, optional
+  float* Z1out;        // n x NC: logits A B1, optional
+  double* loss_part;   // per-workgroup partial sums of row losses (kinds 1, 2)
+  int32_t kind;
+  const int32_t* flag; // if non-NULL and *flag == 0 the kernel does nothing
+};
+
+// Column-pass (transpose product) description: partial[k] = (rows of chunk k of A)^T rows_in
+struct ColArgs {
+  const float* A;
+  int64_t n;
+  int32_t p;
+  int64_t lda;
+  int32_t NC;
+  const float* rows_in;  // n x NC
+  float* partial;        // nparts x (p*NC)
+  int32_t rows_per_chunk;
+  const int32_t* flag;
+};
+
+struct Shape {
+  int64_t n;
+  int32_t p;
+  int32_t NC;
+  int64_t d;  // p * NC
+};
+
+// ---- launchers, generic two-pass path (nadmm_generic.hip) ----
+int generic_row_blocks(int64_t n);
+void generic_col_grid(const Shape& s, int* nslabs, int* nchunks, int* rows_per_chunk);
+hipError_t launch_generic_rows(const RowArgs& a, hipStream_t st);
+hipError_t launch_generic_cols(const ColArgs& a, int nslabs, int nchunks, hipStream_t st);
+
+// ---- vector / tail kernels (nadmm_vec.hip) ----
+struct ReduceArgs {
+  const float* partial;
+  int32_t nparts;
+  int64_t d;
+  float scale;            // s
+  int32_t kind;           // 0: out = s*sum + (lambda+rho) V ; 1: out = s*sum + lambda X + rho (X - z) + y
+  const float* V;         // kind 0
+  const float* X;         // kind 1
+  const float* z;
+  const float* y;
+  float lambda, rho;
+  float* out;
+  const int32_t* flag;
+};
+hipError_t launch_reduce_out(const ReduceArgs& a, hipStream_t st);
+
+struct LossFinishArgs {
+  const double* loss_part;
+  int32_t nblocks;
+  float scale, lambda, rho;
+  const float* X;
+  const float* z;
+  const float* y;
+  int64_t d;
+  double* loss_out;  // device scalar
+};
+hipError_t launch_loss_finish(const LossFinishArgs& a, hipStream_t st);
+
+struct NewtonHeadArgs {
+  DevState* st;
+  const double* loss_part;
+  int32_t nblocks;
+  float scale, lambda, rho;
+  const float* X;
+  const float* z;
+  const float* y;
+  const float* g;
+  float* pdir;
+  float* r;
+  float* dvec;
+  int64_t d;
+  int32_t iter;        // Newton iteration index
+  float grad_tol;
+  int32_t newton_mode; // 1: part of Algorithm 3 (stats, grad_tol); 0: plain CG initialisation from g
+};
+hipError_t launch_newton_head(const NewtonHeadArgs& a, hipStream_t st);
+
+struct CgUpdateArgs {
+  DevState* st;
+  float* pdir;
+  float* r;
+  float* dvec;
+  const float* q;
+  int64_t d;
+  float tol;
+};
+hipError_t launch_cg_update(const CgUpdateArgs& a, hipStream_t st);
+
+struct CgFinishArgs {
+  const DevState* st;
+  const float* pdir;
+  float* p_out;
+  int64_t d;
+  int32_t* iters_out;
+  float* relres_out;
+};
+hipError_t launch_cg_finish(const CgFinishArgs& a, hipStream_t st);
+
+struct LsEvalArgs {
+  const float* Zx;
+  const float* Zp;
+  const int32_t* labels;
+  int64_t n;
+  int32_t NC;
+  int32_t ncand;           // number of step sizes in alphas[] that are evaluated
+  float alphas[kCandSlots];
+  double* lpart;           // nblocks x kCandSlots
+  const int32_t* flag;
+};
+int ls_eval_blocks(int64_t n);
+hipError_t launch_ls_eval(const LsEvalArgs& a, hipStream_t st);
+
+struct LsTailArgs {
+  DevState* st;
+  const double* lpart;
+  int32_t nblocks;
+  int32_t ncand;          // candidates of Algorithm 2 (max_ls + 2)
+  int32_t zero_slot;      // index in alphas[] of alpha = 0, or -1 if loss_at_X is given
+  float alphas[kCandSlots];
+  double loss_at_X;       // used if zero_slot < 0 and !use_state_loss
+  int32_t use_state_loss; // take Fhat(X) from st->loss
+  float scale, lambda, rho, beta;
+  const float* X;
+  const float* z;
+  const float* y;
+  const float* pdir;
+  const float* g;
+  int64_t d;
+  float* X_apply;         // if non-NULL: X_apply += alpha * pdir (Newton update)
+  float* alpha_out;       // optional device outputs of the stand-alone call
+  double* loss_new_out;
+  int32_t* ok_out;
+  int32_t iter;           // Newton iteration index or -1
+  const int32_t* flag;
+};
+hipError_t launch_ls_tail(const LsTailArgs& a, hipStream_t st);
+
+hipError_t launch_state_init(DevState* st, hipStream_t stream);
+
+// ---- fused single-pass path (nadmm_fused.hip) ----
+bool fused_supported(const Shape& s, int64_t lda);
+int fused_num_partials(const Shape& s);
+size_t fused_pack_bytes(const Shape& s);
+// Runs the rows pass and the transpose product in one sweep over A; leaves
+// per-workgroup partial sums of A^T rows in `partial` (fused_num_partials() x d).
+hipError_t launch_fused(const RowArgs& a, float* partial, void* pack_ws, hipStream_t st);
+
+}  // namespace nadmm

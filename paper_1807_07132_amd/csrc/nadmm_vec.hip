@@ -1,0 +1,376 @@
+// Small kernels on vectors of length d = p (C-1) and on the n x (C-1) logit caches:
+// fixed-order reduction of per-workgroup partials, the scalar work of CG
+// (Section 2.4), the Armijo backtracking of Algorithm 2 on cached logits, and
+// the bookkeeping of Algorithm 3.  All scalars stay in device memory; the
+// single-workgroup "tail" kernels sum in a fixed order, so results are
+// reproducible bit for bit.
+#include "nadmm_internal.h"
+
+namespace nadmm {
+namespace {
+
+constexpr int kTail = 1024;
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;
+}
+
+// Sum over the whole workgroup; result valid in every thread.
+__device__ __forceinline__ double block_sum(double v, double* sm /* >= 17 doubles */) {
+  v = wave_sum(v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if (lane == 0) sm[wave] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < nw; ++w) t += sm[w];
+    sm[16] = t;
+  }
+  __syncthreads();
+  return sm[16];
+}
+
+__global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
+  if (a.flag != nullptr && *a.flag == 0) return;
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= a.d) return;
+  float sum = 0.f;
+  const float* __restrict__ pp = a.partial + e;
+  for (int k = 0; k < a.nparts; ++k) sum += pp[(size_t)k * a.d];
+  float out = a.scale * sum;
+  if (a.kind == 0) {
+    out = fmaf(a.lambda + a.rho, a.V[e], out);
+  } else {
+    const float x = a.X[e];
+    const float zz = a.z ? a.z[e] : 0.f;
+    const float yy = a.y ? a.y[e] : 0.f;
+    out += a.lambda * x + a.rho * (x - zz) + yy;
+  }
+  a.out[e] = out;
+}
+
+// lambda/2 ||X||^2 + rho/2 ||X - z + y/rho||^2, summed over the workgroup
+__device__ __forceinline__ double penalty_block(const float* X, const float* z, const float* y, int64_t d,
+                                                float lambda, float rho, double* sm) {
+  double acc = 0.0;
+  const double inv_rho = 1.0 / (double)rho;
+  for (int64_t e = threadIdx.x; e < d; e += blockDim.x) {
+    const double x = X[e];
+    const double u = x - (z ? (double)z[e] : 0.0) + (y ? (double)y[e] : 0.0) * inv_rho;
+    acc += 0.5 * (double)lambda * x * x + 0.5 * (double)rho * u * u;
+  }
+  return block_sum(acc, sm);
+}
+
+__device__ __forceinline__ double partial_sum_block(const double* part, int n, double* sm) {
+  double acc = 0.0;
+  for (int k = threadIdx.x; k < n; k += blockDim.x) acc += part[k];
+  return block_sum(acc, sm);
+}
+
+__global__ __launch_bounds__(kTail) void loss_finish_kernel(const LossFinishArgs a) {
+  __shared__ double sm[17];
+  const double data = partial_sum_block(a.loss_part, a.nblocks, sm);
+  const double pen = penalty_block(a.X, a.z, a.y, a.d, a.lambda, a.rho, sm);
+  if (threadIdx.x == 0) *a.loss_out = (double)a.scale * data + pen;
+}
+
+__global__ void state_init_kernel(DevState* st) {
+  // one thread; zero the scalars and the statistics, raise the activity flags
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  st->loss = 0.0; st->gg = 0.0; st->rr = 0.0; st->gg_cg = 0.0; st->loss_new = 0.0; st->loss_initial = 0.0;
+  st->alpha = 0.f;
+  st->newton_active = 1; st->cg_active = 1; st->cg_iters = 0; st->armijo_ok = 1; st->ls_evals = 0;
+  nadmm_stats* s = &st->stats;
+  s->newton_iters = 0; s->cg_iters_total = 0; s->ls_evals_total = 0; s->armijo_failed = 0;
+  s->loss_initial = 0.0; s->loss_final = 0.0; s->grad_norm_final = 0.0;
+  for (int i = 0; i < NADMM_TRACE_LEN; ++i) {
+    s->alpha[i] = 0.f; s->cg_iters[i] = 0; s->loss[i] = 0.0; s->grad_norm[i] = 0.0;
+  }
+}
+
+// After a gradient evaluation: finish the objective, ||g||, the stopping test of
+// Algorithm 3, and start CG from p = 0, r = d = -g.
+__global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs a) {
+  __shared__ double sm[17];
+  DevState* st = a.st;
+  if (a.newton_mode && st->newton_active == 0) return;
+
+  double gg = 0.0;
+  for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) {
+    const float g = a.g[e];
+    gg += (double)g * (double)g;
+    a.pdir[e] = 0.f;
+    a.r[e] = -g;
+    a.dvec[e] = -g;
+  }
+  gg = block_sum(gg, sm);
+
+  double loss = 0.0;
+  if (a.newton_mode) {
+    const double data = partial_sum_block(a.loss_part, a.nblocks, sm);
+    const double pen = penalty_block(a.X, a.z, a.y, a.d, a.lambda, a.rho, sm);
+    loss = (double)a.scale * data + pen;
+  }
+  if (threadIdx.x == 0) {
+    st->gg = gg;
+    st->rr = gg;
+    st->gg_cg = gg;
+    st->cg_iters = 0;
+    st->cg_active = gg > 0.0 ? 1 : 0;
+    if (a.newton_mode) {
+      const double gn = sqrt(gg);
+      st->loss = loss;
+      nadmm_stats* s = &st->stats;
+      if (a.iter == 0) { st->loss_initial = loss; s->loss_initial = loss; s->loss_final = loss; }
+      s->grad_norm_final = gn;
+      if (gn < (double)a.grad_tol || !(gg > 0.0)) {
+        st->newton_active = 0;
+        st->cg_active = 0;
+      } else if (a.iter < NADMM_TRACE_LEN) {
+        s->loss[a.iter] = loss;
+        s->grad_norm[a.iter] = gn;
+      }
+    }
+  }
+}
+
+// One CG iteration's vector work, given q = H d:  a = rr / <d,q>; p += a d; r -= a q;
+// stop on ||r|| <= tol ||g|| (eq. inexact); else d = r + (rr'/rr) d.
+__global__ __launch_bounds__(kTail) void cg_update_kernel(const CgUpdateArgs a) {
+  __shared__ double sm[17];
+  DevState* st = a.st;
+  if (st->cg_active == 0) return;
+  double dq = 0.0;
+  for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) dq += (double)a.dvec[e] * (double)a.q[e];
+  dq = block_sum(dq, sm);
+  const double rr = st->rr;
+  if (!(dq > 0.0) || !isfinite(dq)) {  // no positive curvature: keep the current iterate
+    __syncthreads();
+    if (threadIdx.x == 0) st->cg_active = 0;
+    return;
+  }
+  const float al = (float)(rr / dq);
+  double rr_new = 0.0;
+  for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) {
+    a.pdir[e] = fmaf(al, a.dvec[e], a.pdir[e]);
+    const float rn = fmaf(-al, a.q[e], a.r[e]);
+    a.r[e] = rn;
+    rr_new += (double)rn * (double)rn;
+  }
+  rr_new = block_sum(rr_new, sm);
+  const bool stop = sqrt(rr_new) <= (double)a.tol * sqrt(st->gg_cg);
+  if (!stop) {
+    const float be = (float)(rr_new / rr);
+    for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) a.dvec[e] = fmaf(be, a.dvec[e], a.r[e]);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    st->rr = rr_new;
+    st->cg_iters += 1;
+    if (stop) st->cg_active = 0;
+  }
+}
+
+__global__ __launch_bounds__(256) void cg_finish_kernel(const CgFinishArgs a) {
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < a.d; e += (int64_t)gridDim.x * blockDim.x)
+    a.p_out[e] = a.pdir[e];
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (a.iters_out) *a.iters_out = a.st->cg_iters;
+    if (a.relres_out) *a.relres_out = a.st->gg_cg > 0.0 ? (float)sqrt(a.st->rr / a.st->gg_cg) : 0.f;
+  }
+}
+
+// Row losses at Z = Zx + alpha Zp for a group of candidate step sizes (Sections 2.1, 2.2).
+template <int NCP>
+__global__ __launch_bounds__(256) void ls_eval_kernel(const LsEvalArgs a) {
+  if (a.flag != nullptr && *a.flag == 0) return;
+  __shared__ double sm[17];
+  const int NC = a.NC;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int k0 = 0; k0 < a.ncand; k0 += 4) {
+    float al[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) al[kk] = (k0 + kk < a.ncand) ? a.alphas[k0 + kk] : 0.f;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < a.n; i += stride) {
+      float zx[NCP], zp[NCP];
+      const size_t ro = (size_t)i * NC;
+#pragma unroll
+      for (int c = 0; c < NCP; ++c) {
+        zx[c] = (c < NC) ? a.Zx[ro + c] : 0.f;
+        zp[c] = (c < NC) ? a.Zp[ro + c] : 0.f;
+      }
+      const int b = a.labels[i];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        float M = 0.f, zb = 0.f;
+        float zz[NCP];
+#pragma unroll
+        for (int c = 0; c < NCP; ++c) {
+          zz[c] = fmaf(al[kk], zp[c], zx[c]);
+          if (c < NC) {
+            M = fmaxf(M, zz[c]);
+            if (c == b) zb = zz[c];
+          }
+        }
+        float alpha = expf(-M);
+#pragma unroll
+        for (int c = 0; c < NCP; ++c)
+          if (c < NC) alpha += expf(zz[c] - M);
+        acc[kk] += (double)M + (double)logf(alpha) - (double)zb;
+      }
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const double t = block_sum(acc[kk], sm);
+      if (threadIdx.x == 0 && k0 + kk < a.ncand) a.lpart[(size_t)blockIdx.x * kCandSlots + k0 + kk] = t;
+    }
+  }
+}
+
+// Algorithm 2 on the candidate objective values; optionally applies X += alpha p.
+__global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a) {
+  __shared__ double sm[17];
+  __shared__ double cand[kCandSlots];
+  __shared__ float s_alpha;
+  DevState* st = a.st;
+  if (a.flag != nullptr && *a.flag == 0) return;
+
+  const int nslots = a.ncand + (a.zero_slot >= 0 ? 1 : 0);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int k = wave; k < nslots; k += kTail / 64) {
+    double acc = 0.0;
+    for (int b = lane; b < a.nblocks; b += 64) acc += a.lpart[(size_t)b * kCandSlots + k];
+    acc = wave_sum(acc);
+    if (lane == 0) cand[k] = acc;
+  }
+  // penalty along the line: q0 + alpha q1 + alpha^2 q2, and the slope <p, g>
+  double q0 = 0.0, q1 = 0.0, q2 = 0.0, sl = 0.0;
+  const double inv_rho = 1.0 / (double)a.rho;
+  for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) {
+    const double x = a.X[e];
+    const double u = x - (a.z ? (double)a.z[e] : 0.0) + (a.y ? (double)a.y[e] : 0.0) * inv_rho;
+    const double pv = a.pdir[e];
+    q0 += 0.5 * (double)a.lambda * x * x + 0.5 * (double)a.rho * u * u;
+    q1 += (double)a.lambda * x * pv + (double)a.rho * u * pv;
+    q2 += 0.5 * ((double)a.lambda + (double)a.rho) * pv * pv;
+    sl += pv * (double)a.g[e];
+  }
+  q0 = block_sum(q0, sm);
+  q1 = block_sum(q1, sm);
+  q2 = block_sum(q2, sm);
+  sl = block_sum(sl, sm);
+
+  if (threadIdx.x == 0) {
+    double f0;
+    if (a.zero_slot >= 0) f0 = (double)a.scale * cand[a.zero_slot] + q0;
+    else if (a.use_state_loss) f0 = st->loss;
+    else f0 = a.loss_at_X;
+    int k = 0, ok = 1;
+    double fk = 0.0;
+    for (;;) {
+      const double al = (double)a.alphas[k];
+      fk = (double)a.scale * cand[k] + q0 + al * q1 + al * al * q2;
+      if (!(fk > f0 + al * (double)a.beta * sl)) break;       // Armijo holds (eq. armijo)
+      if (k + 1 >= a.ncand) { ok = 0; break; }                 // the i > i_max break of Algorithm 2
+      ++k;
+    }
+    const float alpha = a.alphas[k];
+    s_alpha = alpha;
+    st->alpha = alpha;
+    st->loss_new = fk;
+    st->armijo_ok = ok;
+    st->ls_evals = k + 1;
+    if (a.alpha_out) *a.alpha_out = alpha;
+    if (a.loss_new_out) *a.loss_new_out = fk;
+    if (a.ok_out) *a.ok_out = ok;
+    if (a.iter >= 0) {
+      nadmm_stats* s = &st->stats;
+      s->newton_iters += 1;
+      s->cg_iters_total += st->cg_iters;
+      s->ls_evals_total += k + 1;
+      s->armijo_failed += ok ? 0 : 1;
+      s->loss_final = fk;
+      if (a.iter < NADMM_TRACE_LEN) { s->alpha[a.iter] = alpha; s->cg_iters[a.iter] = st->cg_iters; }
+    }
+  }
+  __syncthreads();
+  if (a.X_apply != nullptr) {
+    const float alpha = s_alpha;
+    for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) a.X_apply[e] = fmaf(alpha, a.pdir[e], a.X_apply[e]);
+  }
+}
+
+template <typename F>
+hipError_t dispatch_ncp(int NC, F&& f) {
+  if (NC <= 1) return f(std::integral_constant<int, 1>());
+  if (NC <= 2) return f(std::integral_constant<int, 2>());
+  if (NC <= 4) return f(std::integral_constant<int, 4>());
+  if (NC <= 9) return f(std::integral_constant<int, 9>());
+  if (NC <= 16) return f(std::integral_constant<int, 16>());
+  if (NC <= 19) return f(std::integral_constant<int, 19>());
+  return f(std::integral_constant<int, 32>());
+}
+
+}  // namespace
+
+hipError_t launch_reduce_out(const ReduceArgs& a, hipStream_t st) {
+  const int blocks = (int)((a.d + 255) / 256);
+  hipLaunchKernelGGL(reduce_out_kernel, dim3(blocks), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_loss_finish(const LossFinishArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kTail), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_state_init(DevState* s, hipStream_t st) {
+  hipLaunchKernelGGL(state_init_kernel, dim3(1), dim3(64), 0, st, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_newton_head(const NewtonHeadArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(newton_head_kernel, dim3(1), dim3(kTail), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_cg_update(const CgUpdateArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(cg_update_kernel, dim3(1), dim3(kTail), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_cg_finish(const CgFinishArgs& a, hipStream_t st) {
+  int blocks = (int)((a.d + 255) / 256);
+  if (blocks > 256) blocks = 256;
+  hipLaunchKernelGGL(cg_finish_kernel, dim3(blocks), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+int ls_eval_blocks(int64_t n) {
+  int64_t b = (n + 255) / 256;
+  if (b > 1024) b = 1024;
+  if (b < 1) b = 1;
+  return (int)b;
+}
+
+hipError_t launch_ls_eval(const LsEvalArgs& a, hipStream_t st) {
+  const int blocks = ls_eval_blocks(a.n);
+  return dispatch_ncp(a.NC, [&](auto ncp) {
+    constexpr int NCP = decltype(ncp)::value;
+    hipLaunchKernelGGL(ls_eval_kernel<NCP>, dim3(blocks), dim3(256), 0, st, a);
+    return hipGetLastError();
+  });
+}
+
+hipError_t launch_ls_tail(const LsTailArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(ls_tail_kernel, dim3(1), dim3(kTail), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace nadmm

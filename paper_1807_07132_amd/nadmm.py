@@ -1,0 +1,235 @@
+"""ctypes binding of libnadmm (include/nadmm.h).  Argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the computation
+runs in the library's HIP kernels.  There is no CPU fallback: if the shared
+library has not been built (python -m paper_1807_07132_amd.build) loading fails
+with an error.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnadmm.so")
+
+NADMM_OK, NADMM_EINVAL, NADMM_EWORKSPACE, NADMM_EUNSUPPORTED, NADMM_EHIP = 0, -1, -2, -3, -4
+NADMM_TRACE_LEN = 64
+NADMM_MAX_LS = 62
+NADMM_MAX_FREE_CLASSES = 32
+
+
+class nadmm_problem(C.Structure):
+    _fields_ = [
+        ("d_A", C.c_void_p), ("n", C.c_int64), ("p", C.c_int32), ("lda", C.c_int64),
+        ("d_labels", C.c_void_p), ("C", C.c_int32), ("loss_scale", C.c_float),
+        ("lambda_", C.c_float), ("rho", C.c_float), ("d_z", C.c_void_p), ("d_y", C.c_void_p),
+    ]
+
+
+class nadmm_params(C.Structure):
+    _fields_ = [
+        ("max_newton", C.c_int32), ("max_cg", C.c_int32), ("max_ls", C.c_int32),
+        ("cg_tol", C.c_float), ("grad_tol", C.c_float), ("armijo_beta", C.c_float),
+        ("backtrack_gamma", C.c_float),
+    ]
+
+
+class nadmm_stats(C.Structure):
+    _fields_ = [
+        ("newton_iters", C.c_int32), ("cg_iters_total", C.c_int32), ("ls_evals_total", C.c_int32),
+        ("armijo_failed", C.c_int32), ("loss_initial", C.c_double), ("loss_final", C.c_double),
+        ("grad_norm_final", C.c_double), ("alpha", C.c_float * NADMM_TRACE_LEN),
+        ("cg_iters", C.c_int32 * NADMM_TRACE_LEN), ("loss", C.c_double * NADMM_TRACE_LEN),
+        ("grad_norm", C.c_double * NADMM_TRACE_LEN),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_1807_07132_amd.build`; "
+                           "there is no fallback path")
+    L = C.CDLL(LIB_PATH)
+    PP, PR, PS = C.POINTER(nadmm_problem), C.POINTER(nadmm_params), C.POINTER(nadmm_stats)
+    vp, sz = C.c_void_p, C.c_size_t
+    L.nadmm_version.restype = C.c_int
+    L.nadmm_status_string.restype = C.c_char_p
+    L.nadmm_status_string.argtypes = [C.c_int]
+    L.nadmm_last_hip_error.restype = C.c_char_p
+    L.nadmm_workspace_bytes.restype = sz
+    L.nadmm_workspace_bytes.argtypes = [PP, PR]
+    L.nadmm_loss_grad.argtypes = [PP, vp, vp, vp, vp, sz, vp]
+    L.nadmm_hessvec.argtypes = [PP, vp, vp, vp, vp, sz, vp]
+    L.nadmm_cg_solve.argtypes = [PP, vp, vp, vp, C.c_int, C.c_float, vp, vp, vp, sz, vp]
+    L.nadmm_line_search.argtypes = [PP, vp, vp, vp, C.c_double, C.c_float, C.c_float, C.c_int, vp, vp, vp, vp, sz, vp]
+    L.nadmm_local_newton.argtypes = [PP, vp, PR, PS, vp, sz, vp]
+    L.nadmm_set_kernel_path.argtypes = [C.c_int]
+    L.nadmm_query_kernel_path.argtypes = [PP]
+    for f in (L.nadmm_loss_grad, L.nadmm_hessvec, L.nadmm_cg_solve, L.nadmm_line_search, L.nadmm_local_newton,
+              L.nadmm_set_kernel_path, L.nadmm_query_kernel_path):
+        f.restype = C.c_int
+    _lib = L
+    return L
+
+
+class NadmmError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        msg = lib().nadmm_status_string(code).decode()
+        if code == NADMM_EHIP:
+            msg += ": " + lib().nadmm_last_hip_error().decode()
+        super().__init__(f"nadmm status {code}: {msg}")
+
+
+def _check(code):
+    if code != NADMM_OK:
+        raise NadmmError(code)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+class Problem:
+    """Device-resident data share.  Keeps the tensors alive and builds the C view."""
+
+    def __init__(self, A: torch.Tensor, labels: Optional[torch.Tensor], C_: int, loss_scale: float, lam: float,
+                 rho: float, z: Optional[torch.Tensor] = None, y: Optional[torch.Tensor] = None):
+        assert A.is_cuda and A.dtype == torch.float32 and A.dim() == 2 and A.stride(1) == 1
+        self.A, self.labels, self.C, self.z, self.y = A, labels, int(C_), z, y
+        self.n, self.p = A.shape
+        self.NC = self.C - 1
+        self.loss_scale, self.lam, self.rho = float(loss_scale), float(lam), float(rho)
+        if labels is not None:
+            assert labels.is_cuda and labels.dtype == torch.int32 and labels.numel() == self.n
+        for t in (z, y):
+            if t is not None:
+                assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == self.p * self.NC
+        self.c = nadmm_problem(A.data_ptr(), self.n, self.p, A.stride(0),
+                               labels.data_ptr() if labels is not None else None, self.C,
+                               self.loss_scale, self.lam, self.rho,
+                               z.data_ptr() if z is not None else None, y.data_ptr() if y is not None else None)
+        self._ws = None
+
+    @classmethod
+    def from_workload(cls, w, device="cuda"):
+        dev = torch.device(device)
+        to = lambda a: torch.from_numpy(a).to(dev)
+        return cls(to(w.A), to(w.b), w.C, w.s, w.lam, w.rho, to(w.z), to(w.y))
+
+    def workspace(self) -> torch.Tensor:
+        if self._ws is None:
+            self._ws = alloc_workspace(self)
+        return self._ws
+
+    def vec(self) -> torch.Tensor:
+        return torch.empty((self.p, self.NC), dtype=torch.float32, device=self.A.device)
+
+
+def make_params(max_newton=10, max_cg=10, max_ls=10, cg_tol=0.0, grad_tol=0.0, armijo_beta=1e-4,
+                backtrack_gamma=0.5) -> nadmm_params:
+    return nadmm_params(max_newton, max_cg, max_ls, cg_tol, grad_tol, armijo_beta, backtrack_gamma)
+
+
+def nadmm_version() -> int:
+    return lib().nadmm_version()
+
+
+def nadmm_workspace_bytes(prob: Problem, params: Optional[nadmm_params] = None) -> int:
+    return int(lib().nadmm_workspace_bytes(C.byref(prob.c), C.byref(params) if params is not None else None))
+
+
+def alloc_workspace(prob: Problem) -> torch.Tensor:
+    nbytes = nadmm_workspace_bytes(prob)
+    if nbytes == 0:
+        raise NadmmError(NADMM_EINVAL)
+    return torch.empty(nbytes, dtype=torch.uint8, device=prob.A.device)
+
+
+def nadmm_set_kernel_path(path: int) -> int:
+    rc = lib().nadmm_set_kernel_path(int(path))
+    if rc < 0:
+        raise NadmmError(rc)
+    return rc
+
+
+def nadmm_query_kernel_path(prob: Problem) -> int:
+    rc = lib().nadmm_query_kernel_path(C.byref(prob.c))
+    if rc < 0:
+        raise NadmmError(rc)
+    return rc
+
+
+def nadmm_loss_grad(prob: Problem, X: torch.Tensor, want_grad=True, loss_out=None, grad_out=None, ws=None,
+                    stream=None):
+    """Returns (loss, grad): loss a float64 device scalar tensor, grad p x (C-1) float32 or None."""
+    ws = prob.workspace() if ws is None else ws
+    loss = torch.empty((), dtype=torch.float64, device=X.device) if loss_out is None else loss_out
+    grad = (prob.vec() if grad_out is None else grad_out) if want_grad else None
+    _check(lib().nadmm_loss_grad(C.byref(prob.c), _ptr(X), _ptr(loss), _ptr(grad), _ptr(ws), ws.numel(),
+                                 _stream(stream)))
+    return loss, grad
+
+
+def nadmm_hessvec(prob: Problem, X: torch.Tensor, V: torch.Tensor, out=None, ws=None, stream=None):
+    ws = prob.workspace() if ws is None else ws
+    out = prob.vec() if out is None else out
+    _check(lib().nadmm_hessvec(C.byref(prob.c), _ptr(X), _ptr(V), _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def nadmm_cg_solve(prob: Problem, X: torch.Tensor, g: torch.Tensor, max_iter: int, tol: float, out=None, ws=None,
+                   stream=None):
+    """Returns (p, iters, relres) as device tensors."""
+    ws = prob.workspace() if ws is None else ws
+    out = prob.vec() if out is None else out
+    iters = torch.empty((), dtype=torch.int32, device=X.device)
+    relres = torch.empty((), dtype=torch.float32, device=X.device)
+    _check(lib().nadmm_cg_solve(C.byref(prob.c), _ptr(X), _ptr(g), _ptr(out), int(max_iter), float(tol),
+                                _ptr(iters), _ptr(relres), _ptr(ws), ws.numel(), _stream(stream)))
+    return out, iters, relres
+
+
+def nadmm_line_search(prob: Problem, X: torch.Tensor, p: torch.Tensor, g: torch.Tensor, loss_at_X=math.nan,
+                      beta=1e-4, gamma=0.5, max_ls=10, ws=None, stream=None):
+    """Returns (alpha, loss_new, armijo_ok) as device scalar tensors."""
+    ws = prob.workspace() if ws is None else ws
+    alpha = torch.empty((), dtype=torch.float32, device=X.device)
+    loss_new = torch.empty((), dtype=torch.float64, device=X.device)
+    ok = torch.empty((), dtype=torch.int32, device=X.device)
+    _check(lib().nadmm_line_search(C.byref(prob.c), _ptr(X), _ptr(p), _ptr(g), float(loss_at_X), float(beta),
+                                   float(gamma), int(max_ls), _ptr(alpha), _ptr(loss_new), _ptr(ok), _ptr(ws),
+                                   ws.numel(), _stream(stream)))
+    return alpha, loss_new, ok
+
+
+def nadmm_local_newton(prob: Problem, X: torch.Tensor, params: nadmm_params, want_stats=True, ws=None, stream=None):
+    """Updates X in place.  Returns a dict of statistics (synchronises) or None."""
+    ws = prob.workspace() if ws is None else ws
+    st = nadmm_stats() if want_stats else None
+    _check(lib().nadmm_local_newton(C.byref(prob.c), _ptr(X), C.byref(params), C.byref(st) if st is not None else None,
+                                    _ptr(ws), ws.numel(), _stream(stream)))
+    if st is None:
+        return None
+    k = min(st.newton_iters, NADMM_TRACE_LEN)
+    return dict(newton_iters=st.newton_iters, cg_iters_total=st.cg_iters_total, ls_evals_total=st.ls_evals_total,
+                armijo_failed=st.armijo_failed, loss_initial=st.loss_initial, loss_final=st.loss_final,
+                grad_norm_final=st.grad_norm_final, alpha=list(st.alpha[:k]), cg_iters=list(st.cg_iters[:k]),
+                loss=list(st.loss[:k]), grad_norm=list(st.grad_norm[:k]))

@@ -1,0 +1,137 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared
+symbol, its structs match the header as a C compiler lays them out, and
+argument validation returns the documented codes before anything is enqueued
+(no GPU is touched)."""
+import ctypes as C
+import os
+import re
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "nadmm.h")
+
+from paper_1807_07132_amd import nadmm  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(nadmm.LIB_PATH):
+        from paper_1807_07132_amd import build
+        build.build(verbose=False)
+    return nadmm.lib()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nadmm_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"nadmm_loss_grad", "nadmm_hessvec", "nadmm_cg_solve", "nadmm_line_search", "nadmm_local_newton",
+            "nadmm_workspace_bytes"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert lib.nadmm_version() >= 100
+    assert lib.nadmm_status_string(0) == b"ok"
+    assert b"workspace" in lib.nadmm_status_string(nadmm.NADMM_EWORKSPACE)
+
+
+def test_struct_layout_matches_the_header(tmp_path):
+    src = tmp_path / "sizes.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "nadmm.h"\n'
+        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(nadmm_problem), sizeof(nadmm_params),"
+        " sizeof(nadmm_stats), offsetof(nadmm_problem, d_labels), offsetof(nadmm_problem, d_z),"
+        " offsetof(nadmm_stats, loss_initial), offsetof(nadmm_stats, grad_norm));return 0;}\n")
+    exe = tmp_path / "sizes"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", f"-I{os.path.join(ROOT, 'include')}", str(src), "-o", str(exe)])
+    got = [int(v) for v in subprocess.check_output([str(exe)]).split()]
+    want = [C.sizeof(nadmm.nadmm_problem), C.sizeof(nadmm.nadmm_params), C.sizeof(nadmm.nadmm_stats),
+            nadmm.nadmm_problem.d_labels.offset, nadmm.nadmm_problem.d_z.offset,
+            nadmm.nadmm_stats.loss_initial.offset, nadmm.nadmm_stats.grad_norm.offset]
+    assert got == want
+
+
+def fake_problem(n=1000, p=20, Cc=3, lda=None, rho=1.0, lam=1e-3, A=0x1000, labels=0x2000):
+    return nadmm.nadmm_problem(A, n, p, p if lda is None else lda, labels, Cc, 1.0, lam, rho, None, None)
+
+
+def test_workspace_bytes(lib):
+    small = lib.nadmm_workspace_bytes(C.byref(fake_problem()), None)
+    big = lib.nadmm_workspace_bytes(C.byref(fake_problem(n=60000, p=784, Cc=10)), None)
+    assert small > 0 and big > small and small % 256 == 0
+    assert big >= 4 * 60000 * 9 * 4                      # four n x (C-1) row buffers
+    assert big < 1 << 30
+    assert lib.nadmm_workspace_bytes(C.byref(fake_problem(n=0)), None) == 0
+    assert lib.nadmm_workspace_bytes(None, None) == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n=0), nadmm.NADMM_EINVAL),
+    (dict(p=0), nadmm.NADMM_EINVAL),
+    (dict(Cc=1), nadmm.NADMM_EINVAL),
+    (dict(lda=19), nadmm.NADMM_EINVAL),
+    (dict(rho=0.0), nadmm.NADMM_EINVAL),
+    (dict(rho=float("nan")), nadmm.NADMM_EINVAL),
+    (dict(lam=-1.0), nadmm.NADMM_EINVAL),
+    (dict(A=None), nadmm.NADMM_EINVAL),
+    (dict(Cc=40), nadmm.NADMM_EUNSUPPORTED),
+])
+def test_invalid_problems_are_rejected_on_the_host(lib, kw, code):
+    prob = fake_problem(**kw)
+    fake = C.c_void_p(0x3000)
+    assert lib.nadmm_hessvec(C.byref(prob), fake, fake, fake, fake, 1 << 30, None) == code
+    assert lib.nadmm_loss_grad(C.byref(prob), fake, fake, fake, fake, 1 << 30, None) == code
+    params = nadmm.make_params()
+    assert lib.nadmm_local_newton(C.byref(prob), fake, C.byref(params), None, fake, 1 << 30, None) == code
+
+
+def test_null_arguments_and_workspace_errors(lib):
+    prob = fake_problem()
+    fake = C.c_void_p(0x3000)
+    need = lib.nadmm_workspace_bytes(C.byref(prob), None)
+    assert lib.nadmm_hessvec(C.byref(prob), None, fake, fake, fake, need, None) == nadmm.NADMM_EINVAL
+    assert lib.nadmm_hessvec(C.byref(prob), fake, fake, None, fake, need, None) == nadmm.NADMM_EINVAL
+    assert lib.nadmm_hessvec(C.byref(prob), fake, fake, fake, None, need, None) == nadmm.NADMM_EWORKSPACE
+    assert lib.nadmm_hessvec(C.byref(prob), fake, fake, fake, fake, need - 1, None) == nadmm.NADMM_EWORKSPACE
+    assert lib.nadmm_hessvec(C.byref(prob), fake, fake, fake, C.c_void_p(0x3010), need, None) == nadmm.NADMM_EWORKSPACE
+    # labels are required by the objective but not by the Hessian-vector product
+    nolab = fake_problem(labels=None)
+    assert lib.nadmm_loss_grad(C.byref(nolab), fake, fake, fake, fake, need, None) == nadmm.NADMM_EINVAL
+    assert lib.nadmm_cg_solve(C.byref(prob), fake, fake, fake, -1, 0.0, None, None, fake, need, None) == nadmm.NADMM_EINVAL
+    assert lib.nadmm_cg_solve(C.byref(prob), fake, None, fake, 5, 0.0, None, None, fake, need, None) == nadmm.NADMM_EINVAL
+
+
+@pytest.mark.parametrize("beta,gamma,max_ls,code", [
+    (0.0, 0.5, 10, nadmm.NADMM_EINVAL), (1.0, 0.5, 10, nadmm.NADMM_EINVAL),
+    (1e-4, 0.0, 10, nadmm.NADMM_EINVAL), (1e-4, 1.0, 10, nadmm.NADMM_EINVAL),
+    (1e-4, 0.5, -1, nadmm.NADMM_EINVAL), (1e-4, 0.5, 63, nadmm.NADMM_EUNSUPPORTED),
+])
+def test_line_search_parameters_are_validated(lib, beta, gamma, max_ls, code):
+    prob = fake_problem()
+    fake = C.c_void_p(0x3000)
+    need = lib.nadmm_workspace_bytes(C.byref(prob), None)
+    rc = lib.nadmm_line_search(C.byref(prob), fake, fake, fake, 1.0, beta, gamma, max_ls, fake, fake, fake, fake, need, None)
+    assert rc == code
+    params = nadmm.make_params(armijo_beta=beta, backtrack_gamma=gamma, max_ls=max_ls)
+    assert lib.nadmm_local_newton(C.byref(prob), fake, C.byref(params), None, fake, need, None) == code
+
+
+def test_kernel_path_switch(lib):
+    prev = lib.nadmm_set_kernel_path(1)
+    assert prev in (0, 1, 2)
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem())) == 1
+    assert lib.nadmm_set_kernel_path(7) == nadmm.NADMM_EINVAL
+    lib.nadmm_set_kernel_path(prev)
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem())) in (1, 2)
+
+
+def test_product_path_does_not_import_the_oracle():
+    code = ("import sys; sys.path.insert(0, %r); import paper_1807_07132_amd.nadmm, paper_1807_07132_amd.workloads;"
+            "assert not any(m == 'oracle' or m.startswith('oracle.') for m in sys.modules)" % ROOT)
+    subprocess.check_call([sys.executable, "-c", code])
