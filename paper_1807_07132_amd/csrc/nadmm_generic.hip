@@ -122,7 +122,10 @@ __global__ __launch_bounds__(kRowsPerBlock) void rows_kernel(const RowArgs a) {
     if (valid) {
 #pragma unroll
       for (int c = 0; c < NCP; ++c)
-        if (c < NC) a.rows_out[ro + c] = P[c] * (w[c] - t);
+        if (c < NC) {
+          a.rows_out[ro + c] = P[c] * (w[c] - t);
+          if (a.Pout) a.Pout[ro + c] = P[c];
+        }
     }
     return;
   }
