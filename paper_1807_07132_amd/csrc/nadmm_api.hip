@@ -20,7 +20,7 @@ struct Layout {
   Shape s;
   size_t state, g, pdir, r, dvec, q;
   size_t drows, pcache, zx, zp;
-  size_t partial, loss_part, lpart, pack;
+  size_t partial, loss_part, lpart;
   size_t total;
   int gen_row_blocks, gen_slabs, gen_chunks, gen_rpc;
   int fused_parts;
@@ -48,7 +48,7 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   L->s = s;
   L->gen_row_blocks = generic_row_blocks(s.n);
   generic_col_grid(s, &L->gen_slabs, &L->gen_chunks, &L->gen_rpc);
-  L->fused_ok = fused_supported(s, p->lda);
+  L->fused_ok = fused_supported(s, p->lda, p->d_A);
   L->fused_parts = L->fused_ok ? fused_num_partials(s) : 0;
   const size_t vec = align256((size_t)s.d * sizeof(float));
   const size_t rows = align256((size_t)s.n * s.NC * sizeof(float));
@@ -68,7 +68,6 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   const int lblocks = L->gen_row_blocks > L->fused_parts ? L->gen_row_blocks : L->fused_parts;
   L->loss_part = off; off += align256((size_t)lblocks * sizeof(double));
   L->lpart = off; off += align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
-  L->pack = off; off += align256(L->fused_ok ? fused_pack_bytes(s) : 0);
   L->total = off;
 }
 
@@ -112,7 +111,7 @@ int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArg
   ra.lda = prob->lda;
   ra.NC = L.s.NC;
   if (path == 2) {
-    NADMM_HIP(launch_fused(ra, with_cols ? at<float>(ws, L.partial) : nullptr, at<void>(ws, L.pack), st));
+    NADMM_HIP(launch_fused(ra, with_cols ? at<float>(ws, L.partial) : nullptr, L.fused_parts, st));
     *nparts = L.fused_parts;
     return NADMM_OK;
   }

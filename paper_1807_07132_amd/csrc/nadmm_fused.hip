@@ -1,11 +1,449 @@
-// Fused single-pass path (placeholder until the MFMA kernel lands).
+// Fused single-pass kernel for gfx950: rows pass and transpose product in one
+// sweep over A (Section 2.6: H v = A^T D with D formed row by row from W = A V
+// and the probabilities P; same structure for the gradient A^T (P - Y)).
+//
+// One persistent workgroup of 8 waves per compute unit owns a contiguous range
+// of rows and walks it in tiles of 32 rows.  Columns are cut into steps of 32;
+// wave w owns steps w, w+8, ... in BOTH contractions:
+//   phase 1  Z|W tile (32 x 2*16) = A_tile [X|V]   -- A straight from global
+//            loads in MFMA A-operand layout, [X|V] resident in registers;
+//   rows     cross-wave sum of the K-split partials through LDS, then the
+//            log-sum-exp / probabilities / D per row with 16-lane DPP reductions;
+//   phase 2  out^T (16 x cols) += D^T A_tile        -- A re-read from a
+//            wave-private, bank-swizzled LDS copy written in phase 1.
+// A is read from HBM exactly once; the p x (C-1) accumulators stay in registers
+// for the whole row range and are written once as a per-workgroup partial.
+//
+// Arithmetic: every fp32 operand is split into bf16 high and low parts
+// (x = hi + lo + O(2^-18 |x|)), and each product uses the three MFMA terms
+// hi*hi + hi*lo + lo*hi with fp32 accumulation (v_mfma_f32_16x16x32_bf16).
 #include "nadmm_internal.h"
 
 namespace nadmm {
+namespace {
 
-bool fused_supported(const Shape&, int64_t) { return false; }
-int fused_num_partials(const Shape&) { return 0; }
-size_t fused_pack_bytes(const Shape&) { return 0; }
-hipError_t launch_fused(const RowArgs&, float*, void*, hipStream_t) { return hipErrorNotSupported; }
+constexpr int kThreads = 512;
+constexpr int kWaves = 8;
+constexpr int kTileRows = 32;
+constexpr int kStepCols = 32;
+constexpr int kMaxSteps = 30;                 // LDS: steps * 4 KB + 36 KB <= 160 KB
+constexpr int kStepBytes = 4096;              // hi plane 2 KB + lo plane 2 KB
+constexpr int kPartBytes = kWaves * 4 * 64 * 16;
+constexpr int kSumBytes = 4 * 64 * 16;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+struct FusedArgs {
+  RowArgs r;
+  float* partial;     // gridDim.x x (p*NC) or NULL (no transpose product)
+  int32_t steps;      // ceil(p / 32)
+  int32_t rows_per_wg;
+};
+
+__device__ __forceinline__ unsigned pack2(float a, float b) {  // round-to-nearest-even, a in the low half
+  bf16x2 v = {(__bf16)a, (__bf16)b};
+  return __builtin_bit_cast(unsigned, v);
+}
+__device__ __forceinline__ float low_as_float(unsigned h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ float high_as_float(unsigned h) { return __uint_as_float(h & 0xffff0000u); }
+
+// 8 floats -> packed bf16 high parts and packed bf16 residuals
+__device__ __forceinline__ void split8(const float (&a)[8], u32x4& hi, u32x4& lo) {
+  unsigned h[4], l[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    h[k] = pack2(a[2 * k], a[2 * k + 1]);
+    l[k] = pack2(a[2 * k] - low_as_float(h[k]), a[2 * k + 1] - high_as_float(h[k]));
+  }
+  hi = u32x4{h[0], h[1], h[2], h[3]};
+  lo = u32x4{l[0], l[1], l[2], l[3]};
+}
+
+__device__ __forceinline__ f32x4 mfma(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+// c += (ahi + alo) (bhi + blo) without the lo*lo term
+__device__ __forceinline__ f32x4 mfma3(u32x4 ahi, u32x4 alo, u32x4 bhi, u32x4 blo, f32x4 c) {
+  c = mfma(alo, bhi, c);
+  c = mfma(ahi, blo, c);
+  return mfma(ahi, bhi, c);
+}
+
+template <int N>
+__device__ __forceinline__ float row_ror(float v) {  // rotate within each group of 16 lanes
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += row_ror<8>(v);
+  v += row_ror<4>(v);
+  v += row_ror<2>(v);
+  v += row_ror<1>(v);
+  return v;
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, row_ror<8>(v));
+  v = fmaxf(v, row_ror<4>(v));
+  v = fmaxf(v, row_ror<2>(v));
+  v = fmaxf(v, row_ror<1>(v));
+  return v;
+}
+
+// LDS offset (bytes, within one 2 KB plane of a step) of column q (0..31), 16-byte chunk ck (0..3)
+__device__ __forceinline__ int cm_offset(int q, int ck) {
+  const int qs = q ^ ((q >> 3) & 1);
+  const int g = (qs >> 1) & 3;
+  return qs * 64 + ((ck ^ g) << 4);
+}
+
+template <int SPW, int KIND, bool HAS0, bool HAS1>
+__global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
+  const RowArgs& a = fa.r;
+  if (a.flag != nullptr && *a.flag == 0) return;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int steps = fa.steps;
+  char* cm = lds;                               // steps x 4 KB, step s owned by wave s % 8
+  char* part = lds + (size_t)steps * kStepBytes;  // [wave][quad][lane] x 16 B
+  char* sums = part + kPartBytes;               // [quad][lane] x 16 B
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m = lane & 15;   // phase 1: row within the row block; rows stage / phase 2: class or column
+  const int kg = lane >> 4;  // k-group of the MFMA operands
+  const int NC = a.NC;
+  const int p = a.p;
+  constexpr bool has0 = HAS0;
+  constexpr bool has1 = HAS1;
+  constexpr bool with_cols = KIND == kRowsHv || KIND == kRowsGrad;
+  const bool cv = m < NC;  // this lane's class is a real one
+
+  // ---- [X|V] operands of this wave's steps, split and packed once ----
+  u32x4 bx_hi[SPW], bx_lo[SPW], bv_hi[SPW], bv_lo[SPW];
+#pragma unroll
+  for (int i = 0; i < SPW; ++i) {
+    const int s = wave + kWaves * i;
+    float x[8], v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int j = kStepCols * s + 8 * kg + e;
+      const bool ok = s < steps && j < p && cv;
+      x[e] = (ok && has0) ? a.B0[(size_t)j * NC + m] : 0.f;
+      v[e] = (ok && has1) ? a.B1[(size_t)j * NC + m] : 0.f;
+    }
+    split8(x, bx_hi[i], bx_lo[i]);
+    split8(v, bv_hi[i], bv_lo[i]);
+  }
+
+  f32x4 acc2[SPW][2];
+#pragma unroll
+  for (int i = 0; i < SPW; ++i) {
+    acc2[i][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+    acc2[i][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  double loss_acc = 0.0;
+
+  const int64_t r_begin = (int64_t)blockIdx.x * fa.rows_per_wg;
+  int64_t r_end = r_begin + fa.rows_per_wg;
+  if (r_end > a.n) r_end = a.n;
+
+  // ---- prefetch registers: [step][row block][half of the 8 columns] ----
+  float4 pf[SPW][2][2];
+  auto load_step = [&](int i, int64_t row0) {
+    const int s = wave + kWaves * i;
+    if (s >= steps) return;
+    const int col = kStepCols * s + 8 * kg;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      const int64_t row = row0 + m + 16 * rb;
+      const float* src = a.A + row * a.lda + col;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+        const int c0 = col + 4 * h;
+        if (row < r_end) {
+          if (c0 + 4 <= p) {
+            val = *reinterpret_cast<const float4*>(src + 4 * h);
+          } else if (c0 < p) {
+            val.x = src[4 * h];
+            if (c0 + 1 < p) val.y = src[4 * h + 1];
+            if (c0 + 2 < p) val.z = src[4 * h + 2];
+          }
+        }
+        pf[i][rb][h] = val;
+      }
+    }
+  };
+
+#pragma unroll
+  for (int i = 0; i < SPW; ++i) load_step(i, r_begin);
+
+  for (int64_t row0 = r_begin; row0 < r_end; row0 += kTileRows) {
+    // rows of this lane in the rows stage: e < 4 -> row0 + 4 kg + e, e >= 4 -> row0 + 16 + 4 kg + (e - 4)
+    auto row_of = [&](int e) -> int64_t { return row0 + 4 * kg + (e & 3) + ((e >> 2) << 4); };
+    float aux[8];  // cached probabilities (Hessian-vector rows without X) or labels (gradient / loss rows)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int64_t rr = row_of(e);
+      aux[e] = 0.f;
+      if (KIND == kRowsHv && !has0) {
+        if (rr < r_end && cv) aux[e] = a.Pin[(size_t)rr * NC + m];
+      } else if (KIND == kRowsGrad || KIND == kRowsLoss) {
+        aux[e] = __int_as_float(rr < r_end ? a.labels[rr] : -1);
+      }
+    }
+
+    // ---------------- phase 1 ----------------
+    f32x4 accZ[2], accW[2];
+    accZ[0] = accZ[1] = accW[0] = accW[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const bool more = row0 + kTileRows < r_end;
+#pragma unroll
+    for (int i = 0; i < SPW; ++i) {
+      const int s = wave + kWaves * i;
+      if (s < steps) {
+        u32x4 ahi[2], alo[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+          const float av[8] = {pf[i][rb][0].x, pf[i][rb][0].y, pf[i][rb][0].z, pf[i][rb][0].w,
+                               pf[i][rb][1].x, pf[i][rb][1].y, pf[i][rb][1].z, pf[i][rb][1].w};
+          split8(av, ahi[rb], alo[rb]);
+          if (has0) accZ[rb] = mfma3(ahi[rb], alo[rb], bx_hi[i], bx_lo[i], accZ[rb]);
+          if (has1) accW[rb] = mfma3(ahi[rb], alo[rb], bv_hi[i], bv_lo[i], accW[rb]);
+        }
+        if (more) load_step(i, row0 + kTileRows);  // registers are free again: prefetch the next tile
+        if (with_cols) {
+          // transposed copy for phase 2: pair (row m, row m+16) of one column per 32-bit word
+          char* base = cm + (size_t)s * kStepBytes;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            const unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
+            const unsigned hp = __builtin_amdgcn_perm(ahi[1][c >> 1], ahi[0][c >> 1], sel);
+            const unsigned lp = __builtin_amdgcn_perm(alo[1][c >> 1], alo[0][c >> 1], sel);
+            const int off = cm_offset(8 * kg + c, m >> 2) + ((m & 3) << 2);
+            *reinterpret_cast<unsigned*>(base + off) = hp;
+            *reinterpret_cast<unsigned*>(base + 2048 + off) = lp;
+          }
+        }
+      }
+    }
+    // K-split partials of this wave
+    {
+      f32x4* pw = reinterpret_cast<f32x4*>(part) + (wave * 4) * 64 + lane;
+      pw[0 * 64] = accZ[0];
+      pw[1 * 64] = accZ[1];
+      pw[2 * 64] = accW[0];
+      pw[3 * 64] = accW[1];
+    }
+    __syncthreads();
+    if (wave < 4) {
+      const f32x4* pr = reinterpret_cast<const f32x4*>(part) + wave * 64 + lane;
+      f32x4 t = pr[0];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) t += pr[(w * 4) * 64];
+      reinterpret_cast<f32x4*>(sums)[wave * 64 + lane] = t;
+    }
+    __syncthreads();
+    float zz[8], ww[8];
+    {
+      const f32x4* sr = reinterpret_cast<const f32x4*>(sums) + lane;
+      const f32x4 z0 = sr[0], z1 = sr[64], w0 = sr[128], w1 = sr[192];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        zz[e] = z0[e];
+        zz[4 + e] = z1[e];
+        ww[e] = w0[e];
+        ww[4 + e] = w1[e];
+      }
+    }
+
+    // ---------------- rows stage (every wave, redundantly) ----------------
+    if (KIND == kRowsLogits) {
+      if (wave == 0 && cv) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int64_t rr = row_of(e);
+          if (rr < r_end) {
+            if (has0 && a.Z0out) a.Z0out[(size_t)rr * NC + m] = zz[e];
+            if (has1 && a.Z1out) a.Z1out[(size_t)rr * NC + m] = ww[e];
+          }
+        }
+      }
+      continue;
+    }
+    float dd[8];  // this lane's entries of D (kind 0) or P - Y (kind 1)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int64_t rr = row_of(e);
+      const bool rv = rr < r_end;
+      float P, M = 0.f, alpha = 1.f;
+      if (has0) {
+        const float z = cv ? zz[e] : 0.f;
+        M = row16_max(z);                    // max{0, Z_1..Z_{C-1}}: padded lanes supply the 0
+        const float E = cv ? expf(z - M) : 0.f;
+        alpha = row16_sum(E) + expf(-M);
+        P = E / alpha;
+      } else {
+        P = aux[e];
+      }
+      if (KIND == kRowsHv) {
+        const float t = row16_sum(P * ww[e]);
+        dd[e] = P * (ww[e] - t);
+      } else {
+        const bool mine = cv && m == __float_as_int(aux[e]);
+        dd[e] = P - (mine ? 1.f : 0.f);
+        const float zb = row16_sum(mine ? zz[e] : 0.f);
+        if (wave == 0 && m == 0 && rv) loss_acc += (double)M + (double)logf(alpha) - (double)zb;
+      }
+      if (wave == 0 && cv && rv) {
+        if (a.Pout) a.Pout[(size_t)rr * NC + m] = P;
+        if (has0 && a.Z0out) a.Z0out[(size_t)rr * NC + m] = zz[e];
+      }
+    }
+    if (!with_cols) continue;
+
+    // ---------------- phase 2 ----------------
+    u32x4 dhi, dlo;
+    {
+      unsigned h[4], l[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {  // k-slot pair (2e, 2e+1) = (row 4kg+e, row 16+4kg+e)
+        h[e] = pack2(dd[e], dd[4 + e]);
+        l[e] = pack2(dd[e] - low_as_float(h[e]), dd[4 + e] - high_as_float(h[e]));
+      }
+      dhi = u32x4{h[0], h[1], h[2], h[3]};
+      dlo = u32x4{l[0], l[1], l[2], l[3]};
+    }
+#pragma unroll
+    for (int i = 0; i < SPW; ++i) {
+      const int s = wave + kWaves * i;
+      if (s < steps) {
+        const char* base = cm + (size_t)s * kStepBytes;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int off = cm_offset(16 * h + m, kg);
+          const u32x4 thi = *reinterpret_cast<const u32x4*>(base + off);
+          const u32x4 tlo = *reinterpret_cast<const u32x4*>(base + 2048 + off);
+          acc2[i][h] = mfma3(dhi, dlo, thi, tlo, acc2[i][h]);
+        }
+      }
+    }
+  }
+
+  // ---- epilogue: per-workgroup partial of A^T rows, and the partial loss ----
+  if (with_cols) {
+    float* out = fa.partial + (size_t)blockIdx.x * ((size_t)p * NC);
+#pragma unroll
+    for (int i = 0; i < SPW; ++i) {
+      const int s = wave + kWaves * i;
+      if (s < steps) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int j = kStepCols * s + 16 * h + m;
+          if (j < p) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int c = 4 * kg + e;
+              if (c < NC) out[(size_t)j * NC + c] = acc2[i][h][e];
+            }
+          }
+        }
+      }
+    }
+  }
+  if (a.loss_part != nullptr && wave == 0) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) loss_acc += __shfl_down(loss_acc, off, 64);
+    if (lane == 0) a.loss_part[blockIdx.x] = loss_acc;
+  }
+}
+
+int num_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      cus = v;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+int steps_of(int p) { return (p + kStepCols - 1) / kStepCols; }
+
+template <int SPW, int KIND, bool HAS0, bool HAS1>
+hipError_t launch_one(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_kernel<SPW, KIND, HAS0, HAS1>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((fused_kernel<SPW, KIND, HAS0, HAS1>), dim3(grid), dim3(kThreads), lds_bytes, st, fa);
+  return hipGetLastError();
+}
+
+template <int SPW>
+hipError_t launch_spw(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t st) {
+  const RowArgs& a = fa.r;
+  const bool h0 = a.B0 != nullptr, h1 = a.B1 != nullptr;
+  switch (a.kind) {
+    case kRowsHv:
+      if (fa.partial == nullptr || !h1) return hipErrorInvalidValue;
+      if (h0) return launch_one<SPW, kRowsHv, true, true>(fa, grid, lds_bytes, st);
+      if (a.Pin == nullptr) return hipErrorInvalidValue;
+      return launch_one<SPW, kRowsHv, false, true>(fa, grid, lds_bytes, st);
+    case kRowsGrad:
+      if (fa.partial == nullptr || !h0 || a.labels == nullptr || a.loss_part == nullptr) return hipErrorInvalidValue;
+      return launch_one<SPW, kRowsGrad, true, false>(fa, grid, lds_bytes, st);
+    case kRowsLoss:
+      if (!h0 || a.labels == nullptr || a.loss_part == nullptr) return hipErrorInvalidValue;
+      return launch_one<SPW, kRowsLoss, true, false>(fa, grid, lds_bytes, st);
+    case kRowsLogits:
+      if (h0 && h1) return launch_one<SPW, kRowsLogits, true, true>(fa, grid, lds_bytes, st);
+      if (h1) return launch_one<SPW, kRowsLogits, false, true>(fa, grid, lds_bytes, st);
+      if (h0) return launch_one<SPW, kRowsLogits, true, false>(fa, grid, lds_bytes, st);
+      return hipErrorInvalidValue;
+    default:
+      return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+bool fused_supported(const Shape& s, int64_t lda, const void* A) {
+  if (s.NC > 16) return false;
+  if (steps_of(s.p) > kMaxSteps) return false;
+  if ((lda & 3) != 0 || (reinterpret_cast<uintptr_t>(A) & 15) != 0) return false;
+  return true;
+}
+
+int fused_num_partials(const Shape& s) {
+  // host-only upper bound used for the workspace layout: one partial per workgroup
+  const int64_t tiles = (s.n + kTileRows - 1) / kTileRows;
+  const int64_t g = tiles < 256 ? tiles : 256;
+  return (int)(g < 1 ? 1 : g);
+}
+
+hipError_t launch_fused(const RowArgs& a, float* partial, int nparts, hipStream_t st) {
+  FusedArgs fa;
+  fa.r = a;
+  fa.partial = partial;
+  fa.steps = steps_of(a.p);
+  const int grid = nparts;
+  fa.rows_per_wg = (int)((a.n + grid - 1) / grid);
+  const size_t lds_bytes = (size_t)fa.steps * kStepBytes + kPartBytes + kSumBytes;
+  const int spw = (fa.steps + kWaves - 1) / kWaves;
+  switch (spw) {
+    case 1: return launch_spw<1>(fa, grid, lds_bytes, st);
+    case 2: return launch_spw<2>(fa, grid, lds_bytes, st);
+    case 3: return launch_spw<3>(fa, grid, lds_bytes, st);
+    case 4: return launch_spw<4>(fa, grid, lds_bytes, st);
+    default: return hipErrorInvalidValue;
+  }
+}
 
 }  // namespace nadmm

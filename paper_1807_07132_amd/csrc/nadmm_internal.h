@@ -195,11 +195,12 @@ hipError_t launch_ls_tail(const LsTailArgs& a, hipStream_t st);
 hipError_t launch_state_init(DevState* st, hipStream_t stream);
 
 // ---- fused single-pass path (nadmm_fused.hip) ----
-bool fused_supported(const Shape& s, int64_t lda);
+bool fused_supported(const Shape& s, int64_t lda, const void* A);
 int fused_num_partials(const Shape& s);
-size_t fused_pack_bytes(const Shape& s);
-// Runs the rows pass and the transpose product in one sweep over A; leaves
-// per-workgroup partial sums of A^T rows in `partial` (fused_num_partials() x d).
-hipError_t launch_fused(const RowArgs& a, float* partial, void* pack_ws, hipStream_t st);
+// Runs the rows pass and (if partial != NULL) the transpose product in one sweep
+// over A; leaves per-workgroup partial sums of A^T rows in `partial`
+// (nparts = fused_num_partials() blocks of d floats) and per-workgroup partial
+// losses in a.loss_part[0 .. nparts).
+hipError_t launch_fused(const RowArgs& a, float* partial, int nparts, hipStream_t st);
 
 }  // namespace nadmm

@@ -44,6 +44,12 @@ CASES = {
     "single_feature_300x1_C2": lambda: workloads.generic(300, 1, 2, seed=8),
     "rows_64": lambda: workloads.generic(64, 32, 3, seed=9),
     "rows_65": lambda: workloads.generic(65, 33, 3, seed=10),
+    # shapes the fused single-pass kernel takes (row stride a multiple of 4, C-1 <= 16, p <= 960)
+    "fused_2000x100_C7": lambda: workloads.generic(2000, 100, 7, seed=12),
+    "fused_9001x260_C10": lambda: workloads.generic(9001, 260, 10, seed=13, mean=True),
+    "fused_4100x36_C17": lambda: workloads.generic(4100, 36, 17, seed=14, x_std=0.2),
+    "fused_130x960_C4": lambda: workloads.generic(130, 960, 4, seed=15, x_std=0.05),
+    "fused_8200x64_C2": lambda: workloads.generic(8200, 64, 2, seed=16),
 }
 
 PATHS = [1, 0]  # 1 = two-pass vector kernels forced, 0 = automatic selection
@@ -103,7 +109,8 @@ def test_hessvec(cache, name, path):
 
 
 @pytest.mark.parametrize("path", PATHS)
-@pytest.mark.parametrize("name", ["tiny", "image_like_3k", "tall_binary_50k", "ragged_1237x45_C5", "ragged_333x130_C12"])
+@pytest.mark.parametrize("name", ["tiny", "image_like_3k", "tall_binary_50k", "ragged_1237x45_C5", "ragged_333x130_C12",
+                                  "fused_2000x100_C7", "fused_130x960_C4"])
 def test_cg_fixed_iterations(cache, name, path):
     w, gp, op = setup_case(cache, name)
     nadmm.nadmm_set_kernel_path(path)
@@ -139,7 +146,7 @@ def test_cg_tolerance_mode(cache, name):
 
 
 @pytest.mark.parametrize("path", PATHS)
-@pytest.mark.parametrize("name", ["tiny", "image_like_3k", "tall_binary_50k", "ragged_517x65_C3"])
+@pytest.mark.parametrize("name", ["tiny", "image_like_3k", "tall_binary_50k", "ragged_517x65_C3", "fused_8200x64_C2"])
 def test_line_search(cache, name, path):
     w, gp, op = setup_case(cache, name)
     nadmm.nadmm_set_kernel_path(path)
@@ -157,7 +164,7 @@ def test_line_search(cache, name, path):
 
 
 NEWTON_CASES = ["tiny", "image_like_3k", "wide_700", "tall_binary_50k", "large_multiclass_900", "ragged_1237x45_C5",
-                "single_row_1x7_C4"]
+                "single_row_1x7_C4", "fused_9001x260_C10", "fused_4100x36_C17"]
 
 
 @pytest.mark.parametrize("path", PATHS)
