@@ -7,8 +7,9 @@
 // wave w owns steps w, w+8, ... in BOTH contractions:
 //   phase 1  Z|W tile (32 x 2*16) = A_tile [X|V]   -- A straight from global
 //            loads in MFMA A-operand layout, [X|V] resident in registers;
-//   rows     cross-wave sum of the K-split partials through LDS, then the
-//            log-sum-exp / probabilities / D per row with 16-lane DPP reductions;
+//   rows     cross-wave sum of the K-split partials through LDS; wave e forms the
+//            log-sum-exp / probabilities / D of 4 of the 32 rows with 16-lane DPP
+//            reductions and hands its D entries to the others through LDS;
 //   phase 2  out^T (16 x cols) += D^T A_tile        -- A re-read from a
 //            wave-private, bank-swizzled LDS copy written in phase 1.
 // A is read from HBM exactly once; the p x (C-1) accumulators stay in registers
@@ -29,7 +30,7 @@ constexpr int kStepCols = 32;
 constexpr int kMaxSteps = 30;                 // LDS: steps * 4 KB + 36 KB <= 160 KB
 constexpr int kStepBytes = 4096;              // hi plane 2 KB + lo plane 2 KB
 constexpr int kPartBytes = kWaves * 4 * 64 * 16;
-constexpr int kSumBytes = 4 * 64 * 16;
+constexpr int kSumBytes = 8 * 64 * 4;    // exchange buffer of the rows stage
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -104,9 +105,9 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   if (a.flag != nullptr && *a.flag == 0) return;
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int steps = fa.steps;
-  char* cm = lds;                               // steps x 4 KB, step s owned by wave s % 8
-  char* part = lds + (size_t)steps * kStepBytes;  // [wave][quad][lane] x 16 B
-  char* sums = part + kPartBytes;               // [quad][lane] x 16 B
+  char* cm = lds;                                                  // steps x 4 KB, step s owned by wave s % 8
+  float* part = reinterpret_cast<float*>(lds + (size_t)steps * kStepBytes);  // [wave][quad][comp][lane]
+  float* dbuf = part + kPartBytes / 4;                             // [e][lane]
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -118,8 +119,9 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   constexpr bool has1 = HAS1;
   constexpr bool with_cols = KIND == kRowsHv || KIND == kRowsGrad;
   const bool cv = m < NC;  // this lane's class is a real one
+  const int mc = cv ? m : NC - 1;
 
-  // ---- [X|V] operands of this wave's steps, split and packed once ----
+  // ---- [X|V] operands of this wave's steps, split and packed once (loads are branch-free) ----
   u32x4 bx_hi[SPW], bx_lo[SPW], bv_hi[SPW], bv_lo[SPW];
 #pragma unroll
   for (int i = 0; i < SPW; ++i) {
@@ -128,9 +130,15 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int j = kStepCols * s + 8 * kg + e;
-      const bool ok = s < steps && j < p && cv;
-      x[e] = (ok && has0) ? a.B0[(size_t)j * NC + m] : 0.f;
-      v[e] = (ok && has1) ? a.B1[(size_t)j * NC + m] : 0.f;
+      const size_t idx = (size_t)(j < p ? j : p - 1) * NC + mc;
+      x[e] = has0 ? a.B0[idx] : 0.f;
+      v[e] = has1 ? a.B1[idx] : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const bool ok = cv && (kStepCols * s + 8 * kg + e) < p;
+      x[e] = ok ? x[e] : 0.f;
+      v[e] = ok ? v[e] : 0.f;
     }
     split8(x, bx_hi[i], bx_lo[i]);
     split8(v, bv_hi[i], bv_lo[i]);
@@ -147,8 +155,11 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   const int64_t r_begin = (int64_t)blockIdx.x * fa.rows_per_wg;
   int64_t r_end = r_begin + fa.rows_per_wg;
   if (r_end > a.n) r_end = a.n;
+  const int col_max = (int)a.lda - 4;  // last 16-byte aligned column offset that stays inside a row
 
   // ---- prefetch registers: [step][row block][half of the 8 columns] ----
+  // Addresses are clamped into the matrix, so the loads need no branches; rows
+  // past the range and columns past p are zeroed when the registers are used.
   float4 pf[SPW][2][2];
   auto load_step = [&](int i, int64_t row0) {
     const int s = wave + kWaves * i;
@@ -156,58 +167,69 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     const int col = kStepCols * s + 8 * kg;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-      const int64_t row = row0 + m + 16 * rb;
-      const float* src = a.A + row * a.lda + col;
+      int64_t row = row0 + m + 16 * rb;
+      row = row < r_end ? row : r_end - 1;
+      const float* src = a.A + row * a.lda;
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
         const int c0 = col + 4 * h;
-        if (row < r_end) {
-          if (c0 + 4 <= p) {
-            val = *reinterpret_cast<const float4*>(src + 4 * h);
-          } else if (c0 < p) {
-            val.x = src[4 * h];
-            if (c0 + 1 < p) val.y = src[4 * h + 1];
-            if (c0 + 2 < p) val.z = src[4 * h + 2];
-          }
-        }
-        pf[i][rb][h] = val;
+        pf[i][rb][h] = *reinterpret_cast<const float4*>(src + (c0 < col_max ? c0 : col_max));
       }
     }
   };
 
+  if (r_begin < r_end) {
 #pragma unroll
-  for (int i = 0; i < SPW; ++i) load_step(i, r_begin);
+    for (int i = 0; i < SPW; ++i) load_step(i, r_begin);
+  }
 
   for (int64_t row0 = r_begin; row0 < r_end; row0 += kTileRows) {
-    // rows of this lane in the rows stage: e < 4 -> row0 + 4 kg + e, e >= 4 -> row0 + 16 + 4 kg + (e - 4)
-    auto row_of = [&](int e) -> int64_t { return row0 + 4 * kg + (e & 3) + ((e >> 2) << 4); };
-    float aux[8];  // cached probabilities (Hessian-vector rows without X) or labels (gradient / loss rows)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int64_t rr = row_of(e);
-      aux[e] = 0.f;
-      if (KIND == kRowsHv && !has0) {
-        if (rr < r_end && cv) aux[e] = a.Pin[(size_t)rr * NC + m];
-      } else if (KIND == kRowsGrad || KIND == kRowsLoss) {
-        aux[e] = __int_as_float(rr < r_end ? a.labels[rr] : -1);
-      }
-    }
+    // the row this wave handles in the rows stage: e = wave, row = row0 + 4 kg + (e & 3) + 16 (e >> 2)
+    const int64_t my_row = row0 + 4 * kg + (wave & 3) + ((wave >> 2) << 4);
+    const bool my_valid = my_row < r_end;
+    const int64_t my_rowc = my_valid ? my_row : r_end - 1;
+    float aux = 0.f;  // cached probability (Hessian-vector rows without X) or label (gradient / loss rows)
+    if (KIND == kRowsHv && !has0) aux = a.Pin[(size_t)my_rowc * NC + mc];
+    if (KIND == kRowsGrad || KIND == kRowsLoss) aux = __int_as_float(a.labels[my_rowc]);
 
     // ---------------- phase 1 ----------------
     f32x4 accZ[2], accW[2];
     accZ[0] = accZ[1] = accW[0] = accW[1] = f32x4{0.f, 0.f, 0.f, 0.f};
     const bool more = row0 + kTileRows < r_end;
+    const bool tile_full = row0 + kTileRows <= r_end;
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
       const int s = wave + kWaves * i;
       if (s < steps) {
+        float av[2][8];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+          av[rb][0] = pf[i][rb][0].x; av[rb][1] = pf[i][rb][0].y; av[rb][2] = pf[i][rb][0].z; av[rb][3] = pf[i][rb][0].w;
+          av[rb][4] = pf[i][rb][1].x; av[rb][5] = pf[i][rb][1].y; av[rb][6] = pf[i][rb][1].z; av[rb][7] = pf[i][rb][1].w;
+        }
+        if (!(tile_full && kStepCols * (s + 1) <= p && kStepCols * (s + 1) <= col_max + 4)) {
+          // ragged tile or ragged step (uniform branch): zero what lies outside the matrix
+          const int col = kStepCols * s + 8 * kg;
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb) {
+            const bool rok = row0 + m + 16 * rb < r_end;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const int c0 = col + 4 * h;
+              const int cl = c0 < col_max ? c0 : col_max;  // column the load really started at
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                // element e of the register holds column cl + e; it stands for column c0 + e
+                const bool ok = rok && cl == c0 && c0 + e < p;
+                av[rb][4 * h + e] = ok ? av[rb][4 * h + e] : 0.f;
+              }
+            }
+          }
+        }
         u32x4 ahi[2], alo[2];
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
-          const float av[8] = {pf[i][rb][0].x, pf[i][rb][0].y, pf[i][rb][0].z, pf[i][rb][0].w,
-                               pf[i][rb][1].x, pf[i][rb][1].y, pf[i][rb][1].z, pf[i][rb][1].w};
-          split8(av, ahi[rb], alo[rb]);
+          split8(av[rb], ahi[rb], alo[rb]);
           if (has0) accZ[rb] = mfma3(ahi[rb], alo[rb], bx_hi[i], bx_lo[i], accZ[rb]);
           if (has1) accW[rb] = mfma3(ahi[rb], alo[rb], bv_hi[i], bv_lo[i], accW[rb]);
         }
@@ -227,80 +249,65 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
         }
       }
     }
-    // K-split partials of this wave
+    // K-split partials of this wave, one 256-byte row per (quad, component)
     {
-      f32x4* pw = reinterpret_cast<f32x4*>(part) + (wave * 4) * 64 + lane;
-      pw[0 * 64] = accZ[0];
-      pw[1 * 64] = accZ[1];
-      pw[2 * 64] = accW[0];
-      pw[3 * 64] = accW[1];
-    }
-    __syncthreads();
-    if (wave < 4) {
-      const f32x4* pr = reinterpret_cast<const f32x4*>(part) + wave * 64 + lane;
-      f32x4 t = pr[0];
-#pragma unroll
-      for (int w = 1; w < kWaves; ++w) t += pr[(w * 4) * 64];
-      reinterpret_cast<f32x4*>(sums)[wave * 64 + lane] = t;
-    }
-    __syncthreads();
-    float zz[8], ww[8];
-    {
-      const f32x4* sr = reinterpret_cast<const f32x4*>(sums) + lane;
-      const f32x4 z0 = sr[0], z1 = sr[64], w0 = sr[128], w1 = sr[192];
+      float* pw = part + (size_t)(wave * 16) * 64 + lane;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        zz[e] = z0[e];
-        zz[4 + e] = z1[e];
-        ww[e] = w0[e];
-        ww[4 + e] = w1[e];
+        if (has0) { pw[(0 + e) * 64] = accZ[0][e]; pw[(4 + e) * 64] = accZ[1][e]; }
+        if (has1) { pw[(8 + e) * 64] = accW[0][e]; pw[(12 + e) * 64] = accW[1][e]; }
       }
     }
+    __syncthreads();
 
-    // ---------------- rows stage (every wave, redundantly) ----------------
-    if (KIND == kRowsLogits) {
-      if (wave == 0 && cv) {
+    // ---------------- rows stage: wave e handles rows row0 + 4 kg + (e & 3) + 16 (e >> 2) ----------------
+    float z = 0.f, w = 0.f;
+    {
+      const float* pr = part + (size_t)(((wave >> 2) * 4 + (wave & 3))) * 64 + lane;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int64_t rr = row_of(e);
-          if (rr < r_end) {
-            if (has0 && a.Z0out) a.Z0out[(size_t)rr * NC + m] = zz[e];
-            if (has1 && a.Z1out) a.Z1out[(size_t)rr * NC + m] = ww[e];
-          }
-        }
+      for (int sw = 0; sw < kWaves; ++sw) {
+        if (has0) z += pr[(sw * 16) * 64];
+        if (has1) w += pr[(sw * 16 + 8) * 64];
       }
+    }
+    const size_t my_off = (size_t)my_row * NC + m;
+    if (KIND == kRowsLogits) {
+      if (cv && my_valid) {
+        if (has0 && a.Z0out) a.Z0out[my_off] = z;
+        if (has1 && a.Z1out) a.Z1out[my_off] = w;
+      }
+      __syncthreads();  // the partials are rewritten by the next tile
       continue;
     }
-    float dd[8];  // this lane's entries of D (kind 0) or P - Y (kind 1)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int64_t rr = row_of(e);
-      const bool rv = rr < r_end;
-      float P, M = 0.f, alpha = 1.f;
-      if (has0) {
-        const float z = cv ? zz[e] : 0.f;
-        M = row16_max(z);                    // max{0, Z_1..Z_{C-1}}: padded lanes supply the 0
-        const float E = cv ? expf(z - M) : 0.f;
-        alpha = row16_sum(E) + expf(-M);
-        P = E / alpha;
-      } else {
-        P = aux[e];
-      }
-      if (KIND == kRowsHv) {
-        const float t = row16_sum(P * ww[e]);
-        dd[e] = P * (ww[e] - t);
-      } else {
-        const bool mine = cv && m == __float_as_int(aux[e]);
-        dd[e] = P - (mine ? 1.f : 0.f);
-        const float zb = row16_sum(mine ? zz[e] : 0.f);
-        if (wave == 0 && m == 0 && rv) loss_acc += (double)M + (double)logf(alpha) - (double)zb;
-      }
-      if (wave == 0 && cv && rv) {
-        if (a.Pout) a.Pout[(size_t)rr * NC + m] = P;
-        if (has0 && a.Z0out) a.Z0out[(size_t)rr * NC + m] = zz[e];
-      }
+    float P, M = 0.f, alpha = 1.f, d;
+    if (has0) {
+      const float zc = cv ? z : 0.f;
+      M = row16_max(zc);                   // max{0, Z_1..Z_{C-1}}: padded lanes supply the 0
+      const float E = cv ? expf(zc - M) : 0.f;
+      alpha = row16_sum(E) + expf(-M);
+      P = E / alpha;
+    } else {
+      P = cv ? aux : 0.f;
     }
-    if (!with_cols) continue;
+    if (KIND == kRowsHv) {
+      const float t = row16_sum(P * w);
+      d = P * (w - t);
+    } else {
+      const bool mine = cv && m == __float_as_int(aux);
+      d = P - (mine ? 1.f : 0.f);
+      const float zb = row16_sum(mine ? z : 0.f);
+      if (m == 0 && my_valid) loss_acc += (double)M + (double)logf(alpha) - (double)zb;
+    }
+    if (cv && my_valid) {
+      if (a.Pout) a.Pout[my_off] = P;
+      if (has0 && a.Z0out) a.Z0out[my_off] = z;
+    }
+    if (!with_cols) {
+      __syncthreads();  // the partials are rewritten by the next tile
+      continue;
+    }
+    dbuf[wave * 64 + lane] = d;
+    __syncthreads();
 
     // ---------------- phase 2 ----------------
     u32x4 dhi, dlo;
@@ -308,8 +315,9 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
       unsigned h[4], l[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {  // k-slot pair (2e, 2e+1) = (row 4kg+e, row 16+4kg+e)
-        h[e] = pack2(dd[e], dd[4 + e]);
-        l[e] = pack2(dd[e] - low_as_float(h[e]), dd[4 + e] - high_as_float(h[e]));
+        const float d0 = dbuf[e * 64 + lane], d1 = dbuf[(4 + e) * 64 + lane];
+        h[e] = pack2(d0, d1);
+        l[e] = pack2(d0 - low_as_float(h[e]), d1 - high_as_float(h[e]));
       }
       dhi = u32x4{h[0], h[1], h[2], h[3]};
       dlo = u32x4{l[0], l[1], l[2], l[3]};
@@ -351,10 +359,18 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
       }
     }
   }
-  if (a.loss_part != nullptr && wave == 0) {
+  if (KIND == kRowsGrad || KIND == kRowsLoss) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) loss_acc += __shfl_down(loss_acc, off, 64);
-    if (lane == 0) a.loss_part[blockIdx.x] = loss_acc;
+    double* red = reinterpret_cast<double*>(dbuf);
+    __syncthreads();
+    if (lane == 0) red[wave] = loss_acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      for (int wv = 0; wv < kWaves; ++wv) t += red[wv];
+      a.loss_part[blockIdx.x] = t;
+    }
   }
 }
 

@@ -34,13 +34,30 @@ __device__ __forceinline__ double block_sum(double v, double* sm /* >= 17 double
   return sm[16];
 }
 
+// out[e] = s * sum_k partial[k][e] + linear terms.  A workgroup covers 32 elements; its 8
+// thread groups each sum every 8th partial (independent loads in flight), then the 8 group sums
+// are added in a fixed order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
   if (a.flag != nullptr && *a.flag == 0) return;
-  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (e >= a.d) return;
+  __shared__ float sm[8][32];
+  const int el = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int64_t e = (int64_t)blockIdx.x * 32 + el;
   float sum = 0.f;
-  const float* __restrict__ pp = a.partial + e;
-  for (int k = 0; k < a.nparts; ++k) sum += pp[(size_t)k * a.d];
+  if (e < a.d) {
+    const float* __restrict__ pp = a.partial + e;
+    int k = grp;
+    for (; k + 24 < a.nparts; k += 32) {
+      const float v0 = pp[(size_t)k * a.d], v1 = pp[(size_t)(k + 8) * a.d];
+      const float v2 = pp[(size_t)(k + 16) * a.d], v3 = pp[(size_t)(k + 24) * a.d];
+      sum += v0; sum += v1; sum += v2; sum += v3;
+    }
+    for (; k < a.nparts; k += 8) sum += pp[(size_t)k * a.d];
+  }
+  sm[grp][el] = sum;
+  __syncthreads();
+  if (grp != 0 || e >= a.d) return;
+#pragma unroll
+  for (int g = 1; g < 8; ++g) sum += sm[g][el];
   float out = a.scale * sum;
   if (a.kind == 0) {
     out = fmaf(a.lambda + a.rho, a.V[e], out);
@@ -320,7 +337,7 @@ hipError_t dispatch_ncp(int NC, F&& f) {
 }  // namespace
 
 hipError_t launch_reduce_out(const ReduceArgs& a, hipStream_t st) {
-  const int blocks = (int)((a.d + 255) / 256);
+  const int blocks = (int)((a.d + 31) / 32);
   hipLaunchKernelGGL(reduce_out_kernel, dim3(blocks), dim3(256), 0, st, a);
   return hipGetLastError();
 }
