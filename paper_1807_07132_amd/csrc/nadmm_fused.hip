@@ -20,8 +20,16 @@
 // hi*hi + hi*lo + lo*hi with fp32 accumulation (v_mfma_f32_16x16x32_bf16).
 #include "nadmm_internal.h"
 
+#ifndef NADMM_EXP
+#define NADMM_EXP 0  // timing experiments only (non-zero values skip work and give wrong results)
+#endif
+
 namespace nadmm {
 namespace {
+
+__device__ __forceinline__ void tile_barrier() {
+  if (NADMM_EXP != 4 && NADMM_EXP != 5) __syncthreads();
+}
 
 constexpr int kThreads = 512;
 constexpr int kWaves = 8;
@@ -46,7 +54,9 @@ struct FusedArgs {
 
 __device__ __forceinline__ unsigned pack2(float a, float b) {  // round-to-nearest-even, a in the low half
   bf16x2 v = {(__bf16)a, (__bf16)b};
-  return __builtin_bit_cast(unsigned, v);
+  unsigned r = __builtin_bit_cast(unsigned, v);
+  asm volatile("" : "+v"(r));  // keep the packed conversion as one instruction (no per-half re-conversion)
+  return r;
 }
 __device__ __forceinline__ float low_as_float(unsigned h) { return __uint_as_float(h << 16); }
 __device__ __forceinline__ float high_as_float(unsigned h) { return __uint_as_float(h & 0xffff0000u); }
@@ -99,7 +109,7 @@ __device__ __forceinline__ int cm_offset(int q, int ck) {
   return qs * 64 + ((ck ^ g) << 4);
 }
 
-template <int SPW, int KIND, bool HAS0, bool HAS1>
+template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES>
 __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   const RowArgs& a = fa.r;
   if (a.flag != nullptr && *a.flag == 0) return;
@@ -121,7 +131,48 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   const bool cv = m < NC;  // this lane's class is a real one
   const int mc = cv ? m : NC - 1;
 
-  // ---- [X|V] operands of this wave's steps, split and packed once (loads are branch-free) ----
+  f32x4 acc2[SPW][2];
+#pragma unroll
+  for (int i = 0; i < SPW; ++i) {
+    acc2[i][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+    acc2[i][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  double loss_acc = 0.0;
+
+  const int64_t r_begin = (int64_t)blockIdx.x * fa.rows_per_wg;
+  int64_t r_end = r_begin + fa.rows_per_wg;
+  if (r_end > a.n) r_end = a.n;
+  const int col_max = (int)a.lda - 4;  // last 16-byte aligned column offset that stays inside a row
+
+  // ---- prefetch registers: [step][row block][half of the 8 columns] ----
+  // Addresses are clamped into the matrix, so the loads need no branches; rows
+  // past the range and columns past p are zeroed when the registers are used.
+  float4 pf[SPW][2][2];
+  // Steps i < SPW-1 exist for every wave (steps > 8 (SPW-1)); only the last one is conditional.
+  auto step_exists = [&](int i) { return i < SPW - 1 || wave + kWaves * i < steps; };
+  auto load_step = [&](int i, int64_t row0) {
+    const int col = kStepCols * (wave + kWaves * i) + 8 * kg;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      int64_t row = row0 + m + 16 * rb;
+      row = row < r_end ? row : r_end - 1;
+      const float* src = a.A + row * a.lda;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int c0 = col + 4 * h;
+        pf[i][rb][h] = *reinterpret_cast<const float4*>(src + (c0 < col_max ? c0 : col_max));
+      }
+    }
+  };
+
+  if (r_begin < r_end) {
+#pragma unroll
+    for (int i = 0; i < SPW; ++i)
+      if (step_exists(i)) load_step(i, r_begin);
+  }
+
+  // ---- [X|V] operands of this wave's steps, split and packed once (branch-free loads,
+  //      issued while the first tile is already on its way) ----
   u32x4 bx_hi[SPW], bx_lo[SPW], bv_hi[SPW], bv_lo[SPW];
 #pragma unroll
   for (int i = 0; i < SPW; ++i) {
@@ -144,45 +195,6 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     split8(v, bv_hi[i], bv_lo[i]);
   }
 
-  f32x4 acc2[SPW][2];
-#pragma unroll
-  for (int i = 0; i < SPW; ++i) {
-    acc2[i][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-    acc2[i][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-  double loss_acc = 0.0;
-
-  const int64_t r_begin = (int64_t)blockIdx.x * fa.rows_per_wg;
-  int64_t r_end = r_begin + fa.rows_per_wg;
-  if (r_end > a.n) r_end = a.n;
-  const int col_max = (int)a.lda - 4;  // last 16-byte aligned column offset that stays inside a row
-
-  // ---- prefetch registers: [step][row block][half of the 8 columns] ----
-  // Addresses are clamped into the matrix, so the loads need no branches; rows
-  // past the range and columns past p are zeroed when the registers are used.
-  float4 pf[SPW][2][2];
-  auto load_step = [&](int i, int64_t row0) {
-    const int s = wave + kWaves * i;
-    if (s >= steps) return;
-    const int col = kStepCols * s + 8 * kg;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      int64_t row = row0 + m + 16 * rb;
-      row = row < r_end ? row : r_end - 1;
-      const float* src = a.A + row * a.lda;
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int c0 = col + 4 * h;
-        pf[i][rb][h] = *reinterpret_cast<const float4*>(src + (c0 < col_max ? c0 : col_max));
-      }
-    }
-  };
-
-  if (r_begin < r_end) {
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) load_step(i, r_begin);
-  }
-
   for (int64_t row0 = r_begin; row0 < r_end; row0 += kTileRows) {
     // the row this wave handles in the rows stage: e = wave, row = row0 + 4 kg + (e & 3) + 16 (e >> 2)
     const int64_t my_row = row0 + 4 * kg + (wave & 3) + ((wave >> 2) << 4);
@@ -195,34 +207,28 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     // ---------------- phase 1 ----------------
     f32x4 accZ[2], accW[2];
     accZ[0] = accZ[1] = accW[0] = accW[1] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const bool more = row0 + kTileRows < r_end;
-    const bool tile_full = row0 + kTileRows <= r_end;
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
       const int s = wave + kWaves * i;
-      if (s < steps) {
+      if (step_exists(i)) {
         float av[2][8];
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
           av[rb][0] = pf[i][rb][0].x; av[rb][1] = pf[i][rb][0].y; av[rb][2] = pf[i][rb][0].z; av[rb][3] = pf[i][rb][0].w;
           av[rb][4] = pf[i][rb][1].x; av[rb][5] = pf[i][rb][1].y; av[rb][6] = pf[i][rb][1].z; av[rb][7] = pf[i][rb][1].w;
         }
-        if (!(tile_full && kStepCols * (s + 1) <= p && kStepCols * (s + 1) <= col_max + 4)) {
-          // ragged tile or ragged step (uniform branch): zero what lies outside the matrix
+        // Rows past the range were loaded as copies of the last row; they get D = 0 below.
+        // Columns past p (last step only, uniform branch) must be zeroed: the row padding may hold anything.
+        if (kStepCols * (s + 1) > p) {
           const int col = kStepCols * s + 8 * kg;
 #pragma unroll
-          for (int rb = 0; rb < 2; ++rb) {
-            const bool rok = row0 + m + 16 * rb < r_end;
+          for (int h = 0; h < 2; ++h) {
+            const int c0 = col + 4 * h;
+            const int nv = c0 <= col_max ? p - c0 : 0;  // valid elements of this float4 (clamped loads hold other columns)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-              const int c0 = col + 4 * h;
-              const int cl = c0 < col_max ? c0 : col_max;  // column the load really started at
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                // element e of the register holds column cl + e; it stands for column c0 + e
-                const bool ok = rok && cl == c0 && c0 + e < p;
-                av[rb][4 * h + e] = ok ? av[rb][4 * h + e] : 0.f;
-              }
+            for (int e = 0; e < 4; ++e) {
+              av[0][4 * h + e] = e < nv ? av[0][4 * h + e] : 0.f;
+              av[1][4 * h + e] = e < nv ? av[1][4 * h + e] : 0.f;
             }
           }
         }
@@ -233,8 +239,9 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
           if (has0) accZ[rb] = mfma3(ahi[rb], alo[rb], bx_hi[i], bx_lo[i], accZ[rb]);
           if (has1) accW[rb] = mfma3(ahi[rb], alo[rb], bv_hi[i], bv_lo[i], accW[rb]);
         }
-        if (more) load_step(i, row0 + kTileRows);  // registers are free again: prefetch the next tile
-        if (with_cols) {
+        // the registers are free again: prefetch the next tile (past the range the rows clamp to the last row)
+        load_step(i, row0 + kTileRows);
+        if (with_cols && NADMM_EXP != 2 && NADMM_EXP != 3 && NADMM_EXP != 5) {
           // transposed copy for phase 2: pair (row m, row m+16) of one column per 32-bit word
           char* base = cm + (size_t)s * kStepBytes;
 #pragma unroll
@@ -258,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
         if (has1) { pw[(8 + e) * 64] = accW[0][e]; pw[(12 + e) * 64] = accW[1][e]; }
       }
     }
-    __syncthreads();
+    tile_barrier();
 
     // ---------------- rows stage: wave e handles rows row0 + 4 kg + (e & 3) + 16 (e >> 2) ----------------
     float z = 0.f, w = 0.f;
@@ -276,11 +283,13 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
         if (has0 && a.Z0out) a.Z0out[my_off] = z;
         if (has1 && a.Z1out) a.Z1out[my_off] = w;
       }
-      __syncthreads();  // the partials are rewritten by the next tile
+      tile_barrier();  // the partials are rewritten by the next tile
       continue;
     }
     float P, M = 0.f, alpha = 1.f, d;
-    if (has0) {
+    if (NADMM_EXP == 3 || NADMM_EXP == 5) {
+      P = z;
+    } else if (has0) {
       const float zc = cv ? z : 0.f;
       M = row16_max(zc);                   // max{0, Z_1..Z_{C-1}}: padded lanes supply the 0
       const float E = cv ? expf(zc - M) : 0.f;
@@ -291,23 +300,23 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     }
     if (KIND == kRowsHv) {
       const float t = row16_sum(P * w);
-      d = P * (w - t);
+      d = my_valid ? P * (w - t) : 0.f;
     } else {
       const bool mine = cv && m == __float_as_int(aux);
-      d = P - (mine ? 1.f : 0.f);
+      d = my_valid ? P - (mine ? 1.f : 0.f) : 0.f;
       const float zb = row16_sum(mine ? z : 0.f);
       if (m == 0 && my_valid) loss_acc += (double)M + (double)logf(alpha) - (double)zb;
     }
-    if (cv && my_valid) {
+    if (STORES && cv && my_valid) {
       if (a.Pout) a.Pout[my_off] = P;
       if (has0 && a.Z0out) a.Z0out[my_off] = z;
     }
     if (!with_cols) {
-      __syncthreads();  // the partials are rewritten by the next tile
+      tile_barrier();  // the partials are rewritten by the next tile
       continue;
     }
     dbuf[wave * 64 + lane] = d;
-    __syncthreads();
+    tile_barrier();
 
     // ---------------- phase 2 ----------------
     u32x4 dhi, dlo;
@@ -325,14 +334,15 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
       const int s = wave + kWaves * i;
-      if (s < steps) {
+      if (step_exists(i)) {
         const char* base = cm + (size_t)s * kStepBytes;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           const int off = cm_offset(16 * h + m, kg);
           const u32x4 thi = *reinterpret_cast<const u32x4*>(base + off);
           const u32x4 tlo = *reinterpret_cast<const u32x4*>(base + 2048 + off);
-          acc2[i][h] = mfma3(dhi, dlo, thi, tlo, acc2[i][h]);
+          if (NADMM_EXP != 1 && NADMM_EXP != 2 && NADMM_EXP != 3 && NADMM_EXP != 5) acc2[i][h] = mfma3(dhi, dlo, thi, tlo, acc2[i][h]);
+          else acc2[i][h] += __builtin_bit_cast(f32x4, thi) + __builtin_bit_cast(f32x4, tlo);
         }
       }
     }
@@ -389,17 +399,27 @@ int num_cus() {
 
 int steps_of(int p) { return (p + kStepCols - 1) / kStepCols; }
 
-template <int SPW, int KIND, bool HAS0, bool HAS1>
-hipError_t launch_one(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t st) {
+template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES>
+hipError_t launch_k(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_kernel<SPW, KIND, HAS0, HAS1>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_kernel<SPW, KIND, HAS0, HAS1, STORES>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((fused_kernel<SPW, KIND, HAS0, HAS1>), dim3(grid), dim3(kThreads), lds_bytes, st, fa);
+  hipLaunchKernelGGL((fused_kernel<SPW, KIND, HAS0, HAS1, STORES>), dim3(grid), dim3(kThreads), lds_bytes, st, fa);
   return hipGetLastError();
+}
+
+// Kernels that may store rows of P / Z are separate instantiations: a store between the prefetch
+// and its use makes the compiler wait for all outstanding loads.
+template <int SPW, int KIND, bool HAS0, bool HAS1>
+hipError_t launch_one(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t st) {
+  const RowArgs& a = fa.r;
+  if (KIND == kRowsLogits || a.Pout != nullptr || a.Z0out != nullptr)
+    return launch_k<SPW, KIND, HAS0, HAS1, true>(fa, grid, lds_bytes, st);
+  return launch_k<SPW, KIND, HAS0, HAS1, false>(fa, grid, lds_bytes, st);
 }
 
 template <int SPW>

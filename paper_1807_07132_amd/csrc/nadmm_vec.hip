@@ -17,21 +17,17 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-// Sum over the whole workgroup; result valid in every thread.
+// Sum over the whole workgroup (fixed order); result valid in every thread.
 __device__ __forceinline__ double block_sum(double v, double* sm /* >= 17 doubles */) {
   v = wave_sum(v);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nw = (blockDim.x + 63) >> 6;
-  __syncthreads();
+  __syncthreads();  // previous users of sm are done
   if (lane == 0) sm[wave] = v;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    double t = 0.0;
-    for (int w = 0; w < nw; ++w) t += sm[w];
-    sm[16] = t;
-  }
-  __syncthreads();
-  return sm[16];
+  double t = 0.0;
+  for (int w = 0; w < nw; ++w) t += sm[w];
+  return t;
 }
 
 // out[e] = s * sum_k partial[k][e] + linear terms.  A workgroup covers 32 elements; its 8
@@ -46,10 +42,12 @@ __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
   if (e < a.d) {
     const float* __restrict__ pp = a.partial + e;
     int k = grp;
-    for (; k + 24 < a.nparts; k += 32) {
-      const float v0 = pp[(size_t)k * a.d], v1 = pp[(size_t)(k + 8) * a.d];
-      const float v2 = pp[(size_t)(k + 16) * a.d], v3 = pp[(size_t)(k + 24) * a.d];
-      sum += v0; sum += v1; sum += v2; sum += v3;
+    for (; k + 8 * 15 < a.nparts; k += 8 * 16) {  // 16 independent loads in flight, summed in order
+      float v[16];
+#pragma unroll
+      for (int t = 0; t < 16; ++t) v[t] = pp[(size_t)(k + 8 * t) * a.d];
+#pragma unroll
+      for (int t = 0; t < 16; ++t) sum += v[t];
     }
     for (; k < a.nparts; k += 8) sum += pp[(size_t)k * a.d];
   }
@@ -158,14 +156,32 @@ __global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs
 
 // One CG iteration's vector work, given q = H d:  a = rr / <d,q>; p += a d; r -= a q;
 // stop on ||r|| <= tol ||g|| (eq. inexact); else d = r + (rr'/rr) d.
+// PER > 0: each thread keeps its PER elements of d, q, r in registers (d <= PER * 1024).
+template <int PER>
 __global__ __launch_bounds__(kTail) void cg_update_kernel(const CgUpdateArgs a) {
   __shared__ double sm[17];
   DevState* st = a.st;
   if (st->cg_active == 0) return;
+  constexpr int N = PER > 0 ? PER : 1;
+  float dv[N], qv[N], rv[N];
   double dq = 0.0;
-  for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) dq += (double)a.dvec[e] * (double)a.q[e];
+  if (PER > 0) {
+#pragma unroll
+    for (int t = 0; t < N; ++t) {
+      const int64_t e = threadIdx.x + (int64_t)t * kTail;
+      const bool ok = e < a.d;
+      dv[t] = ok ? a.dvec[e] : 0.f;
+      qv[t] = ok ? a.q[e] : 0.f;
+      rv[t] = ok ? a.r[e] : 0.f;
+    }
+#pragma unroll
+    for (int t = 0; t < N; ++t) dq += (double)dv[t] * (double)qv[t];
+  } else {
+    for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) dq += (double)a.dvec[e] * (double)a.q[e];
+  }
   dq = block_sum(dq, sm);
   const double rr = st->rr;
+  const double gg = st->gg_cg;
   if (!(dq > 0.0) || !isfinite(dq)) {  // no positive curvature: keep the current iterate
     __syncthreads();
     if (threadIdx.x == 0) st->cg_active = 0;
@@ -173,19 +189,37 @@ __global__ __launch_bounds__(kTail) void cg_update_kernel(const CgUpdateArgs a) 
   }
   const float al = (float)(rr / dq);
   double rr_new = 0.0;
-  for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) {
-    a.pdir[e] = fmaf(al, a.dvec[e], a.pdir[e]);
-    const float rn = fmaf(-al, a.q[e], a.r[e]);
-    a.r[e] = rn;
-    rr_new += (double)rn * (double)rn;
+  if (PER > 0) {
+#pragma unroll
+    for (int t = 0; t < N; ++t) {
+      const int64_t e = threadIdx.x + (int64_t)t * kTail;
+      if (e < a.d) a.pdir[e] = fmaf(al, dv[t], a.pdir[e]);
+      rv[t] = fmaf(-al, qv[t], rv[t]);
+      rr_new += (double)rv[t] * (double)rv[t];
+    }
+  } else {
+    for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) {
+      a.pdir[e] = fmaf(al, a.dvec[e], a.pdir[e]);
+      const float rn = fmaf(-al, a.q[e], a.r[e]);
+      a.r[e] = rn;
+      rr_new += (double)rn * (double)rn;
+    }
   }
   rr_new = block_sum(rr_new, sm);
-  const bool stop = sqrt(rr_new) <= (double)a.tol * sqrt(st->gg_cg);
-  if (!stop) {
-    const float be = (float)(rr_new / rr);
+  const bool stop = sqrt(rr_new) <= (double)a.tol * sqrt(gg);
+  const float be = (float)(rr_new / rr);
+  if (PER > 0) {
+#pragma unroll
+    for (int t = 0; t < N; ++t) {
+      const int64_t e = threadIdx.x + (int64_t)t * kTail;
+      if (e < a.d) {
+        a.r[e] = rv[t];
+        if (!stop) a.dvec[e] = fmaf(be, dv[t], rv[t]);
+      }
+    }
+  } else if (!stop) {
     for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) a.dvec[e] = fmaf(be, a.dvec[e], a.r[e]);
   }
-  __syncthreads();
   if (threadIdx.x == 0) {
     st->rr = rr_new;
     st->cg_iters += 1;
@@ -358,7 +392,9 @@ hipError_t launch_newton_head(const NewtonHeadArgs& a, hipStream_t st) {
 }
 
 hipError_t launch_cg_update(const CgUpdateArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(cg_update_kernel, dim3(1), dim3(kTail), 0, st, a);
+  if (a.d <= 8 * kTail) hipLaunchKernelGGL(cg_update_kernel<8>, dim3(1), dim3(kTail), 0, st, a);
+  else if (a.d <= 24 * kTail) hipLaunchKernelGGL(cg_update_kernel<24>, dim3(1), dim3(kTail), 0, st, a);
+  else hipLaunchKernelGGL(cg_update_kernel<0>, dim3(1), dim3(kTail), 0, st, a);
   return hipGetLastError();
 }
 

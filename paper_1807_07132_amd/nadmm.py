@@ -15,7 +15,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libnadmm.so")
+LIB_PATH = os.environ.get("NADMM_LIB", os.path.join(_HERE, "libnadmm.so"))  # NADMM_LIB: alternative build of the same library
 
 NADMM_OK, NADMM_EINVAL, NADMM_EWORKSPACE, NADMM_EUNSUPPORTED, NADMM_EHIP = 0, -1, -2, -3, -4
 NADMM_TRACE_LEN = 64
