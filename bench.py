@@ -29,10 +29,12 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="image_like")
     ap.add_argument("--n", type=int, default=None, help="override the number of rows (testing only)")
-    ap.add_argument("--path", type=int, default=0, help="kernel path: 0 auto, 1 two-pass, 2 fused")
+    ap.add_argument("--path", type=int, default=0, help="kernel path: 0 auto, 1 two-pass, 2 fused, 3 thin")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--only", default="", help="comma list of hv,lg,solve: restrict the step (profiling runs)")
+    ap.add_argument("--hv-per-step", type=int, default=HV_PER_STEP)
+    ap.add_argument("--lg-per-step", type=int, default=LG_PER_STEP)
     return ap.parse_args()
 
 
@@ -97,14 +99,14 @@ def main():
         if do("hv"):
             e0, e1 = ev(), ev()
             e0.record()
-            for i in range(HV_PER_STEP):
+            for i in range(args.hv_per_step):
                 nadmm.nadmm_hessvec(gp, X, Vs[i & 3], out=hv_out, ws=ws)
             e1.record()
             t["hv"] = (e0, e1)
         if do("lg"):
             e0, e1 = ev(), ev()
             e0.record()
-            for i in range(LG_PER_STEP):
+            for i in range(args.lg_per_step):
                 nadmm.nadmm_loss_grad(gp, X, loss_out=loss_out, grad_out=g_out, ws=ws)
             e1.record()
             t["lg"] = (e0, e1)
@@ -132,11 +134,12 @@ def main():
     d = p * NC
     bytes_hv = 4.0 * n * p + 3 * 4.0 * d
     bytes_lg = 4.0 * n * p + 4.0 * n + 4 * 4.0 * d
-    extra = {"kernel_path": {1: "two-pass fp32 vector kernels", 2: "fused single pass"}[path]}
+    extra = {"kernel_path": {1: "two-pass fp32 vector kernels", 2: "fused single pass (matrix cores)",
+                             3: "thin-data single pass"}[path]}
     value = None
     roof = None
     if "hv" in tot:
-        per_hv_s = tot["hv"] / 1e3 / (HV_PER_STEP * args.steps)
+        per_hv_s = tot["hv"] / 1e3 / (args.hv_per_step * args.steps)
         value = 1.0 / per_hv_s
         ach = bytes_hv / per_hv_s / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
@@ -144,7 +147,7 @@ def main():
                 "us_per_launch": per_hv_s * 1e6, "algorithmic_bytes": bytes_hv}
         extra["hv_us"] = per_hv_s * 1e6
     if "lg" in tot:
-        per_lg_s = tot["lg"] / 1e3 / (LG_PER_STEP * args.steps)
+        per_lg_s = tot["lg"] / 1e3 / (args.lg_per_step * args.steps)
         extra["loss_grad_per_s"] = 1.0 / per_lg_s
         extra["loss_grad_us"] = per_lg_s * 1e6
         extra["loss_grad_hbm_frac"] = bytes_lg / per_lg_s / 1e9 / HBM_PEAK_GBS
@@ -160,8 +163,8 @@ def main():
         "value": value, "unit": "Hv/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3 / max(args.steps, 1), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "n": n, "p": p, "C": w.C, "hv_per_step": HV_PER_STEP,
-                   "loss_grad_per_step": LG_PER_STEP, "newton_iters": w.max_newton, "cg_iters": w.max_cg,
+        "config": {"workload": w.name, "n": n, "p": p, "C": w.C, "hv_per_step": args.hv_per_step,
+                   "loss_grad_per_step": args.lg_per_step, "newton_iters": w.max_newton, "cg_iters": w.max_cg,
                    "loss_scale": "1/n", "lambda": w.lam, "rho": w.rho},
         "roofline": roof, "extra": extra,
     }

@@ -23,8 +23,8 @@ struct Layout {
   size_t partial, loss_part, lpart;
   size_t total;
   int gen_row_blocks, gen_slabs, gen_chunks, gen_rpc;
-  int fused_parts;
-  bool fused_ok;
+  int fused_parts, thin_parts;
+  bool fused_ok, thin_ok;
 };
 
 int validate_problem(const nadmm_problem* p, bool need_labels) {
@@ -50,6 +50,8 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   generic_col_grid(s, &L->gen_slabs, &L->gen_chunks, &L->gen_rpc);
   L->fused_ok = fused_supported(s, p->lda, p->d_A);
   L->fused_parts = L->fused_ok ? fused_num_partials(s) : 0;
+  L->thin_ok = thin_supported(s, p->lda, p->d_A);
+  L->thin_parts = L->thin_ok ? thin_num_partials(s) : 0;
   const size_t vec = align256((size_t)s.d * sizeof(float));
   const size_t rows = align256((size_t)s.n * s.NC * sizeof(float));
   size_t off = 0;
@@ -63,9 +65,11 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   L->pcache = off; off += rows;
   L->zx = off; off += rows;
   L->zp = off; off += rows;
-  const int parts = L->gen_chunks > L->fused_parts ? L->gen_chunks : L->fused_parts;
+  int parts = L->gen_chunks > L->fused_parts ? L->gen_chunks : L->fused_parts;
+  if (L->thin_parts > parts) parts = L->thin_parts;
   L->partial = off; off += align256((size_t)parts * s.d * sizeof(float));
-  const int lblocks = L->gen_row_blocks > L->fused_parts ? L->gen_row_blocks : L->fused_parts;
+  int lblocks = L->gen_row_blocks > L->fused_parts ? L->gen_row_blocks : L->fused_parts;
+  if (L->thin_parts > lblocks) lblocks = L->thin_parts;
   L->loss_part = off; off += align256((size_t)lblocks * sizeof(double));
   L->lpart = off; off += align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
   L->total = off;
@@ -90,7 +94,7 @@ int hip_fail(hipError_t e) {
     if (e_ != hipSuccess) return hip_fail(e_);   \
   } while (0)
 
-// 1 = two-pass vector kernels, 2 = fused single pass
+// 1 = two-pass vector kernels, 2 = fused single pass (matrix cores), 3 = thin-data single pass
 int choose_path(const Layout& L, int* path) {
   if (g_path == 1) { *path = 1; return NADMM_OK; }
   if (g_path == 2) {
@@ -98,8 +102,17 @@ int choose_path(const Layout& L, int* path) {
     *path = 2;
     return NADMM_OK;
   }
-  *path = L.fused_ok ? 2 : 1;
+  if (g_path == 3) {
+    if (!L.thin_ok) return NADMM_EUNSUPPORTED;
+    *path = 3;
+    return NADMM_OK;
+  }
+  *path = L.thin_ok ? 3 : (L.fused_ok ? 2 : 1);
   return NADMM_OK;
+}
+
+int loss_blocks(const Layout& L, int path) {
+  return path == 3 ? L.thin_parts : (path == 2 ? L.fused_parts : L.gen_row_blocks);
 }
 
 // One sweep over A: rows pass, and (if with_cols) partial sums of A^T rows_out.
@@ -113,6 +126,11 @@ int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArg
   if (path == 2) {
     NADMM_HIP(launch_fused(ra, with_cols ? at<float>(ws, L.partial) : nullptr, L.fused_parts, st));
     *nparts = L.fused_parts;
+    return NADMM_OK;
+  }
+  if (path == 3) {
+    NADMM_HIP(launch_thin(ra, with_cols ? at<float>(ws, L.partial) : nullptr, L.thin_parts, st));
+    *nparts = L.thin_parts;
     return NADMM_OK;
   }
   NADMM_HIP(launch_generic_rows(ra, st));
@@ -214,7 +232,7 @@ const char* nadmm_status_string(int code) {
 const char* nadmm_last_hip_error(void) { return g_last_hip_error.c_str(); }
 
 int nadmm_set_kernel_path(int path) {
-  if (path < 0 || path > 2) return NADMM_EINVAL;
+  if (path < 0 || path > 3) return NADMM_EINVAL;
   const int prev = g_path;
   g_path = path;
   return prev;
@@ -262,7 +280,7 @@ int nadmm_loss_grad(const nadmm_problem* prob, const float* d_X, double* d_loss,
 
   LossFinishArgs lf;
   lf.loss_part = at<double>(d_ws, L.loss_part);
-  lf.nblocks = path == 2 ? L.fused_parts : L.gen_row_blocks;
+  lf.nblocks = loss_blocks(L, path);
   lf.scale = prob->loss_scale;
   lf.lambda = prob->lambda;
   lf.rho = prob->rho;
@@ -450,7 +468,7 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
     std::memset(&nh, 0, sizeof(nh));
     nh.st = ds;
     nh.loss_part = at<double>(d_ws, L.loss_part);
-    nh.nblocks = path == 2 ? L.fused_parts : L.gen_row_blocks;
+    nh.nblocks = loss_blocks(L, path);
     nh.scale = prob->loss_scale;
     nh.lambda = prob->lambda;
     nh.rho = prob->rho;

@@ -203,4 +203,9 @@ int fused_num_partials(const Shape& s);
 // losses in a.loss_part[0 .. nparts).
 hipError_t launch_fused(const RowArgs& a, float* partial, int nparts, hipStream_t st);
 
+// ---- thin-data single-pass path (nadmm_thin.hip): p <= 32, p % 4 == 0, C-1 <= 3, lda == p ----
+bool thin_supported(const Shape& s, int64_t lda, const void* A);
+int thin_num_partials(const Shape& s);
+hipError_t launch_thin(const RowArgs& a, float* partial, int nparts, hipStream_t st);
+
 }  // namespace nadmm

@@ -1,0 +1,257 @@
+// Single-pass kernel for thin data (p <= 32 features, few classes), gfx950.
+//
+// With rows of 16..128 bytes the pass is a pure HBM stream (about 1.5 flop per
+// byte for C = 2), so there is no contraction worth a matrix core: one lane owns
+// one sample.  A workgroup copies a chunk of 256 consecutive rows -- a contiguous
+// block of memory -- with coalesced 16-byte loads into LDS (row stride padded off
+// the bank period), each lane reads its own row back, forms its logits Z = a_i X
+// and W = a_i V with X and V as wave-uniform operands, the probabilities with the
+// log-sum-exp shift (Section 2.2), its row of D (Section 2.6) or of P - Y, and
+// accumulates a_i^T D into its private p x (C-1) registers.  The next chunk is
+// already in flight in registers while the current one is consumed.  Per-lane
+// accumulators are summed over the workgroup once, at the end, in a fixed order.
+#include "nadmm_internal.h"
+
+namespace nadmm {
+namespace {
+
+constexpr int kThinThreads = 256;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct ThinArgs {
+  RowArgs r;
+  float* partial;      // gridDim.x x (p*NC) or NULL
+  int32_t rows_per_wg; // multiple of 256
+  int32_t lds_stride;  // floats per row in LDS
+  int32_t q1024;       // 1024 / p
+  int32_t r1024;       // 1024 % p
+};
+
+// NQ = p / 4: float4 per row, which is also the float4 per lane in a chunk of 256 rows
+template <int NQ, int NC>
+__global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
+  constexpr int PP = 4 * NQ;
+  constexpr int kMaxQuads = NQ;
+  constexpr int nquads = NQ;
+  const RowArgs& a = ta.r;
+  if (a.flag != nullptr && *a.flag == 0) return;
+  extern __shared__ __attribute__((aligned(16))) float tile[];  // 256 x lds_stride floats
+  __shared__ double red[4];
+  const int t = threadIdx.x;
+  constexpr int p = PP;
+  const int PS = ta.lds_stride;
+  const bool has0 = a.B0 != nullptr;
+  const bool has1 = a.B1 != nullptr;
+  const bool with_cols = ta.partial != nullptr;
+
+  const int64_t r_begin = (int64_t)blockIdx.x * ta.rows_per_wg;
+  int64_t r_end = r_begin + ta.rows_per_wg;
+  if (r_end > a.n) r_end = a.n;
+  const f32x4* A4 = reinterpret_cast<const f32x4*>(a.A);
+  const int64_t last4 = a.n * nquads - 1;  // last float4 of the matrix (lda == p)
+
+  float acc[PP][NC];
+#pragma unroll
+  for (int j = 0; j < PP; ++j)
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc[j][c] = 0.f;
+  double loss_acc = 0.0;
+
+  // position of this lane's k-th float4 inside a chunk: element 4 (t + 256 k) = row * p + col
+  int prow[kMaxQuads], pcol[kMaxQuads];
+  {
+    int row = (4 * t) / p, col = (4 * t) % p;
+#pragma unroll
+    for (int k = 0; k < kMaxQuads; ++k) {
+      prow[k] = row;
+      pcol[k] = col;
+      row += ta.q1024;
+      col += ta.r1024;
+      if (col >= p) { col -= p; row += 1; }
+    }
+  }
+
+  f32x4 pf[kMaxQuads];
+  auto load_chunk = [&](int64_t row0) {
+    const int64_t base4 = row0 * nquads + t;
+#pragma unroll
+    for (int k = 0; k < kMaxQuads; ++k) {
+      int64_t i4 = base4 + (int64_t)k * kThinThreads;
+      i4 = i4 < last4 ? i4 : last4;  // clamp: rows past the end are never used
+      pf[k] = A4[i4];
+    }
+  };
+
+  if (r_begin < r_end) load_chunk(r_begin);
+  for (int64_t row0 = r_begin; row0 < r_end; row0 += kThinThreads) {
+    __syncthreads();  // rows of the previous chunk have been read
+#pragma unroll
+    for (int k = 0; k < kMaxQuads; ++k)
+      *reinterpret_cast<f32x4*>(&tile[prow[k] * PS + pcol[k]]) = pf[k];
+    if (row0 + kThinThreads < r_end) load_chunk(row0 + kThinThreads);
+    __syncthreads();
+
+    const int64_t row = row0 + t;
+    const bool valid = row < r_end;
+    float av[PP];
+#pragma unroll
+    for (int q = 0; q < PP / 4; ++q) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(&tile[t * PS + 4 * q]);
+      av[4 * q + 0] = v[0]; av[4 * q + 1] = v[1]; av[4 * q + 2] = v[2]; av[4 * q + 3] = v[3];
+    }
+    float z[NC], w[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) { z[c] = 0.f; w[c] = 0.f; }
+#pragma unroll
+    for (int j = 0; j < PP; ++j) {
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        if (has0) z[c] = fmaf(av[j], a.B0[j * NC + c], z[c]);
+        if (has1) w[c] = fmaf(av[j], a.B1[j * NC + c], w[c]);
+      }
+    }
+    const size_t ro = (size_t)row * NC;
+    if (a.kind == kRowsLogits) {
+      if (valid) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+          if (has0 && a.Z0out) a.Z0out[ro + c] = z[c];
+          if (has1 && a.Z1out) a.Z1out[ro + c] = w[c];
+        }
+      }
+      continue;
+    }
+    float P[NC], d[NC];
+    float M = 0.f, alpha = 1.f;
+    if (has0) {
+#pragma unroll
+      for (int c = 0; c < NC; ++c) M = fmaxf(M, z[c]);
+      alpha = expf(-M);
+#pragma unroll
+      for (int c = 0; c < NC; ++c) { P[c] = expf(z[c] - M); alpha += P[c]; }
+      const float inv = 1.f / alpha;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) P[c] *= inv;
+    } else {
+#pragma unroll
+      for (int c = 0; c < NC; ++c) P[c] = valid ? a.Pin[ro + c] : 0.f;
+    }
+    if (a.kind == kRowsHv) {
+      float tt = 0.f;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) tt = fmaf(P[c], w[c], tt);
+#pragma unroll
+      for (int c = 0; c < NC; ++c) d[c] = valid ? P[c] * (w[c] - tt) : 0.f;
+    } else {
+      const int b = valid ? a.labels[row] : -1;
+      float zb = 0.f;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        if (c == b) zb = z[c];
+        d[c] = valid ? P[c] - (c == b ? 1.f : 0.f) : 0.f;
+      }
+      if (valid) loss_acc += (double)M + (double)logf(alpha) - (double)zb;
+    }
+    if (valid) {
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        if (a.Pout) a.Pout[ro + c] = P[c];
+        if (has0 && a.Z0out) a.Z0out[ro + c] = z[c];
+      }
+    }
+    if (with_cols) {
+#pragma unroll
+      for (int j = 0; j < PP; ++j)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc[j][c] = fmaf(av[j], d[c], acc[j][c]);
+    }
+  }
+
+  // ---- workgroup sums: wave shuffles, then the 4 wave results in order ----
+  __syncthreads();
+  float* wsum = tile;  // [wave][PP*NC]
+  const int lane = t & 63, wave = t >> 6;
+  if (with_cols) {
+#pragma unroll
+    for (int j = 0; j < PP; ++j)
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        float v = acc[j][c];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+        if (lane == 0) wsum[wave * (PP * NC) + j * NC + c] = v;
+      }
+  }
+  if (a.loss_part != nullptr) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) loss_acc += __shfl_down(loss_acc, off, 64);
+    if (lane == 0) red[wave] = loss_acc;
+  }
+  __syncthreads();
+  if (with_cols && t < p * NC) {
+    const float v = ((wsum[t] + wsum[PP * NC + t]) + wsum[2 * PP * NC + t]) + wsum[3 * PP * NC + t];
+    ta.partial[(size_t)blockIdx.x * (p * NC) + t] = v;
+  }
+  if (a.loss_part != nullptr && t == 0) a.loss_part[blockIdx.x] = ((red[0] + red[1]) + red[2]) + red[3];
+}
+
+int lds_stride_of(int p) { return (p % 8 == 0) ? p + 4 : p; }
+
+template <int NQ, int NC>
+hipError_t launch_thin_t(const ThinArgs& ta, int grid, hipStream_t st) {
+  const size_t lds = (size_t)kThinThreads * ta.lds_stride * sizeof(float);
+  hipLaunchKernelGGL((thin_kernel<NQ, NC>), dim3(grid), dim3(kThinThreads), lds, st, ta);
+  return hipGetLastError();
+}
+
+template <int NQ>
+hipError_t launch_thin_nq(const ThinArgs& ta, int grid, hipStream_t st) {
+  switch (ta.r.NC) {
+    case 1: return launch_thin_t<NQ, 1>(ta, grid, st);
+    case 2: return launch_thin_t<NQ, 2>(ta, grid, st);
+    case 3: return launch_thin_t<NQ, 3>(ta, grid, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+bool thin_supported(const Shape& s, int64_t lda, const void* A) {
+  if (s.p > 32 || (s.p & 3) != 0 || s.NC > 3 || s.p * s.NC > 64) return false;
+  if (lda != s.p || (reinterpret_cast<uintptr_t>(A) & 15) != 0) return false;
+  return true;
+}
+
+int thin_num_partials(const Shape& s) {
+  // 3 resident workgroups per compute unit for small accumulator sets, else 2 (register budget);
+  // every workgroup gets the same whole number of 256-row chunks
+  const int64_t cap = (s.p * s.NC <= 32) ? 768 : 512;
+  const int64_t chunks = (s.n + kThinThreads - 1) / kThinThreads;
+  const int64_t g = chunks < cap ? chunks : cap;
+  const int64_t per = (chunks + g - 1) / g;
+  return (int)((chunks + per - 1) / per);
+}
+
+hipError_t launch_thin(const RowArgs& a, float* partial, int nparts, hipStream_t st) {
+  ThinArgs ta;
+  ta.r = a;
+  ta.partial = partial;
+  const int64_t chunks = (a.n + kThinThreads - 1) / kThinThreads;
+  ta.rows_per_wg = (int32_t)((chunks + nparts - 1) / nparts) * kThinThreads;
+  ta.lds_stride = lds_stride_of(a.p);
+  ta.q1024 = 1024 / a.p;
+  ta.r1024 = 1024 % a.p;
+  switch (a.p >> 2) {
+    case 1: return launch_thin_nq<1>(ta, nparts, st);
+    case 2: return launch_thin_nq<2>(ta, nparts, st);
+    case 3: return launch_thin_nq<3>(ta, nparts, st);
+    case 4: return launch_thin_nq<4>(ta, nparts, st);
+    case 5: return launch_thin_nq<5>(ta, nparts, st);
+    case 6: return launch_thin_nq<6>(ta, nparts, st);
+    case 7: return launch_thin_nq<7>(ta, nparts, st);
+    case 8: return launch_thin_nq<8>(ta, nparts, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace nadmm

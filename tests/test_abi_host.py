@@ -124,11 +124,22 @@ def test_line_search_parameters_are_validated(lib, beta, gamma, max_ls, code):
 
 def test_kernel_path_switch(lib):
     prev = lib.nadmm_set_kernel_path(1)
-    assert prev in (0, 1, 2)
+    assert prev in (0, 1, 2, 3)
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem())) == 1
     assert lib.nadmm_set_kernel_path(7) == nadmm.NADMM_EINVAL
+    lib.nadmm_set_kernel_path(0)
+    # automatic selection: thin data -> 3, medium width -> 2, wide or unaligned rows -> 1
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=1000, p=20, Cc=3))) == 3
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=60000, p=784, Cc=10))) == 2
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=50000, p=3072, Cc=10))) == 1
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=5))) == 1
+    # a forced path that cannot take the shape is reported, on the host
+    lib.nadmm_set_kernel_path(3)
+    fake = C.c_void_p(0x3000)
+    wide = fake_problem(n=60000, p=784, Cc=10)
+    need = lib.nadmm_workspace_bytes(C.byref(wide), None)
+    assert lib.nadmm_hessvec(C.byref(wide), fake, fake, fake, fake, need, None) == nadmm.NADMM_EUNSUPPORTED
     lib.nadmm_set_kernel_path(prev)
-    assert lib.nadmm_query_kernel_path(C.byref(fake_problem())) in (1, 2)
 
 
 def test_product_path_does_not_import_the_oracle():
