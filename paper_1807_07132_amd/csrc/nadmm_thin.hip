@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
   __shared__ double red[4];
   const int t = threadIdx.x;
   constexpr int p = PP;
-  const int PS = ta.lds_stride;
+  constexpr int PS = (PP % 8 == 0) ? PP + 4 : PP;  // LDS row stride, off the bank period
   const bool has0 = a.B0 != nullptr;
   const bool has1 = a.B1 != nullptr;
   const bool with_cols = ta.partial != nullptr;
@@ -49,6 +49,16 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
   if (r_end > a.n) r_end = a.n;
   const f32x4* A4 = reinterpret_cast<const f32x4*>(a.A);
   const int64_t last4 = a.n * nquads - 1;  // last float4 of the matrix (lda == p)
+
+  // X and V are the same for every lane: keep them as wave-uniform (scalar) registers
+  float xs[PP][NC], vs[PP][NC];
+#pragma unroll
+  for (int j = 0; j < PP; ++j)
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      xs[j][c] = has0 ? __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.B0[j * NC + c]))) : 0.f;
+      vs[j][c] = has1 ? __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.B1[j * NC + c]))) : 0.f;
+    }
 
   float acc[PP][NC];
 #pragma unroll
@@ -71,24 +81,27 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
     }
   }
 
-  f32x4 pf[kMaxQuads];
-  auto load_chunk = [&](int64_t row0) {
+  // Two chunks are in flight per workgroup: registers pf[0] and pf[1] alternate.  Loads are
+  // unconditional (addresses clamped to the workgroup's own last float4), so the compiler can
+  // wait for exactly the chunk it needs.
+  f32x4 pf[2][kMaxQuads];
+  const int64_t own_last4 = (r_end > r_begin ? r_end : r_begin + 1) * nquads - 1;
+  auto load_chunk = [&](int b, int64_t row0) {
     const int64_t base4 = row0 * nquads + t;
 #pragma unroll
     for (int k = 0; k < kMaxQuads; ++k) {
       int64_t i4 = base4 + (int64_t)k * kThinThreads;
-      i4 = i4 < last4 ? i4 : last4;  // clamp: rows past the end are never used
-      pf[k] = A4[i4];
+      i4 = i4 < own_last4 ? i4 : own_last4;
+      i4 = i4 < last4 ? i4 : last4;
+      pf[b][k] = A4[i4];
     }
   };
-
-  if (r_begin < r_end) load_chunk(r_begin);
-  for (int64_t row0 = r_begin; row0 < r_end; row0 += kThinThreads) {
+  auto process = [&](int b, int64_t row0) {
     __syncthreads();  // rows of the previous chunk have been read
 #pragma unroll
     for (int k = 0; k < kMaxQuads; ++k)
-      *reinterpret_cast<f32x4*>(&tile[prow[k] * PS + pcol[k]]) = pf[k];
-    if (row0 + kThinThreads < r_end) load_chunk(row0 + kThinThreads);
+      *reinterpret_cast<f32x4*>(__builtin_assume_aligned(&tile[prow[k] * PS + pcol[k]], 16)) = pf[b][k];
+    load_chunk(b, row0 + 2 * kThinThreads);
     __syncthreads();
 
     const int64_t row = row0 + t;
@@ -96,19 +109,23 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
     float av[PP];
 #pragma unroll
     for (int q = 0; q < PP / 4; ++q) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(&tile[t * PS + 4 * q]);
+      const f32x4 v = *reinterpret_cast<const f32x4*>(__builtin_assume_aligned(&tile[t * PS + 4 * q], 16));
       av[4 * q + 0] = v[0]; av[4 * q + 1] = v[1]; av[4 * q + 2] = v[2]; av[4 * q + 3] = v[3];
     }
     float z[NC], w[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) { z[c] = 0.f; w[c] = 0.f; }
+    if (has0) {
 #pragma unroll
-    for (int j = 0; j < PP; ++j) {
+      for (int j = 0; j < PP; ++j)
 #pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        if (has0) z[c] = fmaf(av[j], a.B0[j * NC + c], z[c]);
-        if (has1) w[c] = fmaf(av[j], a.B1[j * NC + c], w[c]);
-      }
+        for (int c = 0; c < NC; ++c) z[c] = fmaf(av[j], xs[j][c], z[c]);
+    }
+    if (has1) {
+#pragma unroll
+      for (int j = 0; j < PP; ++j)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) w[c] = fmaf(av[j], vs[j][c], w[c]);
     }
     const size_t ro = (size_t)row * NC;
     if (a.kind == kRowsLogits) {
@@ -119,7 +136,7 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
           if (has1 && a.Z1out) a.Z1out[ro + c] = w[c];
         }
       }
-      continue;
+      return;
     }
     float P[NC], d[NC];
     float M = 0.f, alpha = 1.f;
@@ -165,6 +182,15 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc[j][c] = fmaf(av[j], d[c], acc[j][c]);
     }
+  };
+
+  if (r_begin < r_end) {
+    load_chunk(0, r_begin);
+    load_chunk(1, r_begin + kThinThreads);
+  }
+  for (int64_t row0 = r_begin; row0 < r_end; row0 += 2 * kThinThreads) {
+    process(0, row0);
+    if (row0 + kThinThreads < r_end) process(1, row0 + kThinThreads);
   }
 
   // ---- workgroup sums: wave shuffles, then the 4 wave results in order ----
@@ -238,7 +264,7 @@ hipError_t launch_thin(const RowArgs& a, float* partial, int nparts, hipStream_t
   ta.partial = partial;
   const int64_t chunks = (a.n + kThinThreads - 1) / kThinThreads;
   ta.rows_per_wg = (int32_t)((chunks + nparts - 1) / nparts) * kThinThreads;
-  ta.lds_stride = lds_stride_of(a.p);
+  ta.lds_stride = lds_stride_of(a.p);  // must equal the kernel's compile-time stride
   ta.q1024 = 1024 / a.p;
   ta.r1024 = 1024 % a.p;
   switch (a.p >> 2) {
