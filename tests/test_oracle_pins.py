@@ -331,3 +331,23 @@ def test_forced_alphas_override_the_line_search():
     X1, st = orc.local_newton(prob, X, 1, 5, 0.0, 0.0, 1e-4, 0.5, 10, forced_alphas=[0.25])
     it = st["iters"][0]
     np.testing.assert_allclose(X1, X + 0.25 * it["p"], rtol=1e-15)
+
+
+# ------------------------------------------------------------------ stored oracle values (regression guard)
+def test_stored_tiny_workload_values_are_reproduced():
+    import json
+    import os
+
+    from paper_1807_07132_amd import workloads
+
+    gold = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "tiny_oracle.json")))
+    w = workloads.tiny(0)
+    prob = orc.Problem(w.A, w.b, w.C, s=w.s, lam=w.lam, rho=w.rho, z=w.z, y=w.y)
+    # closed form: X0 = 0 and y = 0, so Fhat = log C + rho/2 ||z||^2 with s = 1/n
+    assert gold["loss_at_X0"] == pytest.approx(math.log(3) + 0.5 * np.sum(w.z.astype(np.float64) ** 2), rel=1e-13)
+    assert orc.loss(prob, w.X0) == pytest.approx(gold["loss_at_X0"], rel=1e-12)
+    np.testing.assert_allclose(orc.grad(prob, w.X0), np.array(gold["grad_at_X0"]), rtol=1e-10, atol=1e-14)
+    np.testing.assert_allclose(orc.hessvec(prob, w.X0, w.V), np.array(gold["hessvec_at_X0"]), rtol=1e-10, atol=1e-14)
+    X1, st = orc.local_newton(prob, w.X0, 1, 10, 0.0, 0.0, w.beta, w.gamma, w.max_ls)
+    np.testing.assert_allclose(X1, np.array(gold["newton_1step_10cg_X"]), rtol=1e-8, atol=1e-12)
+    assert st["iters"][0]["alpha"] == gold["newton_alpha"]
