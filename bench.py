@@ -147,7 +147,7 @@ def main():
     bytes_hv = 4.0 * n * p + 3 * 4.0 * d
     bytes_lg = 4.0 * n * p + 4.0 * n + 4 * 4.0 * d
     extra = {"kernel_path": {1: "two-pass fp32 vector kernels", 2: "fused single pass (matrix cores)",
-                             3: "thin-data single pass"}[path]}
+                             3: "thin-data single pass", 4: "column-sliced two sweeps (matrix cores)"}[path]}
     value = None
     roof = None
     if "hv" in tot:

@@ -166,13 +166,15 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
  *   0 = automatic (default), 1 = two-pass fp32 vector kernels (any shape),
  *   2 = fused single-pass matrix-core kernel (row stride a multiple of 4, A 16-byte aligned,
  *       C-1 <= 16, p <= 960), 3 = thin-data single-pass kernel (p <= 32, p % 4 == 0,
- *       C-1 <= 3, lda == p).  A forced path that does not support the problem makes the
+ *       C-1 <= 3, lda == p), 4 = column-sliced two-sweep matrix-core kernels (the automatic
+ *       choice where 2 and 3 do not apply: row stride a multiple of 4, A 16-byte aligned,
+ *       C-1 <= 32).  A forced path that does not support the problem makes the
  *       compute calls return NADMM_EUNSUPPORTED.
  * Returns the previous value, or NADMM_EINVAL.
  */
 int nadmm_set_kernel_path(int path);
 
-/* Which path (1, 2 or 3) is taken for this problem under the current setting; host-only. */
+/* Which path (1 to 4) is taken for this problem under the current setting; host-only. */
 int nadmm_query_kernel_path(const nadmm_problem* prob);
 
 #ifdef __cplusplus

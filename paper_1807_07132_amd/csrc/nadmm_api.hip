@@ -20,11 +20,11 @@ struct Layout {
   Shape s;
   size_t state, g, pdir, r, dvec, q;
   size_t drows, pcache, zx, zp;
-  size_t partial, loss_part, lpart;
+  size_t partial, loss_part, lpart, zw;
   size_t total;
   int gen_row_blocks, gen_slabs, gen_chunks, gen_rpc;
-  int fused_parts, thin_parts;
-  bool fused_ok, thin_ok;
+  int fused_parts, thin_parts, sliced_parts, sliced_slices;
+  bool fused_ok, thin_ok, sliced_ok;
 };
 
 int validate_problem(const nadmm_problem* p, bool need_labels) {
@@ -65,13 +65,23 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   L->pcache = off; off += rows;
   L->zx = off; off += rows;
   L->zp = off; off += rows;
+  L->sliced_ok = sliced_supported(s, p->lda, p->d_A);
+  L->sliced_parts = 0;
+  L->sliced_slices = 0;
+  if (L->sliced_ok) {
+    int sps = 0;
+    sliced_grid(s, &L->sliced_slices, &sps, &L->sliced_parts);
+  }
   int parts = L->gen_chunks > L->fused_parts ? L->gen_chunks : L->fused_parts;
+  if (L->sliced_parts > parts) parts = L->sliced_parts;
   if (L->thin_parts > parts) parts = L->thin_parts;
   L->partial = off; off += align256((size_t)parts * s.d * sizeof(float));
   int lblocks = L->gen_row_blocks > L->fused_parts ? L->gen_row_blocks : L->fused_parts;
   if (L->thin_parts > lblocks) lblocks = L->thin_parts;
   L->loss_part = off; off += align256((size_t)lblocks * sizeof(double));
   L->lpart = off; off += align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
+  // per-slice partial logits of the column-sliced path (only where that path is the automatic choice)
+  L->zw = off; off += align256((L->sliced_ok && !L->fused_ok && !L->thin_ok) ? sliced_zw_bytes(s) : 0);
   L->total = off;
 }
 
@@ -94,7 +104,8 @@ int hip_fail(hipError_t e) {
     if (e_ != hipSuccess) return hip_fail(e_);   \
   } while (0)
 
-// 1 = two-pass vector kernels, 2 = fused single pass (matrix cores), 3 = thin-data single pass
+// 1 = two-pass vector kernels, 2 = fused single pass (matrix cores), 3 = thin-data single pass,
+// 4 = column-sliced two-sweep matrix-core path
 int choose_path(const Layout& L, int* path) {
   if (g_path == 1) { *path = 1; return NADMM_OK; }
   if (g_path == 2) {
@@ -107,12 +118,17 @@ int choose_path(const Layout& L, int* path) {
     *path = 3;
     return NADMM_OK;
   }
-  *path = L.thin_ok ? 3 : (L.fused_ok ? 2 : 1);
+  if (g_path == 4) {
+    if (!L.sliced_ok || L.fused_ok || L.thin_ok) return NADMM_EUNSUPPORTED;  // workspace is sized for it only there
+    *path = 4;
+    return NADMM_OK;
+  }
+  *path = L.thin_ok ? 3 : (L.fused_ok ? 2 : (L.sliced_ok ? 4 : 1));
   return NADMM_OK;
 }
 
 int loss_blocks(const Layout& L, int path) {
-  return path == 3 ? L.thin_parts : (path == 2 ? L.fused_parts : L.gen_row_blocks);
+  return path == 3 ? L.thin_parts : (path == 2 ? L.fused_parts : L.gen_row_blocks);  // paths 1 and 4: row blocks
 }
 
 // One sweep over A: rows pass, and (if with_cols) partial sums of A^T rows_out.
@@ -131,6 +147,15 @@ int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArg
   if (path == 3) {
     NADMM_HIP(launch_thin(ra, with_cols ? at<float>(ws, L.partial) : nullptr, L.thin_parts, st));
     *nparts = L.thin_parts;
+    return NADMM_OK;
+  }
+  if (path == 4) {
+    NADMM_HIP(launch_sliced_logits(ra, at<float>(ws, L.zw), st));
+    NADMM_HIP(launch_logit_rows(ra, at<float>(ws, L.zw), L.sliced_slices, st));
+    if (with_cols) {
+      NADMM_HIP(launch_sliced_cols(ra, ra.rows_out, at<float>(ws, L.partial), st));
+      *nparts = L.sliced_parts;
+    }
     return NADMM_OK;
   }
   NADMM_HIP(launch_generic_rows(ra, st));
@@ -232,7 +257,7 @@ const char* nadmm_status_string(int code) {
 const char* nadmm_last_hip_error(void) { return g_last_hip_error.c_str(); }
 
 int nadmm_set_kernel_path(int path) {
-  if (path < 0 || path > 3) return NADMM_EINVAL;
+  if (path < 0 || path > 4) return NADMM_EINVAL;
   const int prev = g_path;
   g_path = path;
   return prev;

@@ -19,6 +19,7 @@
 // (x = hi + lo + O(2^-18 |x|)), and each product uses the three MFMA terms
 // hi*hi + hi*lo + lo*hi with fp32 accumulation (v_mfma_f32_16x16x32_bf16).
 #include "nadmm_internal.h"
+#include "nadmm_mfma.h"
 
 #ifndef NADMM_EXP
 #define NADMM_EXP 0  // timing experiments only (non-zero values skip work and give wrong results)
@@ -26,6 +27,8 @@
 
 namespace nadmm {
 namespace {
+
+using namespace mfma_detail;
 
 __device__ __forceinline__ void tile_barrier() {
   if (NADMM_EXP != 4 && NADMM_EXP != 5) __syncthreads();
@@ -40,74 +43,12 @@ constexpr int kStepBytes = 4096;              // hi plane 2 KB + lo plane 2 KB
 constexpr int kPartBytes = kWaves * 4 * 64 * 16;
 constexpr int kSumBytes = 8 * 64 * 4;    // exchange buffer of the rows stage
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-
 struct FusedArgs {
   RowArgs r;
   float* partial;     // gridDim.x x (p*NC) or NULL (no transpose product)
   int32_t steps;      // ceil(p / 32)
   int32_t rows_per_wg;
 };
-
-__device__ __forceinline__ unsigned pack2(float a, float b) {  // round-to-nearest-even, a in the low half
-  bf16x2 v = {(__bf16)a, (__bf16)b};
-  unsigned r = __builtin_bit_cast(unsigned, v);
-  asm volatile("" : "+v"(r));  // keep the packed conversion as one instruction (no per-half re-conversion)
-  return r;
-}
-__device__ __forceinline__ float low_as_float(unsigned h) { return __uint_as_float(h << 16); }
-__device__ __forceinline__ float high_as_float(unsigned h) { return __uint_as_float(h & 0xffff0000u); }
-
-// 8 floats -> packed bf16 high parts and packed bf16 residuals
-__device__ __forceinline__ void split8(const float (&a)[8], u32x4& hi, u32x4& lo) {
-  unsigned h[4], l[4];
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    h[k] = pack2(a[2 * k], a[2 * k + 1]);
-    l[k] = pack2(a[2 * k] - low_as_float(h[k]), a[2 * k + 1] - high_as_float(h[k]));
-  }
-  hi = u32x4{h[0], h[1], h[2], h[3]};
-  lo = u32x4{l[0], l[1], l[2], l[3]};
-}
-
-__device__ __forceinline__ f32x4 mfma(u32x4 a, u32x4 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
-// c += (ahi + alo) (bhi + blo) without the lo*lo term
-__device__ __forceinline__ f32x4 mfma3(u32x4 ahi, u32x4 alo, u32x4 bhi, u32x4 blo, f32x4 c) {
-  c = mfma(alo, bhi, c);
-  c = mfma(ahi, blo, c);
-  return mfma(ahi, bhi, c);
-}
-
-template <int N>
-__device__ __forceinline__ float row_ror(float v) {  // rotate within each group of 16 lanes
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xf, 0xf, false));
-}
-__device__ __forceinline__ float row16_sum(float v) {
-  v += row_ror<8>(v);
-  v += row_ror<4>(v);
-  v += row_ror<2>(v);
-  v += row_ror<1>(v);
-  return v;
-}
-__device__ __forceinline__ float row16_max(float v) {
-  v = fmaxf(v, row_ror<8>(v));
-  v = fmaxf(v, row_ror<4>(v));
-  v = fmaxf(v, row_ror<2>(v));
-  v = fmaxf(v, row_ror<1>(v));
-  return v;
-}
-
-// LDS offset (bytes, within one 2 KB plane of a step) of column q (0..31), 16-byte chunk ck (0..3)
-__device__ __forceinline__ int cm_offset(int q, int ck) {
-  const int qs = q ^ ((q >> 3) & 1);
-  const int g = (qs >> 1) & 3;
-  return qs * 64 + ((ck ^ g) << 4);
-}
 
 template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES>
 __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {

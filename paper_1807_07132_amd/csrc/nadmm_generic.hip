@@ -29,6 +29,77 @@ __device__ __forceinline__ double block_sum_double(double v, double* sm /* >= 4 
   return t;
 }
 
+// Rows stage shared by the kernels that end with one lane holding the logits of one sample:
+// probabilities with the log-sum-exp shift (Sections 2.2, 2.6), the row of D or of P - Y, the row loss,
+// optional stores of P and of the logits.  Returns the row loss (0 for kinds without one).
+template <int NCP>
+__device__ __forceinline__ double finish_row(const RowArgs& a, int64_t row, bool valid, bool has0, bool has1,
+                                             const float (&z)[NCP], const float (&w)[NCP]) {
+  const int NC = a.NC;
+  const size_t ro = (size_t)row * NC;
+  if (a.kind == kRowsLogits) {
+    if (valid) {
+#pragma unroll
+      for (int c = 0; c < NCP; ++c)
+        if (c < NC) {
+          if (has0 && a.Z0out) a.Z0out[ro + c] = z[c];
+          if (has1 && a.Z1out) a.Z1out[ro + c] = w[c];
+        }
+    }
+    return 0.0;
+  }
+  float P[NCP];
+  float M = 0.f, alpha = 1.f;
+  if (has0) {
+#pragma unroll
+    for (int c = 0; c < NCP; ++c)
+      if (c < NC) M = fmaxf(M, z[c]);
+    alpha = expf(-M);
+#pragma unroll
+    for (int c = 0; c < NCP; ++c) {
+      P[c] = (c < NC) ? expf(z[c] - M) : 0.f;
+      alpha += P[c];
+    }
+    const float inv = 1.f / alpha;
+#pragma unroll
+    for (int c = 0; c < NCP; ++c) P[c] *= inv;
+  } else {
+#pragma unroll
+    for (int c = 0; c < NCP; ++c) P[c] = (valid && c < NC) ? a.Pin[ro + c] : 0.f;
+  }
+  if (a.kind == kRowsHv) {
+    float t = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCP; ++c) t = fmaf(P[c], w[c], t);
+    if (valid) {
+#pragma unroll
+      for (int c = 0; c < NCP; ++c)
+        if (c < NC) {
+          a.rows_out[ro + c] = P[c] * (w[c] - t);
+          if (a.Pout) a.Pout[ro + c] = P[c];
+        }
+    }
+    return 0.0;
+  }
+  double ell = 0.0;
+  if (valid) {
+    const int b = a.labels[row];
+    float zb = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCP; ++c)
+      if (c < NC && c == b) zb = z[c];
+    ell = (double)M + (double)logf(alpha) - (double)zb;
+#pragma unroll
+    for (int c = 0; c < NCP; ++c)
+      if (c < NC) {
+        if (a.kind == kRowsGrad && a.rows_out) a.rows_out[ro + c] = P[c] - (c == b ? 1.f : 0.f);
+        if (a.Pout) a.Pout[ro + c] = P[c];
+        if (a.Z0out) a.Z0out[ro + c] = z[c];
+      }
+  }
+  return ell;
+}
+
 template <int NCP>
 __global__ __launch_bounds__(kRowsPerBlock) void rows_kernel(const RowArgs a) {
   if (a.flag != nullptr && *a.flag == 0) return;
@@ -79,73 +150,40 @@ __global__ __launch_bounds__(kRowsPerBlock) void rows_kernel(const RowArgs a) {
   }
 
   const bool valid = row < a.n;
-  const size_t ro = (size_t)row * NC;
-  double ell = 0.0;
+  const double ell = finish_row<NCP>(a, row, valid, has0, has1, z, w);
+  if (a.kind != kRowsGrad && a.kind != kRowsLoss) return;
+  const double tot = block_sum_double(ell, red);
+  if (threadIdx.x == 0) a.loss_part[blockIdx.x] = tot;
+}
 
-  if (a.kind == kRowsLogits) {
-    if (valid) {
+// Rows stage on logits that were computed elsewhere: the column-sliced matrix-core pass leaves one partial
+// n x 2 x (C-1) array [Z | W] per column slice; this kernel adds the slices in order and finishes the rows.
+template <int NCP>
+__global__ __launch_bounds__(kRowsPerBlock) void logit_rows_kernel(const RowArgs a, const float* __restrict__ zw,
+                                                                    int nslices) {
+  if (a.flag != nullptr && *a.flag == 0) return;
+  __shared__ double red[4];
+  const int NC = a.NC;
+  const bool has0 = a.B0 != nullptr;
+  const bool has1 = a.B1 != nullptr;
+  const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x;
+  const bool valid = row < a.n;
+  float z[NCP], w[NCP];
 #pragma unroll
-      for (int c = 0; c < NCP; ++c)
-        if (c < NC) {
-          if (has0 && a.Z0out) a.Z0out[ro + c] = z[c];
-          if (has1 && a.Z1out) a.Z1out[ro + c] = w[c];
-        }
-    }
-    return;
-  }
-
-  // probabilities of the free classes: P_c = exp(Z_c - M) / alpha (Sections 2.2, 2.6)
-  float P[NCP];
-  float M = 0.f, alpha = 1.f;
-  if (has0) {
-#pragma unroll
-    for (int c = 0; c < NCP; ++c)
-      if (c < NC) M = fmaxf(M, z[c]);
-    alpha = expf(-M);
-#pragma unroll
-    for (int c = 0; c < NCP; ++c) {
-      P[c] = (c < NC) ? expf(z[c] - M) : 0.f;
-      alpha += P[c];
-    }
-    const float inv = 1.f / alpha;
-#pragma unroll
-    for (int c = 0; c < NCP; ++c) P[c] *= inv;
-  } else {
-#pragma unroll
-    for (int c = 0; c < NCP; ++c) P[c] = (valid && c < NC) ? a.Pin[ro + c] : 0.f;
-  }
-
-  if (a.kind == kRowsHv) {
-    float t = 0.f;
-#pragma unroll
-    for (int c = 0; c < NCP; ++c) t = fmaf(P[c], w[c], t);
-    if (valid) {
-#pragma unroll
-      for (int c = 0; c < NCP; ++c)
-        if (c < NC) {
-          a.rows_out[ro + c] = P[c] * (w[c] - t);
-          if (a.Pout) a.Pout[ro + c] = P[c];
-        }
-    }
-    return;
-  }
-
-  // kinds kRowsGrad / kRowsLoss
+  for (int c = 0; c < NCP; ++c) { z[c] = 0.f; w[c] = 0.f; }
   if (valid) {
-    const int b = a.labels[row];
-    float zb = 0.f;
+    for (int s = 0; s < nslices; ++s) {
+      const float* src = zw + ((size_t)s * a.n + row) * 2 * NC;
 #pragma unroll
-    for (int c = 0; c < NCP; ++c)
-      if (c < NC && c == b) zb = z[c];
-    ell = (double)M + (double)logf(alpha) - (double)zb;
-#pragma unroll
-    for (int c = 0; c < NCP; ++c)
-      if (c < NC) {
-        if (a.kind == kRowsGrad && a.rows_out) a.rows_out[ro + c] = P[c] - (c == b ? 1.f : 0.f);
-        if (a.Pout) a.Pout[ro + c] = P[c];
-        if (a.Z0out) a.Z0out[ro + c] = z[c];
-      }
+      for (int c = 0; c < NCP; ++c)
+        if (c < NC) {
+          if (has0) z[c] += src[c];
+          if (has1) w[c] += src[NC + c];
+        }
+    }
   }
+  const double ell = finish_row<NCP>(a, row, valid, has0, has1, z, w);
+  if (a.kind != kRowsGrad && a.kind != kRowsLoss) return;
   const double tot = block_sum_double(ell, red);
   if (threadIdx.x == 0) a.loss_part[blockIdx.x] = tot;
 }
@@ -223,6 +261,15 @@ hipError_t launch_generic_rows(const RowArgs& a, hipStream_t st) {
   return dispatch_ncp(a.NC, [&](auto ncp) {
     constexpr int NCP = decltype(ncp)::value;
     hipLaunchKernelGGL(rows_kernel<NCP>, dim3(blocks), dim3(kRowsPerBlock), 0, st, a);
+    return hipGetLastError();
+  });
+}
+
+hipError_t launch_logit_rows(const RowArgs& a, const float* zw, int nslices, hipStream_t st) {
+  const int blocks = generic_row_blocks(a.n);
+  return dispatch_ncp(a.NC, [&](auto ncp) {
+    constexpr int NCP = decltype(ncp)::value;
+    hipLaunchKernelGGL(logit_rows_kernel<NCP>, dim3(blocks), dim3(kRowsPerBlock), 0, st, a, zw, nslices);
     return hipGetLastError();
   });
 }

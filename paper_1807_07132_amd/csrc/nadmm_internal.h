@@ -83,6 +83,8 @@ int generic_row_blocks(int64_t n);
 void generic_col_grid(const Shape& s, int* nslabs, int* nchunks, int* rows_per_chunk);
 hipError_t launch_generic_rows(const RowArgs& a, hipStream_t st);
 hipError_t launch_generic_cols(const ColArgs& a, int nslabs, int nchunks, hipStream_t st);
+// rows stage on per-slice partial logits zw[slice][row][Z|W][C-1]; partial losses per block of generic_row_blocks()
+hipError_t launch_logit_rows(const RowArgs& a, const float* zw, int nslices, hipStream_t st);
 
 // ---- vector / tail kernels (nadmm_vec.hip) ----
 struct ReduceArgs {
@@ -207,5 +209,12 @@ hipError_t launch_fused(const RowArgs& a, float* partial, int nparts, hipStream_
 bool thin_supported(const Shape& s, int64_t lda, const void* A);
 int thin_num_partials(const Shape& s);
 hipError_t launch_thin(const RowArgs& a, float* partial, int nparts, hipStream_t st);
+
+// ---- column-sliced two-sweep matrix-core path (nadmm_sliced.hip): any p, C-1 <= 32, lda % 4 == 0 ----
+bool sliced_supported(const Shape& s, int64_t lda, const void* A);
+void sliced_grid(const Shape& s, int* nslices, int* steps_per_slice, int* row_groups);
+size_t sliced_zw_bytes(const Shape& s);
+hipError_t launch_sliced_logits(const RowArgs& a, float* zw, hipStream_t st);
+hipError_t launch_sliced_cols(const RowArgs& a, const float* rows_in, float* partial, hipStream_t st);
 
 }  // namespace nadmm

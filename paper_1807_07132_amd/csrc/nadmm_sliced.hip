@@ -1,0 +1,463 @@
+// Column-sliced matrix-core path for wide data and for up to 32 free classes (gfx950).
+//
+// When the p x (C-1) operands and accumulators of a whole row no longer fit one compute unit
+// (p > 960 or C-1 > 16), the columns are cut into slices of at most 24 steps of 32 columns and the
+// Hessian-vector product of Section 2.6 (or the gradient A^T (P - Y)) is taken in two sweeps over A:
+//   sweep 1  every workgroup (slice, row range) forms its slice's share of the logits
+//            Z|W = A[:, slice] [X|V][slice, :] with bf16-split MFMAs and writes it per slice;
+//   rows     a small kernel adds the slices and forms P, D, the row losses (nadmm_generic.hip);
+//   sweep 2  every workgroup forms out^T[:, slice] += D^T A[:, slice] for its row range; the tile is
+//            transposed through a wave-private swizzled LDS copy; no workgroup barrier is needed.
+// Operand layouts, the bf16 high/low split and the three-term product are those of the fused kernel.
+#include "nadmm_internal.h"
+#include "nadmm_mfma.h"
+
+namespace nadmm {
+namespace {
+
+using namespace mfma_detail;
+
+constexpr int kThreads = 512;
+constexpr int kWaves = 8;
+constexpr int kTileRows = 32;
+constexpr int kStepCols = 32;
+constexpr int kSliceSteps = 24;   // at most 3 steps per wave
+constexpr int kStepBytes = 4096;
+
+struct SlicedArgs {
+  RowArgs r;
+  float* zw;             // sweep 1 out: [slice][n][2][NC]
+  const float* rows_in;  // sweep 2 in:  [n][NC]
+  float* partial;        // sweep 2 out: [row group][p*NC]
+  int32_t steps_total;   // ceil(p / 32)
+  int32_t steps_per_slice;
+  int32_t rows_per_wg;
+};
+
+// Loads of one step (2 row blocks x 8 columns per lane), addresses clamped into the matrix.
+__device__ __forceinline__ void load_step_regs(const RowArgs& a, float4 (&pf)[2][2], int64_t row0, int64_t r_end,
+                                               int col, int col_max, int m) {
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    int64_t row = row0 + m + 16 * rb;
+    row = row < r_end ? row : r_end - 1;
+    const float* src = a.A + row * a.lda;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int c0 = col + 4 * h;
+      pf[rb][h] = *reinterpret_cast<const float4*>(src + (c0 < col_max ? c0 : col_max));
+    }
+  }
+}
+
+// Registers of one step -> bf16 high/low operands of both row blocks; columns past p are zeroed.
+__device__ __forceinline__ void convert_step(const float4 (&pf)[2][2], int col, int col_max, int p, bool ragged,
+                                             u32x4 (&ahi)[2], u32x4 (&alo)[2]) {
+  float av[2][8];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    av[rb][0] = pf[rb][0].x; av[rb][1] = pf[rb][0].y; av[rb][2] = pf[rb][0].z; av[rb][3] = pf[rb][0].w;
+    av[rb][4] = pf[rb][1].x; av[rb][5] = pf[rb][1].y; av[rb][6] = pf[rb][1].z; av[rb][7] = pf[rb][1].w;
+  }
+  if (ragged) {  // uniform branch: only the step that contains column p
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int c0 = col + 4 * h;
+      const int nv = c0 <= col_max ? p - c0 : 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        av[0][4 * h + e] = e < nv ? av[0][4 * h + e] : 0.f;
+        av[1][4 * h + e] = e < nv ? av[1][4 * h + e] : 0.f;
+      }
+    }
+  }
+  split8(av[0], ahi[0], alo[0]);
+  split8(av[1], ahi[1], alo[1]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// sweep 1: partial logits of one column slice
+// ------------------------------------------------------------------------------------------------
+template <int SPW, int NB, bool HAS0, bool HAS1>
+__global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs sa) {
+  const RowArgs& a = sa.r;
+  if (a.flag != nullptr && *a.flag == 0) return;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  float* part = reinterpret_cast<float*>(lds);  // [wave][quad (mat, nb, rb)][comp][lane]
+  constexpr int kQuads = 2 * NB * 2;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m = lane & 15, kg = lane >> 4;
+  const int NC = a.NC, p = a.p;
+  const int slice = blockIdx.x;
+  const int step0 = slice * sa.steps_per_slice;
+  int nsteps = sa.steps_total - step0;
+  if (nsteps > sa.steps_per_slice) nsteps = sa.steps_per_slice;
+  const int col_max = (int)a.lda - 4;
+
+  const int64_t r_begin = (int64_t)blockIdx.y * sa.rows_per_wg;
+  int64_t r_end = r_begin + sa.rows_per_wg;
+  if (r_end > a.n) r_end = a.n;
+  if (r_begin >= r_end) return;
+
+  auto step_exists = [&](int i) { return wave + kWaves * i < nsteps; };
+  auto col_of = [&](int i) { return kStepCols * (step0 + wave + kWaves * i) + 8 * kg; };
+
+  float4 pf[SPW][2][2];
+#pragma unroll
+  for (int i = 0; i < SPW; ++i)
+    if (step_exists(i)) load_step_regs(a, pf[i], r_begin, r_end, col_of(i), col_max, m);
+
+  // operands [X|V] of this wave's steps: hi / lo, per class block
+  u32x4 bx_hi[SPW][NB], bx_lo[SPW][NB], bv_hi[SPW][NB], bv_lo[SPW][NB];
+#pragma unroll
+  for (int i = 0; i < SPW; ++i)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int cls = 16 * nb + m;
+      const bool cvn = cls < NC;
+      const int clc = cvn ? cls : NC - 1;
+      float x[8], v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int j = col_of(i) + e;
+        const size_t idx = (size_t)(j < p ? j : p - 1) * NC + clc;
+        const bool ok = cvn && j < p && step_exists(i);
+        const float xv = HAS0 ? a.B0[idx] : 0.f;
+        const float vv = HAS1 ? a.B1[idx] : 0.f;
+        x[e] = ok ? xv : 0.f;
+        v[e] = ok ? vv : 0.f;
+      }
+      split8(x, bx_hi[i][nb], bx_lo[i][nb]);
+      split8(v, bv_hi[i][nb], bv_lo[i][nb]);
+    }
+
+  for (int64_t row0 = r_begin; row0 < r_end; row0 += kTileRows) {
+    f32x4 accZ[NB][2], accW[NB][2];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      accZ[nb][0] = accZ[nb][1] = accW[nb][0] = accW[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int i = 0; i < SPW; ++i) {
+      if (step_exists(i)) {
+        const int col = col_of(i);
+        u32x4 ahi[2], alo[2];
+        convert_step(pf[i], col, col_max, p, kStepCols * (step0 + wave + kWaves * i + 1) > p, ahi, alo);
+        load_step_regs(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb) {
+            if (HAS0) accZ[nb][rb] = mfma3(ahi[rb], alo[rb], bx_hi[i][nb], bx_lo[i][nb], accZ[nb][rb]);
+            if (HAS1) accW[nb][rb] = mfma3(ahi[rb], alo[rb], bv_hi[i][nb], bv_lo[i][nb], accW[nb][rb]);
+          }
+      }
+    }
+    // K-split partials: quad index = (mat * NB + nb) * 2 + rb
+    {
+      float* pw = part + (size_t)(wave * kQuads * 4) * 64 + lane;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (HAS0) pw[(((0 * NB + nb) * 2 + rb) * 4 + e) * 64] = accZ[nb][rb][e];
+            if (HAS1) pw[(((1 * NB + nb) * 2 + rb) * 4 + e) * 64] = accW[nb][rb][e];
+          }
+    }
+    __syncthreads();
+    // wave e adds the 8 partials of rows row0 + 4 kg + (e & 3) + 16 (e >> 2) and stores its slice share
+    {
+      const int rb = wave >> 2, comp = wave & 3;
+      const int64_t my_row = row0 + 4 * kg + comp + 16 * rb;
+      if (my_row < r_end) {
+        float* dst = sa.zw + ((size_t)slice * a.n + my_row) * 2 * NC;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const int cls = 16 * nb + m;
+          float z = 0.f, w = 0.f;
+#pragma unroll
+          for (int sw = 0; sw < kWaves; ++sw) {
+            const float* pr = part + (size_t)(sw * kQuads * 4) * 64 + lane;
+            if (HAS0) z += pr[(((0 * NB + nb) * 2 + rb) * 4 + comp) * 64];
+            if (HAS1) w += pr[(((1 * NB + nb) * 2 + rb) * 4 + comp) * 64];
+          }
+          if (cls < NC) {
+            if (HAS0) dst[cls] = z;
+            if (HAS1) dst[NC + cls] = w;
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// sweep 2: out^T[:, slice] += D^T A[:, slice]
+// ------------------------------------------------------------------------------------------------
+template <int SPW, int NB>
+__global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs sa) {
+  const RowArgs& a = sa.r;
+  if (a.flag != nullptr && *a.flag == 0) return;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  char* cm = lds;  // steps_per_slice x 4 KB, step owned by wave (step % 8): wave-private
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m = lane & 15, kg = lane >> 4;
+  const int NC = a.NC, p = a.p;
+  const int slice = blockIdx.x;
+  const int step0 = slice * sa.steps_per_slice;
+  int nsteps = sa.steps_total - step0;
+  if (nsteps > sa.steps_per_slice) nsteps = sa.steps_per_slice;
+  const int col_max = (int)a.lda - 4;
+
+  const int64_t r_begin = (int64_t)blockIdx.y * sa.rows_per_wg;
+  int64_t r_end = r_begin + sa.rows_per_wg;
+  if (r_end > a.n) r_end = a.n;
+
+  auto step_exists = [&](int i) { return wave + kWaves * i < nsteps; };
+  auto col_of = [&](int i) { return kStepCols * (step0 + wave + kWaves * i) + 8 * kg; };
+
+  f32x4 acc2[SPW][2][NB];
+#pragma unroll
+  for (int i = 0; i < SPW; ++i)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc2[i][h][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // D entries of this lane: class 16 nb + m, rows row0 + 4 kg + (e & 3) + 16 (e >> 2), e = 0..7
+  float dn[NB][8];
+  auto load_d = [&](int64_t row0) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int cls = 16 * nb + m;
+      const int clc = cls < NC ? cls : NC - 1;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        int64_t row = row0 + 4 * kg + (e & 3) + ((e >> 2) << 4);
+        row = row < r_end ? row : r_end - 1;
+        dn[nb][e] = sa.rows_in[(size_t)row * NC + clc];
+      }
+    }
+  };
+
+  float4 pf[SPW][2][2];
+  if (r_begin < r_end) {
+#pragma unroll
+    for (int i = 0; i < SPW; ++i)
+      if (step_exists(i)) load_step_regs(a, pf[i], r_begin, r_end, col_of(i), col_max, m);
+    load_d(r_begin);
+  }
+
+  for (int64_t row0 = r_begin; row0 < r_end; row0 += kTileRows) {
+    // this tile's D operand (rows past the range and padded classes contribute nothing)
+    u32x4 dhi[NB], dlo[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const bool cvn = 16 * nb + m < NC;
+      unsigned h[4], l[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool v0 = cvn && row0 + 4 * kg + e < r_end;
+        const bool v1 = cvn && row0 + 16 + 4 * kg + e < r_end;
+        const float d0 = v0 ? dn[nb][e] : 0.f, d1 = v1 ? dn[nb][4 + e] : 0.f;
+        h[e] = pack2(d0, d1);
+        l[e] = pack2(d0 - low_as_float(h[e]), d1 - high_as_float(h[e]));
+      }
+      dhi[nb] = u32x4{h[0], h[1], h[2], h[3]};
+      dlo[nb] = u32x4{l[0], l[1], l[2], l[3]};
+    }
+    load_d(row0 + kTileRows);  // next tile's D (clamped rows)
+
+#pragma unroll
+    for (int i = 0; i < SPW; ++i) {
+      if (step_exists(i)) {
+        const int col = col_of(i);
+        const int sl = wave + kWaves * i;  // step inside the slice
+        u32x4 ahi[2], alo[2];
+        convert_step(pf[i], col, col_max, p, kStepCols * (step0 + sl + 1) > p, ahi, alo);
+        load_step_regs(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
+        char* base = cm + (size_t)sl * kStepBytes;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          const unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
+          const unsigned hp = __builtin_amdgcn_perm(ahi[1][c >> 1], ahi[0][c >> 1], sel);
+          const unsigned lp = __builtin_amdgcn_perm(alo[1][c >> 1], alo[0][c >> 1], sel);
+          const int off = cm_offset(8 * kg + c, m >> 2) + ((m & 3) << 2);
+          *reinterpret_cast<unsigned*>(base + off) = hp;
+          *reinterpret_cast<unsigned*>(base + 2048 + off) = lp;
+        }
+        // LDS operations of one wave execute in order: the copy just written is read back transposed
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int off = cm_offset(16 * h + m, kg);
+          const u32x4 thi = *reinterpret_cast<const u32x4*>(base + off);
+          const u32x4 tlo = *reinterpret_cast<const u32x4*>(base + 2048 + off);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) acc2[i][h][nb] = mfma3(dhi[nb], dlo[nb], thi, tlo, acc2[i][h][nb]);
+        }
+      }
+    }
+  }
+
+  float* out = sa.partial + (size_t)blockIdx.y * ((size_t)p * NC);
+#pragma unroll
+  for (int i = 0; i < SPW; ++i) {
+    if (step_exists(i)) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int j = kStepCols * (step0 + wave + kWaves * i) + 16 * h + m;
+        if (j < p) {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int c = 16 * nb + 4 * kg + e;
+              if (c < NC) out[(size_t)j * NC + c] = acc2[i][h][nb][e];
+            }
+        }
+      }
+    }
+  }
+}
+
+template <typename K>
+hipError_t set_lds_limit(K kernel) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             160 * 1024);
+}
+
+template <int SPW, int NB, bool HAS0, bool HAS1>
+hipError_t launch_logits_t(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
+  const size_t lds = (size_t)kWaves * (2 * NB * 2) * 4 * 64 * sizeof(float);
+  static bool once = false;
+  if (!once) {
+    hipError_t e = set_lds_limit(&slice_logits_kernel<SPW, NB, HAS0, HAS1>);
+    if (e != hipSuccess) return e;
+    once = true;
+  }
+  hipLaunchKernelGGL((slice_logits_kernel<SPW, NB, HAS0, HAS1>), grid, dim3(kThreads), lds, st, sa);
+  return hipGetLastError();
+}
+
+template <int SPW, int NB>
+hipError_t launch_logits_nb(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
+  const bool h0 = sa.r.B0 != nullptr, h1 = sa.r.B1 != nullptr;
+  if (h0 && h1) return launch_logits_t<SPW, NB, true, true>(sa, grid, st);
+  if (h1) return launch_logits_t<SPW, NB, false, true>(sa, grid, st);
+  if (h0) return launch_logits_t<SPW, NB, true, false>(sa, grid, st);
+  return hipErrorInvalidValue;
+}
+
+template <int SPW, int NB>
+hipError_t launch_cols_t(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
+  const size_t lds = (size_t)sa.steps_per_slice * kStepBytes;
+  static bool once = false;
+  if (!once) {
+    hipError_t e = set_lds_limit(&slice_cols_kernel<SPW, NB>);
+    if (e != hipSuccess) return e;
+    once = true;
+  }
+  hipLaunchKernelGGL((slice_cols_kernel<SPW, NB>), grid, dim3(kThreads), lds, st, sa);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool sliced_supported(const Shape& s, int64_t lda, const void* A) {
+  if (s.NC > 32) return false;
+  if ((lda & 3) != 0 || (reinterpret_cast<uintptr_t>(A) & 15) != 0) return false;
+  return true;
+}
+
+void sliced_grid(const Shape& s, int* nslices, int* steps_per_slice, int* row_groups) {
+  const int steps = (s.p + kStepCols - 1) / kStepCols;
+  const int S = (steps + kSliceSteps - 1) / kSliceSteps;
+  const int sps = (steps + S - 1) / S;
+  const int64_t tiles = (s.n + kTileRows - 1) / kTileRows;
+  int64_t rg = 256 / S;
+  if (rg < 1) rg = 1;
+  if (rg > tiles) rg = tiles;
+  *nslices = (steps + sps - 1) / sps;
+  *steps_per_slice = sps;
+  *row_groups = (int)rg;
+}
+
+size_t sliced_zw_bytes(const Shape& s) {
+  int S, sps, rg;
+  sliced_grid(s, &S, &sps, &rg);
+  return (size_t)S * s.n * 2 * s.NC * sizeof(float);
+}
+
+static SlicedArgs make_args(const RowArgs& a) {
+  SlicedArgs sa;
+  sa.r = a;
+  sa.zw = nullptr;
+  sa.rows_in = nullptr;
+  sa.partial = nullptr;
+  sa.steps_total = (a.p + kStepCols - 1) / kStepCols;
+  return sa;
+}
+
+hipError_t launch_sliced_logits(const RowArgs& a, float* zw, hipStream_t st) {
+  Shape s{a.n, a.p, a.NC, (int64_t)a.p * a.NC};
+  int S, sps, rg;
+  sliced_grid(s, &S, &sps, &rg);
+  SlicedArgs sa = make_args(a);
+  sa.zw = zw;
+  sa.steps_per_slice = sps;
+  sa.rows_per_wg = (int32_t)((a.n + rg - 1) / rg);
+  const dim3 grid(S, rg);
+  const int spw = (sps + kWaves - 1) / kWaves;
+  const int nb = a.NC > 16 ? 2 : 1;
+  if (nb == 1) {
+    switch (spw) {
+      case 1: return launch_logits_nb<1, 1>(sa, grid, st);
+      case 2: return launch_logits_nb<2, 1>(sa, grid, st);
+      case 3: return launch_logits_nb<3, 1>(sa, grid, st);
+    }
+  } else {
+    switch (spw) {
+      case 1: return launch_logits_nb<1, 2>(sa, grid, st);
+      case 2: return launch_logits_nb<2, 2>(sa, grid, st);
+      case 3: return launch_logits_nb<3, 2>(sa, grid, st);
+    }
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_sliced_cols(const RowArgs& a, const float* rows_in, float* partial, hipStream_t st) {
+  Shape s{a.n, a.p, a.NC, (int64_t)a.p * a.NC};
+  int S, sps, rg;
+  sliced_grid(s, &S, &sps, &rg);
+  SlicedArgs sa = make_args(a);
+  sa.rows_in = rows_in;
+  sa.partial = partial;
+  sa.steps_per_slice = sps;
+  sa.rows_per_wg = (int32_t)((a.n + rg - 1) / rg);
+  const dim3 grid(S, rg);
+  const int spw = (sps + kWaves - 1) / kWaves;
+  const int nb = a.NC > 16 ? 2 : 1;
+  if (nb == 1) {
+    switch (spw) {
+      case 1: return launch_cols_t<1, 1>(sa, grid, st);
+      case 2: return launch_cols_t<2, 1>(sa, grid, st);
+      case 3: return launch_cols_t<3, 1>(sa, grid, st);
+    }
+  } else {
+    switch (spw) {
+      case 1: return launch_cols_t<1, 2>(sa, grid, st);
+      case 2: return launch_cols_t<2, 2>(sa, grid, st);
+      case 3: return launch_cols_t<3, 2>(sa, grid, st);
+    }
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace nadmm

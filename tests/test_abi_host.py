@@ -124,14 +124,15 @@ def test_line_search_parameters_are_validated(lib, beta, gamma, max_ls, code):
 
 def test_kernel_path_switch(lib):
     prev = lib.nadmm_set_kernel_path(1)
-    assert prev in (0, 1, 2, 3)
+    assert prev in (0, 1, 2, 3, 4)
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem())) == 1
     assert lib.nadmm_set_kernel_path(7) == nadmm.NADMM_EINVAL
     lib.nadmm_set_kernel_path(0)
-    # automatic selection: thin data -> 3, medium width -> 2, wide or unaligned rows -> 1
+    # automatic selection: thin data -> 3, medium width -> 2, wide or many classes -> 4, unaligned rows -> 1
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=1000, p=20, Cc=3))) == 3
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=60000, p=784, Cc=10))) == 2
-    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=50000, p=3072, Cc=10))) == 1
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=50000, p=3072, Cc=10))) == 4
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=250000, p=2000, Cc=20))) == 4
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=5))) == 1
     # a forced path that cannot take the shape is reported, on the host
     lib.nadmm_set_kernel_path(3)

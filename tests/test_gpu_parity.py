@@ -55,9 +55,14 @@ CASES = {
     "thin_70001x32_C3": lambda: workloads.generic(70001, 32, 3, seed=18, mean=True),
     "thin_300x12_C4": lambda: workloads.generic(300, 12, 4, seed=19),
     "thin_256x8_C2": lambda: workloads.generic(256, 8, 2, seed=20),
+    # shapes the column-sliced two-sweep path takes (p > 960 or C-1 > 16, row stride a multiple of 4)
+    "sliced_3000x100_C26": lambda: workloads.generic(3000, 100, 26, seed=24, x_std=0.1),
+    "sliced_1500x1100_C4": lambda: workloads.generic(1500, 1100, 4, seed=25, x_std=0.05),
+    "sliced_33x1604_C33": lambda: workloads.generic(33, 1604, 33, seed=26, x_std=0.03),
 }
 
 PATHS = [1, 2, 0]  # 1 = two-pass vector kernels forced, 2 = fused matrix-core kernel forced, 0 = automatic
+# (the thin-data and the column-sliced paths are the automatic choice wherever they apply)
 
 
 @pytest.fixture(scope="module")
@@ -125,7 +130,8 @@ def test_hessvec(cache, name, path):
 
 @pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("name", ["tiny", "image_like_3k", "tall_binary_50k", "ragged_1237x45_C5", "ragged_333x130_C12",
-                                  "fused_2000x100_C7", "fused_130x960_C4", "thin_5000x4_C2", "thin_256x8_C2"])
+                                  "fused_2000x100_C7", "fused_130x960_C4", "thin_5000x4_C2", "thin_256x8_C2", "sliced_1500x1100_C4",
+                                  "sliced_33x1604_C33", "wide_700"])
 def test_cg_fixed_iterations(cache, name, path):
     w, gp, op = setup_case(cache, name)
     force_path(gp, path)
@@ -165,7 +171,7 @@ def test_cg_tolerance_mode(cache, name):
 
 @pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("name", ["tiny", "image_like_3k", "tall_binary_50k", "ragged_517x65_C3", "fused_8200x64_C2",
-                                  "thin_70001x32_C3"])
+                                  "thin_70001x32_C3", "sliced_3000x100_C26"])
 def test_line_search(cache, name, path):
     w, gp, op = setup_case(cache, name)
     force_path(gp, path)
@@ -183,7 +189,8 @@ def test_line_search(cache, name, path):
 
 
 NEWTON_CASES = ["tiny", "image_like_3k", "wide_700", "tall_binary_50k", "large_multiclass_900", "ragged_1237x45_C5",
-                "single_row_1x7_C4", "fused_9001x260_C10", "fused_4100x36_C17", "thin_70001x32_C3", "thin_300x12_C4"]
+                "single_row_1x7_C4", "fused_9001x260_C10", "fused_4100x36_C17", "thin_70001x32_C3", "thin_300x12_C4", "sliced_3000x100_C26",
+                "sliced_1500x1100_C4"]
 
 
 @pytest.mark.parametrize("path", PATHS)
