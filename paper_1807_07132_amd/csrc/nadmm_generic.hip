@@ -171,14 +171,24 @@ __global__ __launch_bounds__(kRowsPerBlock) void logit_rows_kernel(const RowArgs
   float z[NCP], w[NCP];
 #pragma unroll
   for (int c = 0; c < NCP; ++c) { z[c] = 0.f; w[c] = 0.f; }
-  if (valid) {
-    for (int s = 0; s < nslices; ++s) {
-      const float* src = zw + ((size_t)s * a.n + row) * 2 * NC;
+  // the 256 rows of this block are one contiguous run of 256 * 2 NC floats per slice: copy it coalesced
+  // into LDS, then every lane picks up its own row
+  extern __shared__ float stage[];
+  const int64_t brow0 = (int64_t)blockIdx.x * kRowsPerBlock;
+  const int64_t left = a.n - brow0;
+  const int count = (int)(left < kRowsPerBlock ? left : kRowsPerBlock) * 2 * NC;
+  for (int s = 0; s < nslices; ++s) {
+    const float* src = zw + ((size_t)s * a.n + brow0) * 2 * NC;
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < count; idx += kRowsPerBlock) stage[idx] = src[idx];
+    __syncthreads();
+    if (valid) {
+      const float* mine = stage + threadIdx.x * 2 * NC;
 #pragma unroll
       for (int c = 0; c < NCP; ++c)
         if (c < NC) {
-          if (has0) z[c] += src[c];
-          if (has1) w[c] += src[NC + c];
+          if (has0) z[c] += mine[c];
+          if (has1) w[c] += mine[NC + c];
         }
     }
   }
@@ -269,7 +279,8 @@ hipError_t launch_logit_rows(const RowArgs& a, const float* zw, int nslices, hip
   const int blocks = generic_row_blocks(a.n);
   return dispatch_ncp(a.NC, [&](auto ncp) {
     constexpr int NCP = decltype(ncp)::value;
-    hipLaunchKernelGGL(logit_rows_kernel<NCP>, dim3(blocks), dim3(kRowsPerBlock), 0, st, a, zw, nslices);
+    hipLaunchKernelGGL(logit_rows_kernel<NCP>, dim3(blocks), dim3(kRowsPerBlock),
+                       (size_t)kRowsPerBlock * 2 * a.NC * sizeof(float), st, a, zw, nslices);
     return hipGetLastError();
   });
 }
