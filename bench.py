@@ -59,7 +59,7 @@ def cpu_baseline(w, seconds):
         orc.hessvec(prob, X, V)
         reps += 1
         el = time.perf_counter() - t0
-        if el >= seconds or reps >= 200:
+        if el >= seconds or reps >= 5000:
             break
     threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
     avail = len(os.sched_getaffinity(0))
