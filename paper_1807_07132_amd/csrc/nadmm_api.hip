@@ -20,10 +20,10 @@ struct Layout {
   Shape s;
   size_t state, g, pdir, r, dvec, q;
   size_t drows, pcache, zx, zp;
-  size_t partial, loss_part, lpart, zw;
+  size_t partial, loss_part, lpart, dotpart, zw;
   size_t total;
   int gen_row_blocks, gen_slabs, gen_chunks, gen_rpc;
-  int fused_parts, thin_parts, sliced_parts, sliced_slices;
+  int fused_parts, thin_parts, sliced_parts;
   bool fused_ok, thin_ok, sliced_ok;
 };
 
@@ -67,10 +67,9 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   L->zp = off; off += rows;
   L->sliced_ok = sliced_supported(s, p->lda, p->d_A);
   L->sliced_parts = 0;
-  L->sliced_slices = 0;
   if (L->sliced_ok) {
-    int sps = 0;
-    sliced_grid(s, &L->sliced_slices, &sps, &L->sliced_parts);
+    int sps = 0, S2 = 0;
+    sliced_grid(s, &S2, &sps, &L->sliced_parts);  // partial sums per row group
   }
   int parts = L->gen_chunks > L->fused_parts ? L->gen_chunks : L->fused_parts;
   if (L->sliced_parts > parts) parts = L->sliced_parts;
@@ -80,6 +79,7 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   if (L->thin_parts > lblocks) lblocks = L->thin_parts;
   L->loss_part = off; off += align256((size_t)lblocks * sizeof(double));
   L->lpart = off; off += align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
+  L->dotpart = off; off += align256((size_t)reduce_out_blocks(s.d) * sizeof(double));
   // per-slice partial logits of the column-sliced path (only where that path is the automatic choice)
   L->zw = off; off += align256((L->sliced_ok && !L->fused_ok && !L->thin_ok) ? sliced_zw_bytes(s) : 0);
   L->total = off;
@@ -150,8 +150,9 @@ int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArg
     return NADMM_OK;
   }
   if (path == 4) {
-    NADMM_HIP(launch_sliced_logits(ra, at<float>(ws, L.zw), st));
-    NADMM_HIP(launch_logit_rows(ra, at<float>(ws, L.zw), L.sliced_slices, st));
+    int nslices = 0;
+    NADMM_HIP(launch_sliced_logits(ra, at<float>(ws, L.zw), &nslices, st));
+    NADMM_HIP(launch_logit_rows(ra, at<float>(ws, L.zw), nslices, st));
     if (with_cols) {
       NADMM_HIP(launch_sliced_cols(ra, ra.rows_out, at<float>(ws, L.partial), st));
       *nparts = L.sliced_parts;
@@ -183,7 +184,7 @@ RowArgs blank_rows() {
 }
 
 int reduce(const nadmm_problem* prob, const Layout& L, void* ws, int nparts, int kind, const float* XorV,
-           float* out, const int32_t* flag, hipStream_t st) {
+           float* out, double* dot_part, const int32_t* flag, hipStream_t st) {
   ReduceArgs r;
   std::memset(&r, 0, sizeof(r));
   r.partial = at<float>(ws, L.partial);
@@ -198,6 +199,7 @@ int reduce(const nadmm_problem* prob, const Layout& L, void* ws, int nparts, int
   r.lambda = prob->lambda;
   r.rho = prob->rho;
   r.out = out;
+  r.dot_part = dot_part;
   r.flag = flag;
   NADMM_HIP(launch_reduce_out(r, st));
   return NADMM_OK;
@@ -205,7 +207,7 @@ int reduce(const nadmm_problem* prob, const Layout& L, void* ws, int nparts, int
 
 // q = H(X) v.  With X == NULL the probabilities cached in the workspace are used.
 int hv_apply(const nadmm_problem* prob, const Layout& L, int path, void* ws, const float* X, bool write_pcache,
-             const float* v, float* out, const int32_t* flag, hipStream_t st) {
+             const float* v, float* out, double* dot_part, const int32_t* flag, hipStream_t st) {
   RowArgs ra = blank_rows();
   ra.kind = kRowsHv;
   ra.B0 = X;
@@ -217,7 +219,7 @@ int hv_apply(const nadmm_problem* prob, const Layout& L, int path, void* ws, con
   int nparts = 0;
   int rc = sweep(prob, L, path, ws, ra, true, &nparts, st);
   if (rc != NADMM_OK) return rc;
-  return reduce(prob, L, ws, nparts, 0, v, out, flag, st);
+  return reduce(prob, L, ws, nparts, 0, v, out, dot_part, flag, st);
 }
 
 void fill_alphas(float* alphas, int ncand, float gamma) {
@@ -301,7 +303,7 @@ int nadmm_loss_grad(const nadmm_problem* prob, const float* d_X, double* d_loss,
   ra.loss_part = at<double>(d_ws, L.loss_part);
   int nparts = 0;
   if ((rc = sweep(prob, L, path, d_ws, ra, d_grad != nullptr, &nparts, st)) != NADMM_OK) return rc;
-  if (d_grad && (rc = reduce(prob, L, d_ws, nparts, 1, d_X, d_grad, nullptr, st)) != NADMM_OK) return rc;
+  if (d_grad && (rc = reduce(prob, L, d_ws, nparts, 1, d_X, d_grad, nullptr, nullptr, st)) != NADMM_OK) return rc;
 
   LossFinishArgs lf;
   lf.loss_part = at<double>(d_ws, L.loss_part);
@@ -328,7 +330,7 @@ int nadmm_hessvec(const nadmm_problem* prob, const float* d_X, const float* d_V,
   if ((rc = check_ws(L, d_ws, ws_bytes)) != NADMM_OK) return rc;
   int path = 0;
   if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
-  return hv_apply(prob, L, path, d_ws, d_X, false, d_V, d_HV, nullptr, (hipStream_t)stream);
+  return hv_apply(prob, L, path, d_ws, d_X, false, d_V, d_HV, nullptr, nullptr, (hipStream_t)stream);
 }
 
 int nadmm_cg_solve(const nadmm_problem* prob, const float* d_X, const float* d_g, float* d_p, int max_iter,
@@ -358,7 +360,7 @@ int nadmm_cg_solve(const nadmm_problem* prob, const float* d_X, const float* d_g
 
   for (int k = 0; k < max_iter; ++k) {
     rc = hv_apply(prob, L, path, d_ws, k == 0 ? d_X : nullptr, true, at<float>(d_ws, L.dvec), at<float>(d_ws, L.q),
-                  &ds->cg_active, st);
+                  at<double>(d_ws, L.dotpart), &ds->cg_active, st);
     if (rc != NADMM_OK) return rc;
     CgUpdateArgs cu;
     cu.st = ds;
@@ -366,6 +368,8 @@ int nadmm_cg_solve(const nadmm_problem* prob, const float* d_X, const float* d_g
     cu.r = at<float>(d_ws, L.r);
     cu.dvec = at<float>(d_ws, L.dvec);
     cu.q = at<float>(d_ws, L.q);
+    cu.dot_part = at<double>(d_ws, L.dotpart);
+    cu.ndot = reduce_out_blocks(L.s.d);
     cu.d = L.s.d;
     cu.tol = tol;
     NADMM_HIP(launch_cg_update(cu, st));
@@ -487,7 +491,7 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
     ra.flag = &ds->newton_active;
     int nparts = 0;
     if ((rc = sweep(prob, L, path, d_ws, ra, true, &nparts, st)) != NADMM_OK) return rc;
-    if ((rc = reduce(prob, L, d_ws, nparts, 1, d_X, g, &ds->newton_active, st)) != NADMM_OK) return rc;
+    if ((rc = reduce(prob, L, d_ws, nparts, 1, d_X, g, nullptr, &ds->newton_active, st)) != NADMM_OK) return rc;
 
     NewtonHeadArgs nh;
     std::memset(&nh, 0, sizeof(nh));
@@ -512,13 +516,15 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
 
     // CG on H p = -g with the probabilities of this iterate
     for (int k = 0; k < params->max_cg; ++k) {
-      if ((rc = hv_apply(prob, L, path, d_ws, nullptr, false, dvec, q, &ds->cg_active, st)) != NADMM_OK) return rc;
+      if ((rc = hv_apply(prob, L, path, d_ws, nullptr, false, dvec, q, at<double>(d_ws, L.dotpart), &ds->cg_active, st)) != NADMM_OK) return rc;
       CgUpdateArgs cu;
       cu.st = ds;
       cu.pdir = pdir;
       cu.r = r;
       cu.dvec = dvec;
       cu.q = q;
+      cu.dot_part = at<double>(d_ws, L.dotpart);
+      cu.ndot = reduce_out_blocks(L.s.d);
       cu.d = L.s.d;
       cu.tol = params->cg_tol;
       NADMM_HIP(launch_cg_update(cu, st));

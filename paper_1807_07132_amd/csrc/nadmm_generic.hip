@@ -9,6 +9,7 @@
 // Pass 2 (columns): one lane per feature column accumulates A^T rows over a
 // chunk of samples; chunk partials are summed in a fixed order afterwards.
 #include "nadmm_internal.h"
+#include "nadmm_mfma.h"
 
 namespace nadmm {
 namespace {
@@ -157,45 +158,140 @@ __global__ __launch_bounds__(kRowsPerBlock) void rows_kernel(const RowArgs a) {
 }
 
 // Rows stage on logits that were computed elsewhere: the column-sliced matrix-core pass leaves one partial
-// n x 2 x (C-1) array [Z | W] per column slice; this kernel adds the slices in order and finishes the rows.
-template <int NCP>
-__global__ __launch_bounds__(kRowsPerBlock) void logit_rows_kernel(const RowArgs a, const float* __restrict__ zw,
-                                                                    int nslices) {
+// n x {1,2} x (C-1) array [Z | W] per column slice (only the matrices whose operand was given); this kernel
+// adds the slices in order and finishes the rows.
+constexpr int kLogitThreads = 1024;  // 16 waves x 16 rows = the kRowsPerBlock rows of one partial loss
+
+// Lane (g, m) of a wave holds classes m, 16 + m, ... of row 4 it + g: the loads and stores of a wave
+// cover whole rows of the n x (C-1) arrays back to back, and the sums over a row's classes are
+// rotations inside 16 lanes.
+template <int NB>
+__global__ __launch_bounds__(kLogitThreads) void logit_rows_kernel(const RowArgs a, const float* __restrict__ zw,
+                                                                   int nslices) {
+  using mfma_detail::row16_max;
+  using mfma_detail::row16_sum;
   if (a.flag != nullptr && *a.flag == 0) return;
-  __shared__ double red[4];
+  __shared__ double red[kLogitThreads / 64];
+  constexpr int kIters = 4;
   const int NC = a.NC;
   const bool has0 = a.B0 != nullptr;
   const bool has1 = a.B1 != nullptr;
-  const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x;
-  const bool valid = row < a.n;
-  float z[NCP], w[NCP];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m = lane & 15, g = lane >> 4;
+  const int64_t wrow0 = (int64_t)blockIdx.x * kRowsPerBlock + wave * (4 * kIters);
+  const bool with_loss = a.kind == kRowsGrad || a.kind == kRowsLoss;
+  const int nmat = (has0 ? 1 : 0) + (has1 ? 1 : 0);  // matrices held per slice and row: [Z][W], [Z] or [W]
+  const int woff = has0 ? NC : 0;
+
+  int cl[NB];
+  bool cv[NB];
 #pragma unroll
-  for (int c = 0; c < NCP; ++c) { z[c] = 0.f; w[c] = 0.f; }
-  // the 256 rows of this block are one contiguous run of 256 * 2 NC floats per slice: copy it coalesced
-  // into LDS, then every lane picks up its own row
-  extern __shared__ float stage[];
-  const int64_t brow0 = (int64_t)blockIdx.x * kRowsPerBlock;
-  const int64_t left = a.n - brow0;
-  const int count = (int)(left < kRowsPerBlock ? left : kRowsPerBlock) * 2 * NC;
-  for (int s = 0; s < nslices; ++s) {
-    const float* src = zw + ((size_t)s * a.n + brow0) * 2 * NC;
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < count; idx += kRowsPerBlock) stage[idx] = src[idx];
-    __syncthreads();
-    if (valid) {
-      const float* mine = stage + threadIdx.x * 2 * NC;
+  for (int nb = 0; nb < NB; ++nb) {
+    cv[nb] = 16 * nb + m < NC;
+    cl[nb] = cv[nb] ? 16 * nb + m : NC - 1;
+  }
+
+  float z[kIters][NB], w[kIters][NB], aux[kIters][NB];
+  int label[kIters];
 #pragma unroll
-      for (int c = 0; c < NCP; ++c)
-        if (c < NC) {
-          if (has0) z[c] += mine[c];
-          if (has1) w[c] += mine[NC + c];
-        }
+  for (int it = 0; it < kIters; ++it) {
+    const int64_t row = wrow0 + 4 * it + g;
+    const int64_t rowc = row < a.n ? row : a.n - 1;
+    label[it] = with_loss ? a.labels[rowc] : 0;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      z[it][nb] = 0.f;
+      w[it][nb] = 0.f;
+      aux[it][nb] = (!has0 && a.kind == kRowsHv) ? a.Pin[(size_t)rowc * NC + cl[nb]] : 0.f;
     }
   }
-  const double ell = finish_row<NCP>(a, row, valid, has0, has1, z, w);
-  if (a.kind != kRowsGrad && a.kind != kRowsLoss) return;
-  const double tot = block_sum_double(ell, red);
-  if (threadIdx.x == 0) a.loss_part[blockIdx.x] = tot;
+  for (int s = 0; s < nslices; ++s) {  // slices are added in order
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+      const int64_t row = wrow0 + 4 * it + g;
+      const int64_t rowc = row < a.n ? row : a.n - 1;
+      const float* src = zw + ((size_t)s * a.n + rowc) * nmat * NC;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        if (has0) z[it][nb] += src[cl[nb]];
+        if (has1) w[it][nb] += src[woff + cl[nb]];
+      }
+    }
+  }
+
+  double ell = 0.0;
+#pragma unroll
+  for (int it = 0; it < kIters; ++it) {
+    const int64_t row = wrow0 + 4 * it + g;
+    const bool valid = row < a.n;
+    const size_t ro = (size_t)(valid ? row : a.n - 1) * NC;
+    if (a.kind == kRowsLogits) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        if (valid && cv[nb]) {
+          if (has0 && a.Z0out) a.Z0out[ro + cl[nb]] = z[it][nb];
+          if (has1 && a.Z1out) a.Z1out[ro + cl[nb]] = w[it][nb];
+        }
+      continue;
+    }
+    float P[NB];
+    float M = 0.f, alpha = 1.f;
+    if (has0) {
+      float mx = 0.f;  // the reference class has logit 0
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) mx = fmaxf(mx, cv[nb] ? z[it][nb] : 0.f);
+      M = row16_max(mx);
+      float es = 0.f;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        P[nb] = cv[nb] ? expf(z[it][nb] - M) : 0.f;
+        es += P[nb];
+      }
+      alpha = row16_sum(es) + expf(-M);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) P[nb] = P[nb] / alpha;
+    } else {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) P[nb] = cv[nb] ? aux[it][nb] : 0.f;
+    }
+    if (a.kind == kRowsHv) {
+      float t = 0.f;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) t = fmaf(P[nb], w[it][nb], t);
+      t = row16_sum(t);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        if (valid && cv[nb]) {
+          a.rows_out[ro + cl[nb]] = P[nb] * (w[it][nb] - t);
+          if (a.Pout) a.Pout[ro + cl[nb]] = P[nb];
+        }
+      continue;
+    }
+    float zb = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const bool mine = cv[nb] && 16 * nb + m == label[it];
+      zb += mine ? z[it][nb] : 0.f;
+      if (valid && cv[nb]) {
+        if (a.kind == kRowsGrad && a.rows_out) a.rows_out[ro + cl[nb]] = P[nb] - (mine ? 1.f : 0.f);
+        if (a.Pout) a.Pout[ro + cl[nb]] = P[nb];
+        if (a.Z0out) a.Z0out[ro + cl[nb]] = z[it][nb];
+      }
+    }
+    zb = row16_sum(zb);
+    if (valid && m == 0) ell += (double)M + (double)logf(alpha) - (double)zb;
+  }
+  if (!with_loss) return;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ell += __shfl_down(ell, off, 64);
+  if (lane == 0) red[wave] = ell;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int wv = 0; wv < kLogitThreads / 64; ++wv) t += red[wv];
+    a.loss_part[blockIdx.x] = t;
+  }
 }
 
 template <int NCP>
@@ -277,12 +373,10 @@ hipError_t launch_generic_rows(const RowArgs& a, hipStream_t st) {
 
 hipError_t launch_logit_rows(const RowArgs& a, const float* zw, int nslices, hipStream_t st) {
   const int blocks = generic_row_blocks(a.n);
-  return dispatch_ncp(a.NC, [&](auto ncp) {
-    constexpr int NCP = decltype(ncp)::value;
-    hipLaunchKernelGGL(logit_rows_kernel<NCP>, dim3(blocks), dim3(kRowsPerBlock),
-                       (size_t)kRowsPerBlock * 2 * a.NC * sizeof(float), st, a, zw, nslices);
-    return hipGetLastError();
-  });
+  if (a.NC <= 16) hipLaunchKernelGGL(logit_rows_kernel<1>, dim3(blocks), dim3(kLogitThreads), 0, st, a, zw, nslices);
+  else if (a.NC <= 32) hipLaunchKernelGGL(logit_rows_kernel<2>, dim3(blocks), dim3(kLogitThreads), 0, st, a, zw, nslices);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
 }
 
 hipError_t launch_generic_cols(const ColArgs& a, int nslabs, int nchunks, hipStream_t st) {

@@ -83,7 +83,8 @@ int generic_row_blocks(int64_t n);
 void generic_col_grid(const Shape& s, int* nslabs, int* nchunks, int* rows_per_chunk);
 hipError_t launch_generic_rows(const RowArgs& a, hipStream_t st);
 hipError_t launch_generic_cols(const ColArgs& a, int nslabs, int nchunks, hipStream_t st);
-// rows stage on per-slice partial logits zw[slice][row][Z|W][C-1]; partial losses per block of generic_row_blocks()
+// rows stage on per-slice partial logits zw[slice][row][Z|W][C-1] (Z only if B0, W only if B1 is given);
+// partial losses per block of generic_row_blocks()
 hipError_t launch_logit_rows(const RowArgs& a, const float* zw, int nslices, hipStream_t st);
 
 // ---- vector / tail kernels (nadmm_vec.hip) ----
@@ -99,8 +100,10 @@ struct ReduceArgs {
   const float* y;
   float lambda, rho;
   float* out;
+  double* dot_part;       // kind 0, optional: per-workgroup sums of out[e] * V[e], reduce_out_blocks(d) entries
   const int32_t* flag;
 };
+int reduce_out_blocks(int64_t d);
 hipError_t launch_reduce_out(const ReduceArgs& a, hipStream_t st);
 
 struct LossFinishArgs {
@@ -140,6 +143,8 @@ struct CgUpdateArgs {
   float* r;
   float* dvec;
   const float* q;
+  const double* dot_part;  // partial sums of <d, q> left by the reduction that formed q
+  int32_t ndot;
   int64_t d;
   float tol;
 };
@@ -214,7 +219,8 @@ hipError_t launch_thin(const RowArgs& a, float* partial, int nparts, hipStream_t
 bool sliced_supported(const Shape& s, int64_t lda, const void* A);
 void sliced_grid(const Shape& s, int* nslices, int* steps_per_slice, int* row_groups);
 size_t sliced_zw_bytes(const Shape& s);
-hipError_t launch_sliced_logits(const RowArgs& a, float* zw, hipStream_t st);
+// writes zw[slice][row][Z|W][C-1] for *nslices column slices (at most the count sliced_zw_bytes() is sized for)
+hipError_t launch_sliced_logits(const RowArgs& a, float* zw, int* nslices, hipStream_t st);
 hipError_t launch_sliced_cols(const RowArgs& a, const float* rows_in, float* partial, hipStream_t st);
 
 }  // namespace nadmm

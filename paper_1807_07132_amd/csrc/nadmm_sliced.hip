@@ -4,7 +4,8 @@
 // (p > 960 or C-1 > 16), the columns are cut into slices of at most 24 steps of 32 columns and the
 // Hessian-vector product of Section 2.6 (or the gradient A^T (P - Y)) is taken in two sweeps over A:
 //   sweep 1  every workgroup (slice, row range) forms its slice's share of the logits
-//            Z|W = A[:, slice] [X|V][slice, :] with bf16-split MFMAs and writes it per slice;
+//            Z|W = A[:, slice] [X|V][slice, :] with bf16-split MFMAs and writes it per slice, the
+//            rows of several tiles gathered in LDS and stored as one contiguous run;
 //   rows     a small kernel adds the slices and forms P, D, the row losses (nadmm_generic.hip);
 //   sweep 2  every workgroup forms out^T[:, slice] += D^T A[:, slice] for its row range; the tile is
 //            transposed through a wave-private swizzled LDS copy; no workgroup barrier is needed.
@@ -23,16 +24,37 @@ constexpr int kTileRows = 32;
 constexpr int kStepCols = 32;
 constexpr int kSliceSteps = 24;   // at most 3 steps per wave
 constexpr int kStepBytes = 4096;
+constexpr int kLogitBatchFloats = 8192;  // sweep 1: output rows gathered in LDS between stores (8 or 4 tiles)
 
 struct SlicedArgs {
   RowArgs r;
-  float* zw;             // sweep 1 out: [slice][n][2][NC]
+  float* zw;             // sweep 1 out: [slice][n][Z|W][NC], only the matrices whose operand is given
   const float* rows_in;  // sweep 2 in:  [n][NC]
   float* partial;        // sweep 2 out: [row group][p*NC]
   int32_t steps_total;   // ceil(p / 32)
-  int32_t steps_per_slice;
+  int32_t steps_q;       // slice s holds steps_q + (s < steps_r) steps, starting at s steps_q + min(s, steps_r)
+  int32_t steps_r;
+  int32_t steps_max;     // steps of the largest slice
   int32_t rows_per_wg;
+  int32_t sync_tiles;    // sweep 2: keep the waves of a workgroup within one tile of each other
 };
+
+// Steps of one wave inside its slice: the slice's steps are dealt out in contiguous, balanced runs,
+// wave w owning steps [w nsteps / 8, (w+1) nsteps / 8).  Every wave then holds at least
+// ceil(steps_max / 8) - 1 steps, so only the last of a wave's SPW step slots is conditional, and a
+// row's bytes are shared between neighbouring waves at one place only (rows need not start on a
+// cache line).
+struct WaveSteps {
+  int step0;   // first step of this wave, counted over the whole matrix
+  int local0;  // the same, counted inside the slice
+  int count;
+};
+__device__ __forceinline__ WaveSteps wave_steps(const SlicedArgs& sa, int slice, int wave) {
+  const int nsteps = sa.steps_q + (slice < sa.steps_r ? 1 : 0);
+  const int first = slice * sa.steps_q + (slice < sa.steps_r ? slice : sa.steps_r);
+  const int b0 = (wave * nsteps) >> 3, b1 = ((wave + 1) * nsteps) >> 3;
+  return WaveSteps{first + b0, b0, b1 - b0};
+}
 
 // Loads of one step (2 row blocks x 8 columns per lane), addresses clamped into the matrix.
 __device__ __forceinline__ void load_step_regs(const RowArgs& a, float4 (&pf)[2][2], int64_t row0, int64_t r_end,
@@ -85,15 +107,16 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
   extern __shared__ __attribute__((aligned(16))) char lds[];
   float* part = reinterpret_cast<float*>(lds);  // [wave][quad (mat, nb, rb)][comp][lane]
   constexpr int kQuads = 2 * NB * 2;
+  constexpr int kMats = (HAS0 ? 1 : 0) + (HAS1 ? 1 : 0);
+  constexpr int kBatch = kLogitBatchFloats / (kTileRows * 2 * 16 * NB);  // tiles per store of the output block
+  float* oblock = part + (size_t)kWaves * kQuads * 4 * 64;  // [row of the batch][matrix][class]
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m = lane & 15, kg = lane >> 4;
   const int NC = a.NC, p = a.p;
   const int slice = blockIdx.x;
-  const int step0 = slice * sa.steps_per_slice;
-  int nsteps = sa.steps_total - step0;
-  if (nsteps > sa.steps_per_slice) nsteps = sa.steps_per_slice;
+  const WaveSteps ws = wave_steps(sa, slice, wave);
   const int col_max = (int)a.lda - 4;
 
   const int64_t r_begin = (int64_t)blockIdx.y * sa.rows_per_wg;
@@ -101,8 +124,8 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
   if (r_end > a.n) r_end = a.n;
   if (r_begin >= r_end) return;
 
-  auto step_exists = [&](int i) { return wave + kWaves * i < nsteps; };
-  auto col_of = [&](int i) { return kStepCols * (step0 + wave + kWaves * i) + 8 * kg; };
+  auto step_exists = [&](int i) { return i < SPW - 1 || i < ws.count; };
+  auto col_of = [&](int i) { return kStepCols * (ws.step0 + i) + 8 * kg; };
 
   float4 pf[SPW][2][2];
 #pragma unroll
@@ -123,7 +146,7 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
       for (int e = 0; e < 8; ++e) {
         const int j = col_of(i) + e;
         const size_t idx = (size_t)(j < p ? j : p - 1) * NC + clc;
-        const bool ok = cvn && j < p && step_exists(i);
+        const bool ok = cvn && j < p && i < ws.count;
         const float xv = HAS0 ? a.B0[idx] : 0.f;
         const float vv = HAS1 ? a.B1[idx] : 0.f;
         x[e] = ok ? xv : 0.f;
@@ -133,6 +156,8 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
       split8(v, bv_hi[i][nb], bv_lo[i][nb]);
     }
 
+  int gathered = 0;  // tiles in the output block
+  int64_t flush_row0 = r_begin;
   for (int64_t row0 = r_begin; row0 < r_end; row0 += kTileRows) {
     f32x4 accZ[NB][2], accW[NB][2];
 #pragma unroll
@@ -144,7 +169,7 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
       if (step_exists(i)) {
         const int col = col_of(i);
         u32x4 ahi[2], alo[2];
-        convert_step(pf[i], col, col_max, p, kStepCols * (step0 + wave + kWaves * i + 1) > p, ahi, alo);
+        convert_step(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo);
         load_step_regs(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -169,30 +194,46 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
           }
     }
     __syncthreads();
-    // wave e adds the 8 partials of rows row0 + 4 kg + (e & 3) + 16 (e >> 2) and stores its slice share
+    // wave e adds the 8 partials of rows row0 + 4 kg + (e & 3) + 16 (e >> 2) and puts them into the output
+    // block, laid out as in memory: [row][Z|W][C-1] (only the matrices that are computed)
     {
       const int rb = wave >> 2, comp = wave & 3;
-      const int64_t my_row = row0 + 4 * kg + comp + 16 * rb;
-      if (my_row < r_end) {
-        float* dst = sa.zw + ((size_t)slice * a.n + my_row) * 2 * NC;
+      const int r_local = kTileRows * gathered + 4 * kg + comp + 16 * rb;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-          const int cls = 16 * nb + m;
-          float z = 0.f, w = 0.f;
+      for (int nb = 0; nb < NB; ++nb) {
+        const int cls = 16 * nb + m;
+        float z = 0.f, w = 0.f;
 #pragma unroll
-          for (int sw = 0; sw < kWaves; ++sw) {
-            const float* pr = part + (size_t)(sw * kQuads * 4) * 64 + lane;
-            if (HAS0) z += pr[(((0 * NB + nb) * 2 + rb) * 4 + comp) * 64];
-            if (HAS1) w += pr[(((1 * NB + nb) * 2 + rb) * 4 + comp) * 64];
-          }
-          if (cls < NC) {
-            if (HAS0) dst[cls] = z;
-            if (HAS1) dst[NC + cls] = w;
-          }
+        for (int sw = 0; sw < kWaves; ++sw) {
+          const float* pr = part + (size_t)(sw * kQuads * 4) * 64 + lane;
+          if (HAS0) z += pr[(((0 * NB + nb) * 2 + rb) * 4 + comp) * 64];
+          if (HAS1) w += pr[(((1 * NB + nb) * 2 + rb) * 4 + comp) * 64];
+        }
+        if (cls < NC) {
+          if (HAS0) oblock[(r_local * kMats + 0) * NC + cls] = z;
+          if (HAS1) oblock[(r_local * kMats + (HAS0 ? 1 : 0)) * NC + cls] = w;
         }
       }
     }
     __syncthreads();
+    // The rows gathered so far are one contiguous run in memory.  They are written once per kBatch
+    // tiles: every store event holds up the loads of the compute unit for about a microsecond,
+    // however little it writes.
+    ++gathered;
+    if (gathered == kBatch || row0 + kTileRows >= r_end) {
+      const int64_t left = r_end - flush_row0;
+      const int rows = (int)(left < kTileRows * gathered ? left : kTileRows * gathered);
+      const int total = rows * kMats * NC;
+      float* dst = sa.zw + ((size_t)slice * a.n + flush_row0) * kMats * NC;
+#pragma unroll
+      for (int k = 0; k < (kBatch * kTileRows * kMats * 16 * NB) / kThreads; ++k) {
+        int idx = threadIdx.x + k * kThreads;
+        idx = idx < total ? idx : total - 1;  // indices past the block repeat its last element
+        dst[idx] = oblock[idx];
+      }
+      flush_row0 += kTileRows * gathered;
+      gathered = 0;
+    }
   }
 }
 
@@ -204,24 +245,22 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
   const RowArgs& a = sa.r;
   if (a.flag != nullptr && *a.flag == 0) return;
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  char* cm = lds;  // steps_per_slice x 4 KB, step owned by wave (step % 8): wave-private
+  char* cm = lds;  // steps_max x 4 KB, every step slot used by the one wave that owns the step
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m = lane & 15, kg = lane >> 4;
   const int NC = a.NC, p = a.p;
   const int slice = blockIdx.x;
-  const int step0 = slice * sa.steps_per_slice;
-  int nsteps = sa.steps_total - step0;
-  if (nsteps > sa.steps_per_slice) nsteps = sa.steps_per_slice;
+  const WaveSteps ws = wave_steps(sa, slice, wave);
   const int col_max = (int)a.lda - 4;
 
   const int64_t r_begin = (int64_t)blockIdx.y * sa.rows_per_wg;
   int64_t r_end = r_begin + sa.rows_per_wg;
   if (r_end > a.n) r_end = a.n;
 
-  auto step_exists = [&](int i) { return wave + kWaves * i < nsteps; };
-  auto col_of = [&](int i) { return kStepCols * (step0 + wave + kWaves * i) + 8 * kg; };
+  auto step_exists = [&](int i) { return i < SPW - 1 || i < ws.count; };
+  auto col_of = [&](int i) { return kStepCols * (ws.step0 + i) + 8 * kg; };
 
   f32x4 acc2[SPW][2][NB];
 #pragma unroll
@@ -279,9 +318,9 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
     for (int i = 0; i < SPW; ++i) {
       if (step_exists(i)) {
         const int col = col_of(i);
-        const int sl = wave + kWaves * i;  // step inside the slice
+        const int sl = ws.local0 + i;  // step inside the slice
         u32x4 ahi[2], alo[2];
-        convert_step(pf[i], col, col_max, p, kStepCols * (step0 + sl + 1) > p, ahi, alo);
+        convert_step(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo);
         load_step_regs(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
         char* base = cm + (size_t)sl * kStepBytes;
 #pragma unroll
@@ -304,15 +343,18 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
         }
       }
     }
+    // Rows that do not start on a cache line share lines between neighbouring waves: waves that
+    // drift apart would fetch such lines from memory twice.
+    if (sa.sync_tiles) __builtin_amdgcn_s_barrier();
   }
 
   float* out = sa.partial + (size_t)blockIdx.y * ((size_t)p * NC);
 #pragma unroll
   for (int i = 0; i < SPW; ++i) {
-    if (step_exists(i)) {
+    if (i < ws.count) {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        const int j = kStepCols * (step0 + wave + kWaves * i) + 16 * h + m;
+        const int j = kStepCols * (ws.step0 + i) + 16 * h + m;
         if (j < p) {
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb)
@@ -335,7 +377,7 @@ hipError_t set_lds_limit(K kernel) {
 
 template <int SPW, int NB, bool HAS0, bool HAS1>
 hipError_t launch_logits_t(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
-  const size_t lds = (size_t)kWaves * (2 * NB * 2) * 4 * 64 * sizeof(float);
+  const size_t lds = ((size_t)kWaves * (2 * NB * 2) * 4 * 64 + (size_t)kLogitBatchFloats) * sizeof(float);
   static bool once = false;
   if (!once) {
     hipError_t e = set_lds_limit(&slice_logits_kernel<SPW, NB, HAS0, HAS1>);
@@ -357,7 +399,7 @@ hipError_t launch_logits_nb(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
 
 template <int SPW, int NB>
 hipError_t launch_cols_t(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
-  const size_t lds = (size_t)sa.steps_per_slice * kStepBytes;
+  const size_t lds = (size_t)sa.steps_max * kStepBytes;
   static bool once = false;
   if (!once) {
     hipError_t e = set_lds_limit(&slice_cols_kernel<SPW, NB>);
@@ -376,16 +418,17 @@ bool sliced_supported(const Shape& s, int64_t lda, const void* A) {
   return true;
 }
 
+// One workgroup per compute unit: (column slices) x (row groups) = at most 256 workgroups; both sweeps use
+// the same plan.  (Finer slices or two workgroups per compute unit in sweep 1 measured no faster.)
 void sliced_grid(const Shape& s, int* nslices, int* steps_per_slice, int* row_groups) {
   const int steps = (s.p + kStepCols - 1) / kStepCols;
   const int S = (steps + kSliceSteps - 1) / kSliceSteps;
-  const int sps = (steps + S - 1) / S;
   const int64_t tiles = (s.n + kTileRows - 1) / kTileRows;
   int64_t rg = 256 / S;
   if (rg < 1) rg = 1;
   if (rg > tiles) rg = tiles;
-  *nslices = (steps + sps - 1) / sps;
-  *steps_per_slice = sps;
+  *nslices = S;
+  *steps_per_slice = (steps + S - 1) / S;  // the largest slice; slices differ by at most one step
   *row_groups = (int)rg;
 }
 
@@ -395,24 +438,28 @@ size_t sliced_zw_bytes(const Shape& s) {
   return (size_t)S * s.n * 2 * s.NC * sizeof(float);
 }
 
-static SlicedArgs make_args(const RowArgs& a) {
+static SlicedArgs make_args(const RowArgs& a, int S, int sps, int rg) {
   SlicedArgs sa;
   sa.r = a;
   sa.zw = nullptr;
   sa.rows_in = nullptr;
   sa.partial = nullptr;
   sa.steps_total = (a.p + kStepCols - 1) / kStepCols;
+  sa.steps_q = sa.steps_total / S;
+  sa.steps_r = sa.steps_total % S;
+  sa.steps_max = sps;
+  sa.rows_per_wg = (int32_t)((a.n + rg - 1) / rg);
+  sa.sync_tiles = ((a.lda * sizeof(float)) % 128 != 0 || (reinterpret_cast<uintptr_t>(a.A) & 127) != 0) ? 1 : 0;
   return sa;
 }
 
-hipError_t launch_sliced_logits(const RowArgs& a, float* zw, hipStream_t st) {
+hipError_t launch_sliced_logits(const RowArgs& a, float* zw, int* nslices, hipStream_t st) {
   Shape s{a.n, a.p, a.NC, (int64_t)a.p * a.NC};
   int S, sps, rg;
   sliced_grid(s, &S, &sps, &rg);
-  SlicedArgs sa = make_args(a);
+  *nslices = S;
+  SlicedArgs sa = make_args(a, S, sps, rg);
   sa.zw = zw;
-  sa.steps_per_slice = sps;
-  sa.rows_per_wg = (int32_t)((a.n + rg - 1) / rg);
   const dim3 grid(S, rg);
   const int spw = (sps + kWaves - 1) / kWaves;
   const int nb = a.NC > 16 ? 2 : 1;
@@ -436,11 +483,9 @@ hipError_t launch_sliced_cols(const RowArgs& a, const float* rows_in, float* par
   Shape s{a.n, a.p, a.NC, (int64_t)a.p * a.NC};
   int S, sps, rg;
   sliced_grid(s, &S, &sps, &rg);
-  SlicedArgs sa = make_args(a);
+  SlicedArgs sa = make_args(a, S, sps, rg);
   sa.rows_in = rows_in;
   sa.partial = partial;
-  sa.steps_per_slice = sps;
-  sa.rows_per_wg = (int32_t)((a.n + rg - 1) / rg);
   const dim3 grid(S, rg);
   const int spw = (sps + kWaves - 1) / kWaves;
   const int nb = a.NC > 16 ? 2 : 1;

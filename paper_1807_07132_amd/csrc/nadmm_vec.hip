@@ -53,19 +53,30 @@ __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
   }
   sm[grp][el] = sum;
   __syncthreads();
-  if (grp != 0 || e >= a.d) return;
+  if (grp != 0) return;
+  const bool ok = e < a.d;
 #pragma unroll
   for (int g = 1; g < 8; ++g) sum += sm[g][el];
   float out = a.scale * sum;
-  if (a.kind == 0) {
-    out = fmaf(a.lambda + a.rho, a.V[e], out);
-  } else {
-    const float x = a.X[e];
-    const float zz = a.z ? a.z[e] : 0.f;
-    const float yy = a.y ? a.y[e] : 0.f;
-    out += a.lambda * x + a.rho * (x - zz) + yy;
+  double prod = 0.0;
+  if (ok) {
+    if (a.kind == 0) {
+      const float v = a.V[e];
+      out = fmaf(a.lambda + a.rho, v, out);
+      prod = (double)out * (double)v;
+    } else {
+      const float x = a.X[e];
+      const float zz = a.z ? a.z[e] : 0.f;
+      const float yy = a.y ? a.y[e] : 0.f;
+      out += a.lambda * x + a.rho * (x - zz) + yy;
+    }
+    a.out[e] = out;
   }
-  a.out[e] = out;
+  if (a.dot_part != nullptr) {  // the 32 products of this workgroup, summed in a fixed order by lane 0
+#pragma unroll
+    for (int off = 16; off > 0; off >>= 1) prod += __shfl_down(prod, off, 64);
+    if (el == 0) a.dot_part[blockIdx.x] = prod;
+  }
 }
 
 // lambda/2 ||X||^2 + rho/2 ||X - z + y/rho||^2, summed over the workgroup
@@ -156,30 +167,20 @@ __global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs
 
 // One CG iteration's vector work, given q = H d:  a = rr / <d,q>; p += a d; r -= a q;
 // stop on ||r|| <= tol ||g|| (eq. inexact); else d = r + (rr'/rr) d.
-// PER > 0: each thread keeps its PER elements of d, q, r in registers (d <= PER * 1024).
+// <d, q> arrives as partial sums from the reduction that formed q.  Every vector is then read once:
+// pass 1 forms the new residual (kept in registers if PER > 0, d <= PER * 1024, else re-read) and its
+// norm, pass 2 updates the iterate and the direction.  Loads go out in blocks of 8 per vector and thread.
 template <int PER>
 __global__ __launch_bounds__(kTail) void cg_update_kernel(const CgUpdateArgs a) {
   __shared__ double sm[17];
   DevState* st = a.st;
   if (st->cg_active == 0) return;
-  constexpr int N = PER > 0 ? PER : 1;
-  float dv[N], qv[N], rv[N];
-  double dq = 0.0;
-  if (PER > 0) {
-#pragma unroll
-    for (int t = 0; t < N; ++t) {
-      const int64_t e = threadIdx.x + (int64_t)t * kTail;
-      const bool ok = e < a.d;
-      dv[t] = ok ? a.dvec[e] : 0.f;
-      qv[t] = ok ? a.q[e] : 0.f;
-      rv[t] = ok ? a.r[e] : 0.f;
-    }
-#pragma unroll
-    for (int t = 0; t < N; ++t) dq += (double)dv[t] * (double)qv[t];
-  } else {
-    for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) dq += (double)a.dvec[e] * (double)a.q[e];
-  }
-  dq = block_sum(dq, sm);
+  constexpr int U = 8;
+  constexpr int N = PER > 0 ? PER : U;
+  static_assert(N % U == 0, "blocks of 8");
+  constexpr int kUnroll = PER > 0 ? PER / U : 1;
+  const int nblk = PER > 0 ? PER / U : (int)((a.d + (int64_t)U * kTail - 1) / ((int64_t)U * kTail));
+  const double dq = partial_sum_block(a.dot_part, a.ndot, sm);
   const double rr = st->rr;
   const double gg = st->gg_cg;
   if (!(dq > 0.0) || !isfinite(dq)) {  // no positive curvature: keep the current iterate
@@ -188,37 +189,50 @@ __global__ __launch_bounds__(kTail) void cg_update_kernel(const CgUpdateArgs a) 
     return;
   }
   const float al = (float)(rr / dq);
+  float rn[N];
   double rr_new = 0.0;
-  if (PER > 0) {
+#pragma unroll kUnroll
+  for (int b = 0; b < nblk; ++b) {
+    float y[U], re[U];
 #pragma unroll
-    for (int t = 0; t < N; ++t) {
-      const int64_t e = threadIdx.x + (int64_t)t * kTail;
-      if (e < a.d) a.pdir[e] = fmaf(al, dv[t], a.pdir[e]);
-      rv[t] = fmaf(-al, qv[t], rv[t]);
-      rr_new += (double)rv[t] * (double)rv[t];
+    for (int u = 0; u < U; ++u) {
+      const int64_t e = threadIdx.x + (int64_t)(b * U + u) * kTail;
+      const bool ok = e < a.d;
+      y[u] = ok ? a.q[e] : 0.f;
+      re[u] = ok ? a.r[e] : 0.f;
     }
-  } else {
-    for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) {
-      a.pdir[e] = fmaf(al, a.dvec[e], a.pdir[e]);
-      const float rn = fmaf(-al, a.q[e], a.r[e]);
-      a.r[e] = rn;
-      rr_new += (double)rn * (double)rn;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t e = threadIdx.x + (int64_t)(b * U + u) * kTail;
+      const float v = fmaf(-al, y[u], re[u]);
+      rn[PER > 0 ? b * U + u : u] = v;
+      if (e < a.d) a.r[e] = v;
+      rr_new += (double)v * (double)v;
     }
   }
   rr_new = block_sum(rr_new, sm);
   const bool stop = sqrt(rr_new) <= (double)a.tol * sqrt(gg);
   const float be = (float)(rr_new / rr);
-  if (PER > 0) {
+  // every thread re-reads only elements of r that it wrote itself
+#pragma unroll kUnroll
+  for (int b = 0; b < nblk; ++b) {
+    float x[U], pe[U], re[U];
 #pragma unroll
-    for (int t = 0; t < N; ++t) {
-      const int64_t e = threadIdx.x + (int64_t)t * kTail;
+    for (int u = 0; u < U; ++u) {
+      const int64_t e = threadIdx.x + (int64_t)(b * U + u) * kTail;
+      const bool ok = e < a.d;
+      x[u] = ok ? a.dvec[e] : 0.f;
+      pe[u] = ok ? a.pdir[e] : 0.f;
+      re[u] = PER > 0 ? rn[b * U + u] : (ok ? a.r[e] : 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t e = threadIdx.x + (int64_t)(b * U + u) * kTail;
       if (e < a.d) {
-        a.r[e] = rv[t];
-        if (!stop) a.dvec[e] = fmaf(be, dv[t], rv[t]);
+        a.pdir[e] = fmaf(al, x[u], pe[u]);
+        if (!stop) a.dvec[e] = fmaf(be, x[u], re[u]);
       }
     }
-  } else if (!stop) {
-    for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) a.dvec[e] = fmaf(be, a.dvec[e], a.r[e]);
   }
   if (threadIdx.x == 0) {
     st->rr = rr_new;
@@ -370,8 +384,10 @@ hipError_t dispatch_ncp(int NC, F&& f) {
 
 }  // namespace
 
+int reduce_out_blocks(int64_t d) { return (int)((d + 31) / 32); }
+
 hipError_t launch_reduce_out(const ReduceArgs& a, hipStream_t st) {
-  const int blocks = (int)((a.d + 31) / 32);
+  const int blocks = reduce_out_blocks(a.d);
   hipLaunchKernelGGL(reduce_out_kernel, dim3(blocks), dim3(256), 0, st, a);
   return hipGetLastError();
 }
@@ -394,6 +410,7 @@ hipError_t launch_newton_head(const NewtonHeadArgs& a, hipStream_t st) {
 hipError_t launch_cg_update(const CgUpdateArgs& a, hipStream_t st) {
   if (a.d <= 8 * kTail) hipLaunchKernelGGL(cg_update_kernel<8>, dim3(1), dim3(kTail), 0, st, a);
   else if (a.d <= 24 * kTail) hipLaunchKernelGGL(cg_update_kernel<24>, dim3(1), dim3(kTail), 0, st, a);
+  else if (a.d <= 40 * kTail) hipLaunchKernelGGL(cg_update_kernel<40>, dim3(1), dim3(kTail), 0, st, a);
   else hipLaunchKernelGGL(cg_update_kernel<0>, dim3(1), dim3(kTail), 0, st, a);
   return hipGetLastError();
 }
