@@ -22,7 +22,12 @@ HV_PER_STEP = 100
 LG_PER_STEP = 100
 # HBM bytes per nadmm_hessvec call from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by a plain copy of known size); counters cannot be read inside a timing run.
-MEASURED_HV_TRAFFIC = {("image_like_60000x784_C10", 2): 207.1e6}
+MEASURED_HV_TRAFFIC = {
+    ("image_like_60000x784_C10", 2): 207.0e6,
+    ("tall_binary_1375000x28_C2", 3): 154.4e6,
+    ("wide_50000x3072_C10", 4): 1286.5e6,
+    ("large_multiclass_250000x2000_C20", 4): 4435.8e6,
+}
 
 
 def parse():
@@ -32,7 +37,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="image_like")
     ap.add_argument("--n", type=int, default=None, help="override the number of rows (testing only)")
-    ap.add_argument("--path", type=int, default=0, help="kernel path: 0 auto, 1 two-pass, 2 fused, 3 thin")
+    ap.add_argument("--path", type=int, default=0, help="kernel path: 0 auto, 1 two-pass, 2 fused, 3 thin, 4 column-sliced")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--only", default="", help="comma list of hv,lg,solve: restrict the step (profiling runs)")
