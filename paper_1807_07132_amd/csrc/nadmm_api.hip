@@ -20,7 +20,7 @@ struct Layout {
   Shape s;
   size_t state, g, pdir, r, dvec, q;
   size_t drows, pcache, zx, zp;
-  size_t partial, loss_part, lpart, dotpart, zw;
+  size_t partial, loss_part, lpart, dotpart, rrpart, zw;
   size_t total;
   int gen_row_blocks, gen_slabs, gen_chunks, gen_rpc;
   int fused_parts, thin_parts, sliced_parts;
@@ -80,8 +80,9 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   L->loss_part = off; off += align256((size_t)lblocks * sizeof(double));
   L->lpart = off; off += align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
   L->dotpart = off; off += align256((size_t)reduce_out_blocks(s.d) * sizeof(double));
-  // per-slice partial logits of the column-sliced path (only where that path is the automatic choice)
-  L->zw = off; off += align256((L->sliced_ok && !L->fused_ok && !L->thin_ok) ? sliced_zw_bytes(s) : 0);
+  L->rrpart = off; off += align256((size_t)cg_update_blocks(s.d) * sizeof(double));
+  // per-slice partial logits of the column-sliced path
+  L->zw = off; off += align256(L->sliced_ok ? sliced_zw_bytes(s) : 0);
   L->total = off;
 }
 
@@ -119,7 +120,7 @@ int choose_path(const Layout& L, int* path) {
     return NADMM_OK;
   }
   if (g_path == 4) {
-    if (!L.sliced_ok || L.fused_ok || L.thin_ok) return NADMM_EUNSUPPORTED;  // workspace is sized for it only there
+    if (!L.sliced_ok) return NADMM_EUNSUPPORTED;
     *path = 4;
     return NADMM_OK;
   }
@@ -370,6 +371,7 @@ int nadmm_cg_solve(const nadmm_problem* prob, const float* d_X, const float* d_g
     cu.q = at<float>(d_ws, L.q);
     cu.dot_part = at<double>(d_ws, L.dotpart);
     cu.ndot = reduce_out_blocks(L.s.d);
+    cu.rr_part = at<double>(d_ws, L.rrpart);
     cu.d = L.s.d;
     cu.tol = tol;
     NADMM_HIP(launch_cg_update(cu, st));
@@ -525,6 +527,7 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
       cu.q = q;
       cu.dot_part = at<double>(d_ws, L.dotpart);
       cu.ndot = reduce_out_blocks(L.s.d);
+      cu.rr_part = at<double>(d_ws, L.rrpart);
       cu.d = L.s.d;
       cu.tol = params->cg_tol;
       NADMM_HIP(launch_cg_update(cu, st));

@@ -28,7 +28,11 @@ struct DevState {
   int32_t cg_iters;
   int32_t armijo_ok;
   int32_t ls_evals;
-  int32_t pad_[2];
+  int32_t cg_go;    // two-kernel CG update: the first kernel's verdict (active and positive curvature)
+  int32_t cg_ok;    //   0 if the first kernel met non-positive curvature
+  float cg_alpha;   //   step length of this CG iteration
+  int32_t pad_[3];
+  double rr_prev;   //   ||r||^2 before this CG iteration
   nadmm_stats stats;  // copied to the host at the end of nadmm_local_newton
 };
 
@@ -145,9 +149,11 @@ struct CgUpdateArgs {
   const float* q;
   const double* dot_part;  // partial sums of <d, q> left by the reduction that formed q
   int32_t ndot;
+  double* rr_part;         // cg_update_blocks(d) partial sums of the new ||r||^2 (two-kernel form, long vectors)
   int64_t d;
   float tol;
 };
+int cg_update_blocks(int64_t d);
 hipError_t launch_cg_update(const CgUpdateArgs& a, hipStream_t st);
 
 struct CgFinishArgs {

@@ -111,6 +111,7 @@ __global__ void state_init_kernel(DevState* st) {
   st->loss = 0.0; st->gg = 0.0; st->rr = 0.0; st->gg_cg = 0.0; st->loss_new = 0.0; st->loss_initial = 0.0;
   st->alpha = 0.f;
   st->newton_active = 1; st->cg_active = 1; st->cg_iters = 0; st->armijo_ok = 1; st->ls_evals = 0;
+  st->cg_go = 0; st->cg_ok = 1; st->cg_alpha = 0.f; st->rr_prev = 0.0;
   nadmm_stats* s = &st->stats;
   s->newton_iters = 0; s->cg_iters_total = 0; s->ls_evals_total = 0; s->armijo_failed = 0;
   s->loss_initial = 0.0; s->loss_final = 0.0; s->grad_norm_final = 0.0;
@@ -168,8 +169,9 @@ __global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs
 // One CG iteration's vector work, given q = H d:  a = rr / <d,q>; p += a d; r -= a q;
 // stop on ||r|| <= tol ||g|| (eq. inexact); else d = r + (rr'/rr) d.
 // <d, q> arrives as partial sums from the reduction that formed q.  Every vector is then read once:
-// pass 1 forms the new residual (kept in registers if PER > 0, d <= PER * 1024, else re-read) and its
-// norm, pass 2 updates the iterate and the direction.  Loads go out in blocks of 8 per vector and thread.
+// pass 1 forms the new residual (kept in registers, d <= PER * 1024) and its norm, pass 2 updates the
+// iterate and the direction.  Loads go out in blocks of 8 per vector and thread.  One workgroup: for
+// short vectors a second launch would cost more than the serial work.
 template <int PER>
 __global__ __launch_bounds__(kTail) void cg_update_kernel(const CgUpdateArgs a) {
   __shared__ double sm[17];
@@ -235,6 +237,87 @@ __global__ __launch_bounds__(kTail) void cg_update_kernel(const CgUpdateArgs a) 
     }
   }
   if (threadIdx.x == 0) {
+    st->rr = rr_new;
+    st->cg_iters += 1;
+    if (stop) st->cg_active = 0;
+  }
+}
+
+// The same update for long vectors (d > 24576), spread over several workgroups in two kernels; the sum
+// of the new ||r||^2 passes between them as per-workgroup partials, added in a fixed order.  Flags that
+// one kernel reads are never written by the same kernel: the first one reads cg_active and leaves its
+// verdict in cg_go, the second one reads cg_go and writes cg_active.
+constexpr int kCgThreads = 256;
+constexpr int kCgPerThread = 8;
+constexpr int kCgChunk = kCgThreads * kCgPerThread;
+
+__global__ __launch_bounds__(kCgThreads) void cg_residual_kernel(const CgUpdateArgs a) {
+  __shared__ double sm[17];
+  DevState* st = a.st;
+  const bool active = st->cg_active != 0;
+  const double dq = active ? partial_sum_block(a.dot_part, a.ndot, sm) : 0.0;
+  const bool curv = dq > 0.0 && isfinite(dq);
+  const double rr = st->rr;
+  const float al = curv ? (float)(rr / dq) : 0.f;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    st->cg_go = (active && curv) ? 1 : 0;
+    st->cg_ok = (!active || curv) ? 1 : 0;
+    st->cg_alpha = al;
+    st->rr_prev = rr;
+  }
+  if (!active || !curv) return;
+  double acc = 0.0;
+  for (int64_t base = (int64_t)blockIdx.x * kCgChunk; base < a.d; base += (int64_t)gridDim.x * kCgChunk) {
+    float y[kCgPerThread], re[kCgPerThread];
+#pragma unroll
+    for (int u = 0; u < kCgPerThread; ++u) {
+      const int64_t e = base + threadIdx.x + u * kCgThreads;
+      y[u] = e < a.d ? a.q[e] : 0.f;
+      re[u] = e < a.d ? a.r[e] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < kCgPerThread; ++u) {
+      const int64_t e = base + threadIdx.x + u * kCgThreads;
+      const float v = fmaf(-al, y[u], re[u]);
+      if (e < a.d) a.r[e] = v;
+      acc += (double)v * (double)v;
+    }
+  }
+  acc = block_sum(acc, sm);
+  if (threadIdx.x == 0) a.rr_part[blockIdx.x] = acc;
+}
+
+__global__ __launch_bounds__(kCgThreads) void cg_direction_kernel(const CgUpdateArgs a) {
+  __shared__ double sm[17];
+  DevState* st = a.st;
+  if (st->cg_go == 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0 && st->cg_ok == 0) st->cg_active = 0;  // no positive curvature
+    return;
+  }
+  const float al = st->cg_alpha;
+  const double rr = st->rr_prev;
+  const double rr_new = partial_sum_block(a.rr_part, (int)gridDim.x, sm);
+  const bool stop = sqrt(rr_new) <= (double)a.tol * sqrt(st->gg_cg);
+  const float be = (float)(rr_new / rr);
+  for (int64_t base = (int64_t)blockIdx.x * kCgChunk; base < a.d; base += (int64_t)gridDim.x * kCgChunk) {
+    float x[kCgPerThread], pe[kCgPerThread], re[kCgPerThread];
+#pragma unroll
+    for (int u = 0; u < kCgPerThread; ++u) {
+      const int64_t e = base + threadIdx.x + u * kCgThreads;
+      x[u] = e < a.d ? a.dvec[e] : 0.f;
+      pe[u] = e < a.d ? a.pdir[e] : 0.f;
+      re[u] = e < a.d ? a.r[e] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < kCgPerThread; ++u) {
+      const int64_t e = base + threadIdx.x + u * kCgThreads;
+      if (e < a.d) {
+        a.pdir[e] = fmaf(al, x[u], pe[u]);
+        if (!stop) a.dvec[e] = fmaf(be, x[u], re[u]);
+      }
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
     st->rr = rr_new;
     st->cg_iters += 1;
     if (stop) st->cg_active = 0;
@@ -407,11 +490,21 @@ hipError_t launch_newton_head(const NewtonHeadArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+int cg_update_blocks(int64_t d) {
+  int64_t b = (d + kCgChunk - 1) / kCgChunk;
+  return (int)(b < 64 ? b : 64);
+}
+
 hipError_t launch_cg_update(const CgUpdateArgs& a, hipStream_t st) {
-  if (a.d <= 8 * kTail) hipLaunchKernelGGL(cg_update_kernel<8>, dim3(1), dim3(kTail), 0, st, a);
-  else if (a.d <= 24 * kTail) hipLaunchKernelGGL(cg_update_kernel<24>, dim3(1), dim3(kTail), 0, st, a);
-  else if (a.d <= 40 * kTail) hipLaunchKernelGGL(cg_update_kernel<40>, dim3(1), dim3(kTail), 0, st, a);
-  else hipLaunchKernelGGL(cg_update_kernel<0>, dim3(1), dim3(kTail), 0, st, a);
+  if (a.d <= 8 * kTail) {
+    hipLaunchKernelGGL(cg_update_kernel<8>, dim3(1), dim3(kTail), 0, st, a);
+  } else if (a.d <= 24 * kTail) {
+    hipLaunchKernelGGL(cg_update_kernel<24>, dim3(1), dim3(kTail), 0, st, a);
+  } else {
+    const int blocks = cg_update_blocks(a.d);
+    hipLaunchKernelGGL(cg_residual_kernel, dim3(blocks), dim3(kCgThreads), 0, st, a);
+    hipLaunchKernelGGL(cg_direction_kernel, dim3(blocks), dim3(kCgThreads), 0, st, a);
+  }
   return hipGetLastError();
 }
 

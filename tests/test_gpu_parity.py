@@ -61,8 +61,9 @@ CASES = {
     "sliced_33x1604_C33": lambda: workloads.generic(33, 1604, 33, seed=26, x_std=0.03),
 }
 
-PATHS = [1, 2, 0]  # 1 = two-pass vector kernels forced, 2 = fused matrix-core kernel forced, 0 = automatic
-# (the thin-data and the column-sliced paths are the automatic choice wherever they apply)
+# 1 = two-pass vector kernels forced, 2 = fused matrix-core kernel forced, 4 = column-sliced two-sweep path forced,
+# 0 = automatic (the thin-data path is the automatic choice wherever it applies)
+PATHS = [1, 2, 4, 0]
 
 
 @pytest.fixture(scope="module")
