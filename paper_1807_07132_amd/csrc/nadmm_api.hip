@@ -184,8 +184,8 @@ RowArgs blank_rows() {
   return ra;
 }
 
-int reduce(const nadmm_problem* prob, const Layout& L, void* ws, int nparts, int kind, const float* XorV,
-           float* out, double* dot_part, const int32_t* flag, hipStream_t st) {
+ReduceArgs reduce_args(const nadmm_problem* prob, const Layout& L, void* ws, int nparts, int kind, const float* XorV,
+                       float* out, double* dot_part, const int32_t* flag) {
   ReduceArgs r;
   std::memset(&r, 0, sizeof(r));
   r.partial = at<float>(ws, L.partial);
@@ -202,13 +202,19 @@ int reduce(const nadmm_problem* prob, const Layout& L, void* ws, int nparts, int
   r.out = out;
   r.dot_part = dot_part;
   r.flag = flag;
-  NADMM_HIP(launch_reduce_out(r, st));
+  return r;
+}
+
+int reduce(const nadmm_problem* prob, const Layout& L, void* ws, int nparts, int kind, const float* XorV,
+           float* out, double* dot_part, const int32_t* flag, hipStream_t st) {
+  NADMM_HIP(launch_reduce_out(reduce_args(prob, L, ws, nparts, kind, XorV, out, dot_part, flag), st));
   return NADMM_OK;
 }
 
-// q = H(X) v.  With X == NULL the probabilities cached in the workspace are used.
+// q = H(X) v.  With X == NULL the probabilities cached in the workspace are used.  With out == NULL only
+// the partial sums of A^T D are formed (*nparts_out of them) and the caller finishes q.
 int hv_apply(const nadmm_problem* prob, const Layout& L, int path, void* ws, const float* X, bool write_pcache,
-             const float* v, float* out, double* dot_part, const int32_t* flag, hipStream_t st) {
+             const float* v, float* out, double* dot_part, const int32_t* flag, int* nparts_out, hipStream_t st) {
   RowArgs ra = blank_rows();
   ra.kind = kRowsHv;
   ra.B0 = X;
@@ -220,7 +226,39 @@ int hv_apply(const nadmm_problem* prob, const Layout& L, int path, void* ws, con
   int nparts = 0;
   int rc = sweep(prob, L, path, ws, ra, true, &nparts, st);
   if (rc != NADMM_OK) return rc;
+  if (nparts_out) *nparts_out = nparts;
+  if (out == nullptr) return NADMM_OK;
   return reduce(prob, L, ws, nparts, 0, v, out, dot_part, flag, st);
+}
+
+// One CG iteration after the initialisation: q = H d, then the update of p, r, d (Section 2.4).
+int cg_iteration(const nadmm_problem* prob, const Layout& L, int path, void* ws, DevState* ds, const float* X,
+                 bool write_pcache, float tol, hipStream_t st) {
+  float* dvec = at<float>(ws, L.dvec);
+  float* q = at<float>(ws, L.q);
+  CgUpdateArgs cu;
+  cu.st = ds;
+  cu.pdir = at<float>(ws, L.pdir);
+  cu.r = at<float>(ws, L.r);
+  cu.dvec = dvec;
+  cu.q = q;
+  cu.dot_part = at<double>(ws, L.dotpart);
+  cu.ndot = reduce_out_blocks(L.s.d);
+  cu.rr_part = at<double>(ws, L.rrpart);
+  cu.d = L.s.d;
+  cu.tol = tol;
+  const int parts = path == 3 ? L.thin_parts : (path == 2 ? L.fused_parts : (path == 4 ? L.sliced_parts : L.gen_chunks));
+  if (cg_fused_tail_supported(L.s.d, parts)) {
+    int nparts = 0;
+    int rc = hv_apply(prob, L, path, ws, X, write_pcache, dvec, nullptr, nullptr, &ds->cg_active, &nparts, st);
+    if (rc != NADMM_OK) return rc;
+    NADMM_HIP(launch_cg_reduce_update(reduce_args(prob, L, ws, nparts, 0, dvec, q, nullptr, &ds->cg_active), cu, st));
+    return NADMM_OK;
+  }
+  int rc = hv_apply(prob, L, path, ws, X, write_pcache, dvec, q, at<double>(ws, L.dotpart), &ds->cg_active, nullptr, st);
+  if (rc != NADMM_OK) return rc;
+  NADMM_HIP(launch_cg_update(cu, st));
+  return NADMM_OK;
 }
 
 void fill_alphas(float* alphas, int ncand, float gamma) {
@@ -331,7 +369,7 @@ int nadmm_hessvec(const nadmm_problem* prob, const float* d_X, const float* d_V,
   if ((rc = check_ws(L, d_ws, ws_bytes)) != NADMM_OK) return rc;
   int path = 0;
   if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
-  return hv_apply(prob, L, path, d_ws, d_X, false, d_V, d_HV, nullptr, nullptr, (hipStream_t)stream);
+  return hv_apply(prob, L, path, d_ws, d_X, false, d_V, d_HV, nullptr, nullptr, nullptr, (hipStream_t)stream);
 }
 
 int nadmm_cg_solve(const nadmm_problem* prob, const float* d_X, const float* d_g, float* d_p, int max_iter,
@@ -360,21 +398,7 @@ int nadmm_cg_solve(const nadmm_problem* prob, const float* d_X, const float* d_g
   NADMM_HIP(launch_newton_head(nh, st));
 
   for (int k = 0; k < max_iter; ++k) {
-    rc = hv_apply(prob, L, path, d_ws, k == 0 ? d_X : nullptr, true, at<float>(d_ws, L.dvec), at<float>(d_ws, L.q),
-                  at<double>(d_ws, L.dotpart), &ds->cg_active, st);
-    if (rc != NADMM_OK) return rc;
-    CgUpdateArgs cu;
-    cu.st = ds;
-    cu.pdir = at<float>(d_ws, L.pdir);
-    cu.r = at<float>(d_ws, L.r);
-    cu.dvec = at<float>(d_ws, L.dvec);
-    cu.q = at<float>(d_ws, L.q);
-    cu.dot_part = at<double>(d_ws, L.dotpart);
-    cu.ndot = reduce_out_blocks(L.s.d);
-    cu.rr_part = at<double>(d_ws, L.rrpart);
-    cu.d = L.s.d;
-    cu.tol = tol;
-    NADMM_HIP(launch_cg_update(cu, st));
+    if ((rc = cg_iteration(prob, L, path, d_ws, ds, k == 0 ? d_X : nullptr, true, tol, st)) != NADMM_OK) return rc;
   }
   CgFinishArgs cf;
   cf.st = ds;
@@ -475,7 +499,6 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
   float* pdir = at<float>(d_ws, L.pdir);
   float* r = at<float>(d_ws, L.r);
   float* dvec = at<float>(d_ws, L.dvec);
-  float* q = at<float>(d_ws, L.q);
 
   NADMM_HIP(launch_state_init(ds, st));
   const int ncand = params->max_ls + 2;
@@ -518,19 +541,7 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
 
     // CG on H p = -g with the probabilities of this iterate
     for (int k = 0; k < params->max_cg; ++k) {
-      if ((rc = hv_apply(prob, L, path, d_ws, nullptr, false, dvec, q, at<double>(d_ws, L.dotpart), &ds->cg_active, st)) != NADMM_OK) return rc;
-      CgUpdateArgs cu;
-      cu.st = ds;
-      cu.pdir = pdir;
-      cu.r = r;
-      cu.dvec = dvec;
-      cu.q = q;
-      cu.dot_part = at<double>(d_ws, L.dotpart);
-      cu.ndot = reduce_out_blocks(L.s.d);
-      cu.rr_part = at<double>(d_ws, L.rrpart);
-      cu.d = L.s.d;
-      cu.tol = params->cg_tol;
-      NADMM_HIP(launch_cg_update(cu, st));
+      if ((rc = cg_iteration(prob, L, path, d_ws, ds, nullptr, false, params->cg_tol, st)) != NADMM_OK) return rc;
     }
 
     // Armijo backtracking on Z(alpha) = A X + alpha A p, then X += alpha p

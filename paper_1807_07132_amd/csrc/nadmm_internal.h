@@ -154,6 +154,10 @@ struct CgUpdateArgs {
   float tol;
 };
 int cg_update_blocks(int64_t d);
+// Small problems (d <= 1024 and at most 64 partial sums per thread): the reduction of the partial sums
+// of A^T D, the linear term and the whole CG update in one single-workgroup kernel.
+bool cg_fused_tail_supported(int64_t d, int nparts);
+hipError_t launch_cg_reduce_update(const ReduceArgs& r, const CgUpdateArgs& a, hipStream_t st);
 hipError_t launch_cg_update(const CgUpdateArgs& a, hipStream_t st);
 
 struct CgFinishArgs {

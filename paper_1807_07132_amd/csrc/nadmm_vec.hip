@@ -324,6 +324,66 @@ __global__ __launch_bounds__(kCgThreads) void cg_direction_kernel(const CgUpdate
   }
 }
 
+// Small problems: q = s sum_k partial[k] + (lambda + rho) d and the CG update above in one kernel.
+// Thread t sums the partials k = g, g + G, ... of element e = t mod d (g = t / d, G = 1024 / d groups),
+// the G group sums are added in order.
+__global__ __launch_bounds__(kTail) void cg_reduce_update_kernel(const ReduceArgs ra, const CgUpdateArgs a) {
+  __shared__ double sm[17];
+  __shared__ float gsum[kTail];
+  DevState* st = a.st;
+  if (st->cg_active == 0) return;
+  const int d = (int)a.d;
+  const int groups = kTail / d;
+  const int t = threadIdx.x;
+  const int e = t % d, g = t / d;
+  float sum = 0.f;
+  if (g < groups) {
+    const float* __restrict__ pp = ra.partial + e;
+    int k = g;
+    for (; k + 7 * groups < ra.nparts; k += 8 * groups) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = pp[(size_t)(k + u * groups) * d];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) sum += v[u];
+    }
+    for (; k < ra.nparts; k += groups) sum += pp[(size_t)k * d];
+  }
+  gsum[t] = sum;
+  __syncthreads();
+  const bool mine = t < d;
+  float dv = 0.f, qv = 0.f;
+  if (mine) {
+    float s2 = 0.f;
+    for (int g2 = 0; g2 < groups; ++g2) s2 += gsum[g2 * d + t];
+    dv = a.dvec[t];
+    qv = fmaf(ra.lambda + ra.rho, dv, ra.scale * s2);
+  }
+  const double dq = block_sum((double)dv * (double)qv, sm);
+  const double rr = st->rr;
+  const double gg = st->gg_cg;
+  if (!(dq > 0.0) || !isfinite(dq)) {  // no positive curvature: keep the current iterate
+    __syncthreads();
+    if (t == 0) st->cg_active = 0;
+    return;
+  }
+  const float al = (float)(rr / dq);
+  const float rn = mine ? fmaf(-al, qv, a.r[t]) : 0.f;
+  const double rr_new = block_sum((double)rn * (double)rn, sm);
+  const bool stop = sqrt(rr_new) <= (double)a.tol * sqrt(gg);
+  const float be = (float)(rr_new / rr);
+  if (mine) {
+    a.r[t] = rn;
+    a.pdir[t] = fmaf(al, dv, a.pdir[t]);
+    if (!stop) a.dvec[t] = fmaf(be, dv, rn);
+  }
+  if (t == 0) {
+    st->rr = rr_new;
+    st->cg_iters += 1;
+    if (stop) st->cg_active = 0;
+  }
+}
+
 __global__ __launch_bounds__(256) void cg_finish_kernel(const CgFinishArgs a) {
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < a.d; e += (int64_t)gridDim.x * blockDim.x)
     a.p_out[e] = a.pdir[e];
@@ -505,6 +565,17 @@ hipError_t launch_cg_update(const CgUpdateArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(cg_residual_kernel, dim3(blocks), dim3(kCgThreads), 0, st, a);
     hipLaunchKernelGGL(cg_direction_kernel, dim3(blocks), dim3(kCgThreads), 0, st, a);
   }
+  return hipGetLastError();
+}
+
+bool cg_fused_tail_supported(int64_t d, int nparts) {
+  if (d < 1 || d > kTail) return false;
+  const int groups = kTail / (int)d;
+  return (nparts + groups - 1) / groups <= 64;
+}
+
+hipError_t launch_cg_reduce_update(const ReduceArgs& r, const CgUpdateArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(cg_reduce_update_kernel, dim3(1), dim3(kTail), 0, st, r, a);
   return hipGetLastError();
 }
 
