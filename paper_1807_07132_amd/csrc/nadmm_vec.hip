@@ -79,22 +79,48 @@ __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
   }
 }
 
+// The single-workgroup tail kernels walk vectors of d elements.  Loads go out in blocks of kBlk per
+// vector and thread before any of them is used, so that a pass costs a few memory round trips
+// instead of one per element and thread.
+constexpr int kBlk = 4;
+
 // lambda/2 ||X||^2 + rho/2 ||X - z + y/rho||^2, summed over the workgroup
 __device__ __forceinline__ double penalty_block(const float* X, const float* z, const float* y, int64_t d,
                                                 float lambda, float rho, double* sm) {
   double acc = 0.0;
   const double inv_rho = 1.0 / (double)rho;
-  for (int64_t e = threadIdx.x; e < d; e += blockDim.x) {
-    const double x = X[e];
-    const double u = x - (z ? (double)z[e] : 0.0) + (y ? (double)y[e] : 0.0) * inv_rho;
-    acc += 0.5 * (double)lambda * x * x + 0.5 * (double)rho * u * u;
+  for (int64_t e0 = threadIdx.x; e0 < d; e0 += (int64_t)kBlk * blockDim.x) {
+    float xv[kBlk], zv[kBlk], yv[kBlk];
+#pragma unroll
+    for (int u = 0; u < kBlk; ++u) {
+      const int64_t e = e0 + (int64_t)u * blockDim.x;
+      const bool ok = e < d;
+      xv[u] = ok ? X[e] : 0.f;
+      zv[u] = (ok && z) ? z[e] : 0.f;
+      yv[u] = (ok && y) ? y[e] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < kBlk; ++u) {
+      const double x = xv[u];
+      const double uu = x - (double)zv[u] + (double)yv[u] * inv_rho;
+      acc += 0.5 * (double)lambda * x * x + 0.5 * (double)rho * uu * uu;  // zero for the padding (x = z = y = 0)
+    }
   }
   return block_sum(acc, sm);
 }
 
 __device__ __forceinline__ double partial_sum_block(const double* part, int n, double* sm) {
   double acc = 0.0;
-  for (int k = threadIdx.x; k < n; k += blockDim.x) acc += part[k];
+  for (int k0 = threadIdx.x; k0 < n; k0 += kBlk * blockDim.x) {
+    double v[kBlk];
+#pragma unroll
+    for (int u = 0; u < kBlk; ++u) {
+      const int k = k0 + u * blockDim.x;
+      v[u] = k < n ? part[k] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < kBlk; ++u) acc += v[u];
+  }
   return block_sum(acc, sm);
 }
 
@@ -128,12 +154,23 @@ __global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs
   if (a.newton_mode && st->newton_active == 0) return;
 
   double gg = 0.0;
-  for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) {
-    const float g = a.g[e];
-    gg += (double)g * (double)g;
-    a.pdir[e] = 0.f;
-    a.r[e] = -g;
-    a.dvec[e] = -g;
+  for (int64_t e0 = threadIdx.x; e0 < a.d; e0 += (int64_t)kBlk * blockDim.x) {
+    float gv[kBlk];
+#pragma unroll
+    for (int u = 0; u < kBlk; ++u) {
+      const int64_t e = e0 + (int64_t)u * blockDim.x;
+      gv[u] = e < a.d ? a.g[e] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < kBlk; ++u) {
+      const int64_t e = e0 + (int64_t)u * blockDim.x;
+      gg += (double)gv[u] * (double)gv[u];
+      if (e < a.d) {
+        a.pdir[e] = 0.f;
+        a.r[e] = -gv[u];
+        a.dvec[e] = -gv[u];
+      }
+    }
   }
   gg = block_sum(gg, sm);
 
@@ -393,18 +430,22 @@ __global__ __launch_bounds__(256) void cg_finish_kernel(const CgFinishArgs a) {
   }
 }
 
-// Row losses at Z = Zx + alpha Zp for a group of candidate step sizes (Sections 2.1, 2.2).
+// Row losses at Z = Zx + alpha Zp for all candidate step sizes (Sections 2.1, 2.2); the cached logits are
+// read once per 16 candidates.
 template <int NCP>
 __global__ __launch_bounds__(256) void ls_eval_kernel(const LsEvalArgs a) {
   if (a.flag != nullptr && *a.flag == 0) return;
   __shared__ double sm[17];
   const int NC = a.NC;
   const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int k0 = 0; k0 < a.ncand; k0 += 4) {
-    float al[4];
+  constexpr int G = 16;  // candidates per pass over the cached logits (the usual 12 take one pass)
+  for (int k0 = 0; k0 < a.ncand; k0 += G) {
+    float al[G];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) al[kk] = (k0 + kk < a.ncand) ? a.alphas[k0 + kk] : 0.f;
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int kk = 0; kk < G; ++kk) al[kk] = (k0 + kk < a.ncand) ? a.alphas[k0 + kk] : 0.f;
+    double acc[G];
+#pragma unroll
+    for (int kk = 0; kk < G; ++kk) acc[kk] = 0.0;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < a.n; i += stride) {
       float zx[NCP], zp[NCP];
       const size_t ro = (size_t)i * NC;
@@ -415,28 +456,32 @@ __global__ __launch_bounds__(256) void ls_eval_kernel(const LsEvalArgs a) {
       }
       const int b = a.labels[i];
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        float M = 0.f, zb = 0.f;
-        float zz[NCP];
+      for (int kk = 0; kk < G; ++kk) {
+        if (k0 + kk < a.ncand) {  // uniform
+          float M = 0.f, zb = 0.f;
+          float zz[NCP];
 #pragma unroll
-        for (int c = 0; c < NCP; ++c) {
-          zz[c] = fmaf(al[kk], zp[c], zx[c]);
-          if (c < NC) {
-            M = fmaxf(M, zz[c]);
-            if (c == b) zb = zz[c];
+          for (int c = 0; c < NCP; ++c) {
+            zz[c] = fmaf(al[kk], zp[c], zx[c]);
+            if (c < NC) {
+              M = fmaxf(M, zz[c]);
+              if (c == b) zb = zz[c];
+            }
           }
-        }
-        float alpha = expf(-M);
+          float alpha = expf(-M);
 #pragma unroll
-        for (int c = 0; c < NCP; ++c)
-          if (c < NC) alpha += expf(zz[c] - M);
-        acc[kk] += (double)M + (double)logf(alpha) - (double)zb;
+          for (int c = 0; c < NCP; ++c)
+            if (c < NC) alpha += expf(zz[c] - M);
+          acc[kk] += (double)M + (double)logf(alpha) - (double)zb;
+        }
       }
     }
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const double t = block_sum(acc[kk], sm);
-      if (threadIdx.x == 0 && k0 + kk < a.ncand) a.lpart[(size_t)blockIdx.x * kCandSlots + k0 + kk] = t;
+    for (int kk = 0; kk < G; ++kk) {
+      if (k0 + kk < a.ncand) {  // uniform
+        const double t = block_sum(acc[kk], sm);
+        if (threadIdx.x == 0) a.lpart[(size_t)blockIdx.x * kCandSlots + k0 + kk] = t;
+      }
     }
   }
 }
@@ -453,21 +498,44 @@ __global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int k = wave; k < nslots; k += kTail / 64) {
     double acc = 0.0;
-    for (int b = lane; b < a.nblocks; b += 64) acc += a.lpart[(size_t)b * kCandSlots + k];
+    for (int b0 = lane; b0 < a.nblocks; b0 += 64 * kBlk) {
+      double v[kBlk];
+#pragma unroll
+      for (int u = 0; u < kBlk; ++u) {
+        const int b = b0 + 64 * u;
+        v[u] = b < a.nblocks ? a.lpart[(size_t)b * kCandSlots + k] : 0.0;
+      }
+#pragma unroll
+      for (int u = 0; u < kBlk; ++u) acc += v[u];
+    }
     acc = wave_sum(acc);
     if (lane == 0) cand[k] = acc;
   }
   // penalty along the line: q0 + alpha q1 + alpha^2 q2, and the slope <p, g>
   double q0 = 0.0, q1 = 0.0, q2 = 0.0, sl = 0.0;
   const double inv_rho = 1.0 / (double)a.rho;
-  for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) {
-    const double x = a.X[e];
-    const double u = x - (a.z ? (double)a.z[e] : 0.0) + (a.y ? (double)a.y[e] : 0.0) * inv_rho;
-    const double pv = a.pdir[e];
-    q0 += 0.5 * (double)a.lambda * x * x + 0.5 * (double)a.rho * u * u;
-    q1 += (double)a.lambda * x * pv + (double)a.rho * u * pv;
-    q2 += 0.5 * ((double)a.lambda + (double)a.rho) * pv * pv;
-    sl += pv * (double)a.g[e];
+  for (int64_t e0 = threadIdx.x; e0 < a.d; e0 += (int64_t)kBlk * blockDim.x) {
+    float xv[kBlk], zv[kBlk], yv[kBlk], pvv[kBlk], gv[kBlk];
+#pragma unroll
+    for (int u = 0; u < kBlk; ++u) {
+      const int64_t e = e0 + (int64_t)u * blockDim.x;
+      const bool ok = e < a.d;
+      xv[u] = ok ? a.X[e] : 0.f;
+      zv[u] = (ok && a.z) ? a.z[e] : 0.f;
+      yv[u] = (ok && a.y) ? a.y[e] : 0.f;
+      pvv[u] = ok ? a.pdir[e] : 0.f;
+      gv[u] = ok ? a.g[e] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < kBlk; ++u) {  // the padding (all zero) adds nothing
+      const double x = xv[u];
+      const double uu = x - (double)zv[u] + (double)yv[u] * inv_rho;
+      const double pv = pvv[u];
+      q0 += 0.5 * (double)a.lambda * x * x + 0.5 * (double)a.rho * uu * uu;
+      q1 += (double)a.lambda * x * pv + (double)a.rho * uu * pv;
+      q2 += 0.5 * ((double)a.lambda + (double)a.rho) * pv * pv;
+      sl += pv * (double)gv[u];
+    }
   }
   q0 = block_sum(q0, sm);
   q1 = block_sum(q1, sm);
@@ -510,7 +578,20 @@ __global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a) {
   __syncthreads();
   if (a.X_apply != nullptr) {
     const float alpha = s_alpha;
-    for (int64_t e = threadIdx.x; e < a.d; e += blockDim.x) a.X_apply[e] = fmaf(alpha, a.pdir[e], a.X_apply[e]);
+    for (int64_t e0 = threadIdx.x; e0 < a.d; e0 += (int64_t)kBlk * blockDim.x) {
+      float pvv[kBlk], xv[kBlk];
+#pragma unroll
+      for (int u = 0; u < kBlk; ++u) {
+        const int64_t e = e0 + (int64_t)u * blockDim.x;
+        pvv[u] = e < a.d ? a.pdir[e] : 0.f;
+        xv[u] = e < a.d ? a.X_apply[e] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < kBlk; ++u) {
+        const int64_t e = e0 + (int64_t)u * blockDim.x;
+        if (e < a.d) a.X_apply[e] = fmaf(alpha, pvv[u], xv[u]);
+      }
+    }
   }
 }
 
