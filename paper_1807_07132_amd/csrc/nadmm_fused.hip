@@ -21,18 +21,12 @@
 #include "nadmm_internal.h"
 #include "nadmm_mfma.h"
 
-#ifndef NADMM_EXP
-#define NADMM_EXP 0  // timing experiments only (non-zero values skip work and give wrong results)
-#endif
-
 namespace nadmm {
 namespace {
 
 using namespace mfma_detail;
 
-__device__ __forceinline__ void tile_barrier() {
-  if (NADMM_EXP != 4 && NADMM_EXP != 5) __syncthreads();
-}
+__device__ __forceinline__ void tile_barrier() { __syncthreads(); }
 
 constexpr int kThreads = 512;
 constexpr int kWaves = 8;
@@ -182,7 +176,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
         }
         // the registers are free again: prefetch the next tile (past the range the rows clamp to the last row)
         load_step(i, row0 + kTileRows);
-        if (with_cols && NADMM_EXP != 2 && NADMM_EXP != 3 && NADMM_EXP != 5) {
+        if (with_cols) {
           // transposed copy for phase 2: pair (row m, row m+16) of one column per 32-bit word
           char* base = cm + (size_t)s * kStepBytes;
 #pragma unroll
@@ -228,9 +222,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
       continue;
     }
     float P, M = 0.f, alpha = 1.f, d;
-    if (NADMM_EXP == 3 || NADMM_EXP == 5) {
-      P = z;
-    } else if (has0) {
+    if (has0) {
       const float zc = cv ? z : 0.f;
       M = row16_max(zc);                   // max{0, Z_1..Z_{C-1}}: padded lanes supply the 0
       const float E = cv ? expf(zc - M) : 0.f;
@@ -282,8 +274,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
           const int off = cm_offset(16 * h + m, kg);
           const u32x4 thi = *reinterpret_cast<const u32x4*>(base + off);
           const u32x4 tlo = *reinterpret_cast<const u32x4*>(base + 2048 + off);
-          if (NADMM_EXP != 1 && NADMM_EXP != 2 && NADMM_EXP != 3 && NADMM_EXP != 5) acc2[i][h] = mfma3(dhi, dlo, thi, tlo, acc2[i][h]);
-          else acc2[i][h] += __builtin_bit_cast(f32x4, thi) + __builtin_bit_cast(f32x4, tlo);
+          acc2[i][h] = mfma3(dhi, dlo, thi, tlo, acc2[i][h]);
         }
       }
     }
