@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--workload", default="image_like")
     ap.add_argument("--n", type=int, default=None, help="override the number of rows (testing only)")
     ap.add_argument("--path", type=int, default=0, help="kernel path: 0 auto, 1 two-pass, 2 fused, 3 thin, 4 column-sliced")
+    ap.add_argument("--admm-workers", type=int, default=4,
+                    help="simulated ADMM workers for the outer-iteration timing in extra (0 or 1: skip)")
+    ap.add_argument("--admm-outer", type=int, default=2, help="outer iterations timed for that figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--only", default="", help="comma list of hv,lg,solve: restrict the step (profiling runs)")
@@ -164,6 +167,38 @@ def main():
         del gp2, pair
     tot = {k: sum(v) for k, v in ms.items()}
 
+    # Outside the timed steps: Algorithm 1 with the rows of A split over simulated workers (one after the
+    # other on this GPU, fixed penalty): time of one outer iteration and of the consensus step alone.
+    admm = None
+    if args.admm_workers > 1 and not only:
+        N = args.admm_workers
+        bounds = [w.n * i // N for i in range(N + 1)]
+        shards = [nadmm.Problem(gp.A[bounds[i]:bounds[i + 1]], gp.labels[bounds[i]:bounds[i + 1]], w.C, w.s, 0.0, w.rho)
+                  for i in range(N)]
+        ap = nadmm.make_admm_params(args.admm_outer, params)
+        aws = torch.empty(nadmm.nadmm_admm_workspace_bytes(shards, ap), dtype=torch.uint8, device="cuda")
+        xw = torch.stack([X] * N).contiguous()
+        nadmm.nadmm_admm_solve(shards, w.lam, xw, ap, want_stats=False, ws=aws)   # warm-up
+        xw.copy_(torch.stack([X] * N))
+        e0, e1 = ev(), ev()
+        e0.record()
+        nadmm.nadmm_admm_solve(shards, w.lam, xw, ap, want_stats=False, ws=aws)
+        e1.record()
+        torch.cuda.synchronize()
+        t_admm = e0.elapsed_time(e1) / 1e3 / args.admm_outer
+        uw, zw = torch.zeros_like(xw), torch.zeros_like(X)
+        for _ in range(3):
+            nadmm.nadmm_admm_consensus(xw, uw, zw, [w.rho] * N, w.lam, ws=aws)
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(20):
+            nadmm.nadmm_admm_consensus(xw, uw, zw, [w.rho] * N, w.lam, ws=aws)
+        e1.record()
+        torch.cuda.synchronize()
+        admm = {"workers": N, "outer_iterations_timed": args.admm_outer, "seconds_per_outer_iteration": t_admm,
+                "consensus_step_us": e0.elapsed_time(e1) * 1e3 / 20}
+        del shards, aws, xw, uw, zw
+
     n, p, NC = w.n, w.p, w.C - 1
     d = p * NC
     bytes_hv = 4.0 * n * p + 3 * 4.0 * d
@@ -199,6 +234,8 @@ def main():
         extra["local_solve_passes_over_A"] = passes
         extra["local_solve_hbm_frac"] = passes * 4.0 * n * p / per_solve_s / 1e9 / HBM_PEAK_GBS
 
+    if admm is not None:
+        extra["admm"] = admm
     out = {
         "metric": "Hv products/s (n=60k,p=784,C=10); loss+grad/s and local Newton-CG solve seconds in extra",
         "value": value, "unit": "Hv/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

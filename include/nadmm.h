@@ -161,6 +161,66 @@ int nadmm_line_search(const nadmm_problem* prob, const float* d_X, const float* 
 int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params* params,
                        nadmm_stats* h_stats, void* d_ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * ADMM outer solver with N workers simulated on one GPU (Algorithm 1 with fixed penalty parameters;
+ * Section 2.3: x-, z-, y-updates, closed-form z-update for g(z) = lambda/2 ||z||^2; Section 2.3.1:
+ * residuals and stopping).  The workers' local solves run one after the other on the one device.
+ *
+ * Multipliers are kept in the sign convention of nadmm_problem.d_y: u_i = -y_i of the paper, so
+ *   z   = sum_i (rho_i x_i + u_i) / (lambda + sum_i rho_i)
+ *   u_i = u_i + rho_i (x_i - z)
+ *   r_i = z - x_i,  d_i = -rho_i (z - z_prev)
+ * Stopping compares the stacked norms ||r||, ||d|| with
+ *   eps_pri  = sqrt(N) eps_abs + eps_rel max{ sqrt(sum_i ||x_i||^2), sqrt(N) ||z|| }
+ *   eps_dual = sqrt(d) eps_abs + eps_rel sqrt(sum_i ||u_i||^2)
+ * (the printed tolerances with every squared norm read as the norm).
+ * ------------------------------------------------------------------------------------------------ */
+#define NADMM_MAX_WORKERS 64
+
+typedef struct nadmm_admm_params {
+  int32_t      max_outer;   /* ADMM iterations */
+  float        eps_abs;     /* both tolerances 0: run max_outer iterations */
+  float        eps_rel;
+  nadmm_params local;       /* Algorithm 3, run on every worker in every iteration */
+} nadmm_admm_params;
+
+typedef struct nadmm_admm_stats {
+  int32_t outer_iters;      /* iterations performed */
+  int32_t converged;        /* 1 if the residual test stopped the iteration */
+  double  r_norm, d_norm, eps_pri, eps_dual;     /* of the last iteration */
+  double  r_trace[NADMM_TRACE_LEN];              /* per iteration (first NADMM_TRACE_LEN) */
+  double  d_trace[NADMM_TRACE_LEN];
+} nadmm_admm_stats;
+
+/*
+ * Workspace for nadmm_admm_solve / nadmm_admm_consensus: the largest local workspace of the N
+ * workers plus the consensus state.  h_workers: host array of N problem descriptions (shards of the
+ * rows of A; same p and C).  Returns 0 on invalid arguments.
+ */
+size_t nadmm_admm_workspace_bytes(const nadmm_problem* h_workers, int32_t N, const nadmm_admm_params* params);
+
+/*
+ * One consensus step (z-, y-update, residuals, tolerances) on device-resident iterates:
+ * d_x N x d (row i = x_i), d_u N x d (multipliers, updated in place), d_z d (z_prev in, z out),
+ * h_rho host array of N penalties.  d_out (device, 4 doubles): ||r||, ||d||, eps_pri, eps_dual.
+ * d_ws: at least nadmm_admm_workspace_bytes() (or 64 KiB if only this call is used), 256-byte aligned.
+ */
+int nadmm_admm_consensus(int32_t N, int64_t d, const float* d_x, float* d_u, float* d_z, const float* h_rho,
+                         float lambda, float eps_abs, float eps_rel, double* d_out,
+                         void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Algorithm 1.  h_workers[i]: shard i (d_A, n, p, lda, d_labels, C, loss_scale, rho = rho_i; its lambda,
+ * d_z, d_y are ignored: the local subproblems have no regulariser and use d_z, d_u below).
+ * d_x: N x d, x_i^0 on entry, x_i on return.  d_u: N x d (out; zero-initialised by the call), d_z: d (out;
+ * zero-initialised).  Everything is enqueued on `stream`; after the residual test has stopped the
+ * iteration the remaining kernels are no-ops.  h_stats (host) may be NULL; if not, the stream is
+ * synchronised before return.
+ */
+int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, float* d_x, float* d_u, float* d_z,
+                     const nadmm_admm_params* params, nadmm_admm_stats* h_stats,
+                     void* d_ws, size_t ws_bytes, void* stream);
+
 /*
  * Kernel selection, for tests and benchmarks (process-wide, not thread-safe):
  *   0 = automatic (default), 1 = two-pass fp32 vector kernels (any shape),

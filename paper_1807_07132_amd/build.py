@@ -14,7 +14,8 @@ INCLUDE = os.path.join(ROOT, "include")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnadmm.so")
 
-SOURCES = ["nadmm_api.hip", "nadmm_generic.hip", "nadmm_vec.hip", "nadmm_fused.hip", "nadmm_thin.hip", "nadmm_sliced.hip"]
+SOURCES = ["nadmm_api.hip", "nadmm_generic.hip", "nadmm_vec.hip", "nadmm_fused.hip", "nadmm_thin.hip", "nadmm_sliced.hip",
+           "nadmm_admm.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -280,6 +280,141 @@ int validate_ls(float beta, float gamma, int max_ls) {
 
 using namespace nadmm;
 
+static int validate_params(const nadmm_params* params) {
+  if (params == nullptr) return NADMM_EINVAL;
+  if (params->max_newton < 0 || params->max_cg < 0 || !(params->cg_tol >= 0.f) || !(params->grad_tol >= 0.f))
+    return NADMM_EINVAL;
+  return validate_ls(params->armijo_beta, params->backtrack_gamma, params->max_ls);
+}
+
+// Enqueues Algorithm 3 (arguments already validated).  outer_flag: see launch_state_init.
+static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nadmm_params* params, const Layout& L,
+                                int path, void* d_ws, const int32_t* outer_flag, hipStream_t st) {
+  int rc = NADMM_OK;
+  DevState* ds = at<DevState>(d_ws, L.state);
+  float* g = at<float>(d_ws, L.g);
+  float* pdir = at<float>(d_ws, L.pdir);
+  float* r = at<float>(d_ws, L.r);
+  float* dvec = at<float>(d_ws, L.dvec);
+
+  NADMM_HIP(launch_state_init(ds, outer_flag, st));
+  const int ncand = params->max_ls + 2;
+
+  for (int t = 0; t < params->max_newton; ++t) {
+    // gradient and objective at X; caches the probabilities and the logits A X
+    RowArgs ra = blank_rows();
+    ra.kind = kRowsGrad;
+    ra.B0 = d_X;
+    ra.labels = prob->d_labels;
+    ra.rows_out = at<float>(d_ws, L.drows);
+    ra.Pout = at<float>(d_ws, L.pcache);
+    ra.Z0out = at<float>(d_ws, L.zx);
+    ra.loss_part = at<double>(d_ws, L.loss_part);
+    ra.flag = &ds->newton_active;
+    int nparts = 0;
+    if ((rc = sweep(prob, L, path, d_ws, ra, true, &nparts, st)) != NADMM_OK) return rc;
+    if ((rc = reduce(prob, L, d_ws, nparts, 1, d_X, g, nullptr, &ds->newton_active, st)) != NADMM_OK) return rc;
+
+    NewtonHeadArgs nh;
+    std::memset(&nh, 0, sizeof(nh));
+    nh.st = ds;
+    nh.loss_part = at<double>(d_ws, L.loss_part);
+    nh.nblocks = loss_blocks(L, path);
+    nh.scale = prob->loss_scale;
+    nh.lambda = prob->lambda;
+    nh.rho = prob->rho;
+    nh.X = d_X;
+    nh.z = prob->d_z;
+    nh.y = prob->d_y;
+    nh.g = g;
+    nh.pdir = pdir;
+    nh.r = r;
+    nh.dvec = dvec;
+    nh.d = L.s.d;
+    nh.iter = t;
+    nh.grad_tol = params->grad_tol;
+    nh.newton_mode = 1;
+    NADMM_HIP(launch_newton_head(nh, st));
+
+    // CG on H p = -g with the probabilities of this iterate
+    for (int k = 0; k < params->max_cg; ++k) {
+      if ((rc = cg_iteration(prob, L, path, d_ws, ds, nullptr, false, params->cg_tol, st)) != NADMM_OK) return rc;
+    }
+
+    // Armijo backtracking on Z(alpha) = A X + alpha A p, then X += alpha p
+    RowArgs rz = blank_rows();
+    rz.kind = kRowsLogits;
+    rz.B1 = pdir;
+    rz.Z1out = at<float>(d_ws, L.zp);
+    rz.flag = &ds->newton_active;
+    if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st)) != NADMM_OK) return rc;
+
+    LsEvalArgs le;
+    std::memset(&le, 0, sizeof(le));
+    le.Zx = at<float>(d_ws, L.zx);
+    le.Zp = at<float>(d_ws, L.zp);
+    le.labels = prob->d_labels;
+    le.n = prob->n;
+    le.NC = L.s.NC;
+    fill_alphas(le.alphas, ncand, params->backtrack_gamma);
+    le.ncand = ncand;
+    le.lpart = at<double>(d_ws, L.lpart);
+    le.flag = &ds->newton_active;
+    NADMM_HIP(launch_ls_eval(le, st));
+
+    LsTailArgs lt;
+    std::memset(&lt, 0, sizeof(lt));
+    lt.st = ds;
+    lt.lpart = le.lpart;
+    lt.nblocks = ls_eval_blocks(prob->n);
+    lt.ncand = ncand;
+    lt.zero_slot = -1;
+    std::memcpy(lt.alphas, le.alphas, sizeof(lt.alphas));
+    lt.use_state_loss = 1;
+    lt.scale = prob->loss_scale;
+    lt.lambda = prob->lambda;
+    lt.rho = prob->rho;
+    lt.beta = params->armijo_beta;
+    lt.X = d_X;
+    lt.z = prob->d_z;
+    lt.y = prob->d_y;
+    lt.pdir = pdir;
+    lt.g = g;
+    lt.d = L.s.d;
+    lt.X_apply = d_X;
+    lt.iter = t;
+    lt.flag = &ds->newton_active;
+    NADMM_HIP(launch_ls_tail(lt, st));
+  }
+
+  return NADMM_OK;
+}
+
+struct AdmmLayout {
+  size_t state, part, local, total;
+};
+
+static int admm_layout(const nadmm_problem* w, int32_t N, AdmmLayout* AL, int64_t* d_out) {
+  if (w == nullptr || N < 1 || N > NADMM_MAX_WORKERS) return NADMM_EINVAL;
+  size_t local = 0;
+  for (int i = 0; i < N; ++i) {
+    int rc = validate_problem(&w[i], true);
+    if (rc != NADMM_OK) return rc;
+    if (w[i].p != w[0].p || w[i].C != w[0].C) return NADMM_EINVAL;
+    Layout L;
+    make_layout(&w[i], &L);
+    if (L.total > local) local = L.total;
+  }
+  const int64_t d = (int64_t)w[0].p * (w[0].C - 1);
+  size_t off = 0;
+  AL->state = off; off += align256(sizeof(AdmmState));
+  AL->part = off; off += align256((size_t)admm_blocks(d) * 5 * sizeof(double));
+  AL->local = off; off += local;
+  AL->total = off;
+  if (d_out) *d_out = d;
+  return NADMM_OK;
+}
+
 extern "C" {
 
 int nadmm_version(void) { return 100; }
@@ -385,7 +520,7 @@ int nadmm_cg_solve(const nadmm_problem* prob, const float* d_X, const float* d_g
   hipStream_t st = (hipStream_t)stream;
   DevState* ds = at<DevState>(d_ws, L.state);
 
-  NADMM_HIP(launch_state_init(ds, st));
+  NADMM_HIP(launch_state_init(ds, nullptr, st));
   NewtonHeadArgs nh;
   std::memset(&nh, 0, sizeof(nh));
   nh.st = ds;
@@ -425,7 +560,7 @@ int nadmm_line_search(const nadmm_problem* prob, const float* d_X, const float* 
   if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   DevState* ds = at<DevState>(d_ws, L.state);
-  NADMM_HIP(launch_state_init(ds, st));
+  NADMM_HIP(launch_state_init(ds, nullptr, st));
 
   RowArgs ra = blank_rows();
   ra.kind = kRowsLogits;
@@ -484,114 +619,100 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
                        void* d_ws, size_t ws_bytes, void* stream) {
   int rc = validate_problem(prob, true);
   if (rc != NADMM_OK) return rc;
-  if (d_X == nullptr || params == nullptr) return NADMM_EINVAL;
-  if (params->max_newton < 0 || params->max_cg < 0 || !(params->cg_tol >= 0.f) || !(params->grad_tol >= 0.f))
-    return NADMM_EINVAL;
-  if ((rc = validate_ls(params->armijo_beta, params->backtrack_gamma, params->max_ls)) != NADMM_OK) return rc;
+  if (d_X == nullptr) return NADMM_EINVAL;
+  if ((rc = validate_params(params)) != NADMM_OK) return rc;
   Layout L;
   make_layout(prob, &L);
   if ((rc = check_ws(L, d_ws, ws_bytes)) != NADMM_OK) return rc;
   int path = 0;
   if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
+  if ((rc = local_newton_enqueue(prob, d_X, params, L, path, d_ws, nullptr, st)) != NADMM_OK) return rc;
   DevState* ds = at<DevState>(d_ws, L.state);
-  float* g = at<float>(d_ws, L.g);
-  float* pdir = at<float>(d_ws, L.pdir);
-  float* r = at<float>(d_ws, L.r);
-  float* dvec = at<float>(d_ws, L.dvec);
-
-  NADMM_HIP(launch_state_init(ds, st));
-  const int ncand = params->max_ls + 2;
-
-  for (int t = 0; t < params->max_newton; ++t) {
-    // gradient and objective at X; caches the probabilities and the logits A X
-    RowArgs ra = blank_rows();
-    ra.kind = kRowsGrad;
-    ra.B0 = d_X;
-    ra.labels = prob->d_labels;
-    ra.rows_out = at<float>(d_ws, L.drows);
-    ra.Pout = at<float>(d_ws, L.pcache);
-    ra.Z0out = at<float>(d_ws, L.zx);
-    ra.loss_part = at<double>(d_ws, L.loss_part);
-    ra.flag = &ds->newton_active;
-    int nparts = 0;
-    if ((rc = sweep(prob, L, path, d_ws, ra, true, &nparts, st)) != NADMM_OK) return rc;
-    if ((rc = reduce(prob, L, d_ws, nparts, 1, d_X, g, nullptr, &ds->newton_active, st)) != NADMM_OK) return rc;
-
-    NewtonHeadArgs nh;
-    std::memset(&nh, 0, sizeof(nh));
-    nh.st = ds;
-    nh.loss_part = at<double>(d_ws, L.loss_part);
-    nh.nblocks = loss_blocks(L, path);
-    nh.scale = prob->loss_scale;
-    nh.lambda = prob->lambda;
-    nh.rho = prob->rho;
-    nh.X = d_X;
-    nh.z = prob->d_z;
-    nh.y = prob->d_y;
-    nh.g = g;
-    nh.pdir = pdir;
-    nh.r = r;
-    nh.dvec = dvec;
-    nh.d = L.s.d;
-    nh.iter = t;
-    nh.grad_tol = params->grad_tol;
-    nh.newton_mode = 1;
-    NADMM_HIP(launch_newton_head(nh, st));
-
-    // CG on H p = -g with the probabilities of this iterate
-    for (int k = 0; k < params->max_cg; ++k) {
-      if ((rc = cg_iteration(prob, L, path, d_ws, ds, nullptr, false, params->cg_tol, st)) != NADMM_OK) return rc;
-    }
-
-    // Armijo backtracking on Z(alpha) = A X + alpha A p, then X += alpha p
-    RowArgs rz = blank_rows();
-    rz.kind = kRowsLogits;
-    rz.B1 = pdir;
-    rz.Z1out = at<float>(d_ws, L.zp);
-    rz.flag = &ds->newton_active;
-    if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st)) != NADMM_OK) return rc;
-
-    LsEvalArgs le;
-    std::memset(&le, 0, sizeof(le));
-    le.Zx = at<float>(d_ws, L.zx);
-    le.Zp = at<float>(d_ws, L.zp);
-    le.labels = prob->d_labels;
-    le.n = prob->n;
-    le.NC = L.s.NC;
-    fill_alphas(le.alphas, ncand, params->backtrack_gamma);
-    le.ncand = ncand;
-    le.lpart = at<double>(d_ws, L.lpart);
-    le.flag = &ds->newton_active;
-    NADMM_HIP(launch_ls_eval(le, st));
-
-    LsTailArgs lt;
-    std::memset(&lt, 0, sizeof(lt));
-    lt.st = ds;
-    lt.lpart = le.lpart;
-    lt.nblocks = ls_eval_blocks(prob->n);
-    lt.ncand = ncand;
-    lt.zero_slot = -1;
-    std::memcpy(lt.alphas, le.alphas, sizeof(lt.alphas));
-    lt.use_state_loss = 1;
-    lt.scale = prob->loss_scale;
-    lt.lambda = prob->lambda;
-    lt.rho = prob->rho;
-    lt.beta = params->armijo_beta;
-    lt.X = d_X;
-    lt.z = prob->d_z;
-    lt.y = prob->d_y;
-    lt.pdir = pdir;
-    lt.g = g;
-    lt.d = L.s.d;
-    lt.X_apply = d_X;
-    lt.iter = t;
-    lt.flag = &ds->newton_active;
-    NADMM_HIP(launch_ls_tail(lt, st));
-  }
-
   if (h_stats != nullptr) {
     NADMM_HIP(hipMemcpyAsync(h_stats, &ds->stats, sizeof(nadmm_stats), hipMemcpyDeviceToHost, st));
+    NADMM_HIP(hipStreamSynchronize(st));
+  }
+  return NADMM_OK;
+}
+
+
+// ---- ADMM outer solver (Algorithm 1) ----
+size_t nadmm_admm_workspace_bytes(const nadmm_problem* h_workers, int32_t N, const nadmm_admm_params* /*params*/) {
+  AdmmLayout AL;
+  if (admm_layout(h_workers, N, &AL, nullptr) != NADMM_OK) return 0;
+  return AL.total;
+}
+
+int nadmm_admm_consensus(int32_t N, int64_t d, const float* d_x, float* d_u, float* d_z, const float* h_rho,
+                         float lambda, float eps_abs, float eps_rel, double* d_out,
+                         void* d_ws, size_t ws_bytes, void* stream) {
+  if (N < 1 || N > NADMM_MAX_WORKERS || d < 1 || d_x == nullptr || d_u == nullptr || d_z == nullptr || h_rho == nullptr)
+    return NADMM_EINVAL;
+  if (!(lambda >= 0.f) || !(eps_abs >= 0.f) || !(eps_rel >= 0.f)) return NADMM_EINVAL;
+  const size_t need = align256((size_t)admm_blocks(d) * 5 * sizeof(double));
+  if (d_ws == nullptr || ((uintptr_t)d_ws & 255) != 0 || ws_bytes < need) return NADMM_EWORKSPACE;
+  AdmmConsensusArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.x = d_x; a.u = d_u; a.z = d_z; a.N = N; a.d = d;
+  for (int i = 0; i < N; ++i) {
+    if (!(h_rho[i] > 0.f) || !std::isfinite(h_rho[i])) return NADMM_EINVAL;
+    a.rho[i] = h_rho[i];
+  }
+  a.lambda = lambda; a.eps_abs = eps_abs; a.eps_rel = eps_rel;
+  a.part = static_cast<double*>(d_ws);
+  a.out = d_out;
+  NADMM_HIP(launch_admm_consensus(a, (hipStream_t)stream));
+  return NADMM_OK;
+}
+
+int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, float* d_x, float* d_u, float* d_z,
+                     const nadmm_admm_params* params, nadmm_admm_stats* h_stats,
+                     void* d_ws, size_t ws_bytes, void* stream) {
+  AdmmLayout AL;
+  int64_t d = 0;
+  int rc = admm_layout(h_workers, N, &AL, &d);
+  if (rc != NADMM_OK) return rc;
+  if (d_x == nullptr || d_u == nullptr || d_z == nullptr || params == nullptr) return NADMM_EINVAL;
+  if (params->max_outer < 0 || !(lambda >= 0.f) || !std::isfinite(lambda) || !(params->eps_abs >= 0.f) ||
+      !(params->eps_rel >= 0.f))
+    return NADMM_EINVAL;
+  if ((rc = validate_params(&params->local)) != NADMM_OK) return rc;
+  if (d_ws == nullptr || ((uintptr_t)d_ws & 255) != 0 || ws_bytes < AL.total) return NADMM_EWORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  AdmmState* as = at<AdmmState>(d_ws, AL.state);
+  void* local_ws = at<char>(d_ws, AL.local);
+
+  // per-worker subproblems: no local regulariser, consensus variable and multipliers of this call
+  nadmm_problem wk[NADMM_MAX_WORKERS];
+  Layout Ls[NADMM_MAX_WORKERS];
+  int paths[NADMM_MAX_WORKERS];
+  AdmmConsensusArgs ca;
+  std::memset(&ca, 0, sizeof(ca));
+  for (int i = 0; i < N; ++i) {
+    wk[i] = h_workers[i];
+    wk[i].lambda = 0.f;
+    wk[i].d_z = d_z;
+    wk[i].d_y = d_u + (size_t)i * d;
+    make_layout(&wk[i], &Ls[i]);
+    if ((rc = choose_path(Ls[i], &paths[i])) != NADMM_OK) return rc;
+    ca.rho[i] = wk[i].rho;
+  }
+  ca.st = as; ca.x = d_x; ca.u = d_u; ca.z = d_z; ca.N = N; ca.d = d;
+  ca.lambda = lambda; ca.eps_abs = params->eps_abs; ca.eps_rel = params->eps_rel;
+  ca.part = at<double>(d_ws, AL.part);
+
+  NADMM_HIP(launch_admm_init(as, d_u, d_z, N, d, st));
+  for (int k = 0; k < params->max_outer; ++k) {
+    for (int i = 0; i < N; ++i) {
+      rc = local_newton_enqueue(&wk[i], d_x + (size_t)i * d, &params->local, Ls[i], paths[i], local_ws, &as->active, st);
+      if (rc != NADMM_OK) return rc;
+    }
+    ca.iter = k;
+    NADMM_HIP(launch_admm_consensus(ca, st));
+  }
+  if (h_stats != nullptr) {
+    NADMM_HIP(hipMemcpyAsync(h_stats, &as->stats, sizeof(nadmm_admm_stats), hipMemcpyDeviceToHost, st));
     NADMM_HIP(hipStreamSynchronize(st));
   }
   return NADMM_OK;

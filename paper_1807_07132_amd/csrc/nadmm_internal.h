@@ -209,7 +209,31 @@ struct LsTailArgs {
 };
 hipError_t launch_ls_tail(const LsTailArgs& a, hipStream_t st);
 
-hipError_t launch_state_init(DevState* st, hipStream_t stream);
+// outer_flag, if non-NULL, is copied into newton_active: a stopped outer iteration turns the local solve into no-ops
+hipError_t launch_state_init(DevState* st, const int32_t* outer_flag, hipStream_t stream);
+
+// ---- ADMM outer solver (nadmm_admm.hip) ----
+struct AdmmState {
+  int32_t active;     // 0 once the residual test has stopped the iteration
+  int32_t pad_;
+  nadmm_admm_stats stats;
+};
+struct AdmmConsensusArgs {
+  AdmmState* st;           // may be NULL (stand-alone consensus step)
+  const float* x;          // N x d
+  float* u;                // N x d
+  float* z;                // d
+  int32_t N;
+  int64_t d;
+  float rho[NADMM_MAX_WORKERS];
+  float lambda, eps_abs, eps_rel;
+  double* part;            // admm_blocks(d) x 5 partial sums
+  double* out;             // optional: r_norm, d_norm, eps_pri, eps_dual
+  int32_t iter;
+};
+int admm_blocks(int64_t d);
+hipError_t launch_admm_init(AdmmState* st, float* u, float* z, int32_t N, int64_t d, hipStream_t stream);
+hipError_t launch_admm_consensus(const AdmmConsensusArgs& a, hipStream_t stream);
 
 // ---- fused single-pass path (nadmm_fused.hip) ----
 bool fused_supported(const Shape& s, int64_t lda, const void* A);

@@ -131,12 +131,12 @@ __global__ __launch_bounds__(kTail) void loss_finish_kernel(const LossFinishArgs
   if (threadIdx.x == 0) *a.loss_out = (double)a.scale * data + pen;
 }
 
-__global__ void state_init_kernel(DevState* st) {
+__global__ void state_init_kernel(DevState* st, const int32_t* outer_flag) {
   // one thread; zero the scalars and the statistics, raise the activity flags
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
   st->loss = 0.0; st->gg = 0.0; st->rr = 0.0; st->gg_cg = 0.0; st->loss_new = 0.0; st->loss_initial = 0.0;
   st->alpha = 0.f;
-  st->newton_active = 1; st->cg_active = 1; st->cg_iters = 0; st->armijo_ok = 1; st->ls_evals = 0;
+  st->newton_active = outer_flag ? *outer_flag : 1; st->cg_active = st->newton_active; st->cg_iters = 0; st->armijo_ok = 1; st->ls_evals = 0;
   st->cg_go = 0; st->cg_ok = 1; st->cg_alpha = 0.f; st->rr_prev = 0.0;
   nadmm_stats* s = &st->stats;
   s->newton_iters = 0; s->cg_iters_total = 0; s->ls_evals_total = 0; s->armijo_failed = 0;
@@ -621,8 +621,8 @@ hipError_t launch_loss_finish(const LossFinishArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_state_init(DevState* s, hipStream_t st) {
-  hipLaunchKernelGGL(state_init_kernel, dim3(1), dim3(64), 0, st, s);
+hipError_t launch_state_init(DevState* s, const int32_t* outer_flag, hipStream_t st) {
+  hipLaunchKernelGGL(state_init_kernel, dim3(1), dim3(64), 0, st, s, outer_flag);
   return hipGetLastError();
 }
 

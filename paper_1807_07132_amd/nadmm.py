@@ -49,6 +49,21 @@ class nadmm_stats(C.Structure):
     ]
 
 
+NADMM_MAX_WORKERS = 64
+
+
+class nadmm_admm_params(C.Structure):
+    _fields_ = [("max_outer", C.c_int32), ("eps_abs", C.c_float), ("eps_rel", C.c_float), ("local", nadmm_params)]
+
+
+class nadmm_admm_stats(C.Structure):
+    _fields_ = [
+        ("outer_iters", C.c_int32), ("converged", C.c_int32), ("r_norm", C.c_double), ("d_norm", C.c_double),
+        ("eps_pri", C.c_double), ("eps_dual", C.c_double), ("r_trace", C.c_double * NADMM_TRACE_LEN),
+        ("d_trace", C.c_double * NADMM_TRACE_LEN),
+    ]
+
+
 _lib = None
 
 
@@ -74,10 +89,16 @@ def lib():
     L.nadmm_cg_solve.argtypes = [PP, vp, vp, vp, C.c_int, C.c_float, vp, vp, vp, sz, vp]
     L.nadmm_line_search.argtypes = [PP, vp, vp, vp, C.c_double, C.c_float, C.c_float, C.c_int, vp, vp, vp, vp, sz, vp]
     L.nadmm_local_newton.argtypes = [PP, vp, PR, PS, vp, sz, vp]
+    PA, PAS = C.POINTER(nadmm_admm_params), C.POINTER(nadmm_admm_stats)
+    L.nadmm_admm_workspace_bytes.restype = sz
+    L.nadmm_admm_workspace_bytes.argtypes = [PP, C.c_int32, PA]
+    L.nadmm_admm_consensus.argtypes = [C.c_int32, C.c_int64, vp, vp, vp, C.POINTER(C.c_float), C.c_float, C.c_float,
+                                       C.c_float, vp, vp, sz, vp]
+    L.nadmm_admm_solve.argtypes = [PP, C.c_int32, C.c_float, vp, vp, vp, PA, PAS, vp, sz, vp]
     L.nadmm_set_kernel_path.argtypes = [C.c_int]
     L.nadmm_query_kernel_path.argtypes = [PP]
     for f in (L.nadmm_loss_grad, L.nadmm_hessvec, L.nadmm_cg_solve, L.nadmm_line_search, L.nadmm_local_newton,
-              L.nadmm_set_kernel_path, L.nadmm_query_kernel_path):
+              L.nadmm_set_kernel_path, L.nadmm_query_kernel_path, L.nadmm_admm_consensus, L.nadmm_admm_solve):
         f.restype = C.c_int
     _lib = L
     return L
@@ -233,3 +254,58 @@ def nadmm_local_newton(prob: Problem, X: torch.Tensor, params: nadmm_params, wan
                 armijo_failed=st.armijo_failed, loss_initial=st.loss_initial, loss_final=st.loss_final,
                 grad_norm_final=st.grad_norm_final, alpha=list(st.alpha[:k]), cg_iters=list(st.cg_iters[:k]),
                 loss=list(st.loss[:k]), grad_norm=list(st.grad_norm[:k]))
+
+
+def make_admm_params(max_outer: int, local: nadmm_params, eps_abs=0.0, eps_rel=0.0) -> nadmm_admm_params:
+    return nadmm_admm_params(int(max_outer), float(eps_abs), float(eps_rel), local)
+
+
+def _worker_array(workers):
+    arr = (nadmm_problem * len(workers))()
+    for i, w in enumerate(workers):
+        arr[i] = w.c
+    return arr
+
+
+def nadmm_admm_workspace_bytes(workers, params: Optional[nadmm_admm_params] = None) -> int:
+    arr = _worker_array(workers)
+    return int(lib().nadmm_admm_workspace_bytes(arr, len(workers), C.byref(params) if params is not None else None))
+
+
+def nadmm_admm_consensus(x: torch.Tensor, u: torch.Tensor, z: torch.Tensor, rhos, lam: float, eps_abs=0.0, eps_rel=0.0,
+                         ws=None, stream=None):
+    """One z-/multiplier update on x (N x d), u (N x d, updated in place), z (d, updated in place).
+    Returns a device tensor of 4 float64: ||r||, ||d||, eps_pri, eps_dual."""
+    N, d = x.shape[0], x[0].numel()
+    assert x.is_contiguous() and u.is_contiguous() and z.is_contiguous() and u.shape == x.shape and z.numel() == d
+    out = torch.empty(4, dtype=torch.float64, device=x.device)
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device=x.device) if ws is None else ws
+    rho_arr = (C.c_float * N)(*[float(r) for r in rhos])
+    _check(lib().nadmm_admm_consensus(N, d, _ptr(x), _ptr(u), _ptr(z), rho_arr, float(lam), float(eps_abs),
+                                      float(eps_rel), _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def nadmm_admm_solve(workers, lam: float, x: torch.Tensor, params: nadmm_admm_params, want_stats=True, ws=None,
+                     stream=None):
+    """Algorithm 1 on the shards `workers` (Problem objects; rho of each is its penalty).  x: N x p x (C-1), warm
+    starts in, local iterates out.  Returns (z, u, stats): u = multipliers in the sign convention of
+    nadmm_problem.d_y (minus the paper's y)."""
+    N = len(workers)
+    assert x.is_contiguous() and x.shape[0] == N
+    arr = _worker_array(workers)
+    if ws is None:
+        nbytes = int(lib().nadmm_admm_workspace_bytes(arr, N, C.byref(params)))
+        if nbytes == 0:
+            raise NadmmError(NADMM_EINVAL)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=x.device)
+    u = torch.empty_like(x)
+    z = torch.empty_like(x[0])
+    st = nadmm_admm_stats() if want_stats else None
+    _check(lib().nadmm_admm_solve(arr, N, float(lam), _ptr(x), _ptr(u), _ptr(z), C.byref(params),
+                                  C.byref(st) if st is not None else None, _ptr(ws), ws.numel(), _stream(stream)))
+    if st is None:
+        return z, u, None
+    k = min(st.outer_iters, NADMM_TRACE_LEN)
+    return z, u, dict(outer_iters=st.outer_iters, converged=bool(st.converged), r_norm=st.r_norm, d_norm=st.d_norm,
+                      eps_pri=st.eps_pri, eps_dual=st.eps_dual, r_trace=list(st.r_trace[:k]), d_trace=list(st.d_trace[:k]))

@@ -45,15 +45,18 @@ def test_struct_layout_matches_the_header(tmp_path):
     src = tmp_path / "sizes.c"
     src.write_text(
         '#include <stdio.h>\n#include <stddef.h>\n#include "nadmm.h"\n'
-        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(nadmm_problem), sizeof(nadmm_params),"
+        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(nadmm_problem), sizeof(nadmm_params),"
         " sizeof(nadmm_stats), offsetof(nadmm_problem, d_labels), offsetof(nadmm_problem, d_z),"
-        " offsetof(nadmm_stats, loss_initial), offsetof(nadmm_stats, grad_norm));return 0;}\n")
+        " offsetof(nadmm_stats, loss_initial), offsetof(nadmm_stats, grad_norm), sizeof(nadmm_admm_params),"
+        " sizeof(nadmm_admm_stats), offsetof(nadmm_admm_params, local), offsetof(nadmm_admm_stats, d_trace));return 0;}\n")
     exe = tmp_path / "sizes"
     subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", f"-I{os.path.join(ROOT, 'include')}", str(src), "-o", str(exe)])
     got = [int(v) for v in subprocess.check_output([str(exe)]).split()]
     want = [C.sizeof(nadmm.nadmm_problem), C.sizeof(nadmm.nadmm_params), C.sizeof(nadmm.nadmm_stats),
             nadmm.nadmm_problem.d_labels.offset, nadmm.nadmm_problem.d_z.offset,
-            nadmm.nadmm_stats.loss_initial.offset, nadmm.nadmm_stats.grad_norm.offset]
+            nadmm.nadmm_stats.loss_initial.offset, nadmm.nadmm_stats.grad_norm.offset,
+            C.sizeof(nadmm.nadmm_admm_params), C.sizeof(nadmm.nadmm_admm_stats), nadmm.nadmm_admm_params.local.offset,
+            nadmm.nadmm_admm_stats.d_trace.offset]
     assert got == want
 
 
@@ -147,3 +150,25 @@ def test_product_path_does_not_import_the_oracle():
     code = ("import sys; sys.path.insert(0, %r); import paper_1807_07132_amd.nadmm, paper_1807_07132_amd.workloads;"
             "assert not any(m == 'oracle' or m.startswith('oracle.') for m in sys.modules)" % ROOT)
     subprocess.check_call([sys.executable, "-c", code])
+
+
+def test_admm_host_validation(lib):
+    params = nadmm.make_admm_params(3, nadmm.make_params(2, 5, 10))
+    fake = C.c_void_p(0x4000)
+    workers = (nadmm.nadmm_problem * 3)(*[fake_problem(n=500 + 10 * i) for i in range(3)])
+    need = lib.nadmm_admm_workspace_bytes(workers, 3, C.byref(params))
+    single = max(lib.nadmm_workspace_bytes(C.byref(workers[i]), None) for i in range(3))
+    assert need > single
+    assert lib.nadmm_admm_workspace_bytes(workers, 0, C.byref(params)) == 0
+    assert lib.nadmm_admm_workspace_bytes(workers, nadmm.NADMM_MAX_WORKERS + 1, C.byref(params)) == 0
+    call = lambda w, N, lam, prm, ws: lib.nadmm_admm_solve(w, N, lam, fake, fake, fake, C.byref(prm), None, fake, ws, None)
+    assert call(workers, 3, 0.1, params, need - 1) == nadmm.NADMM_EWORKSPACE
+    assert call(workers, 3, -0.1, params, need) == nadmm.NADMM_EINVAL
+    bad = nadmm.make_admm_params(-1, nadmm.make_params(2, 5, 10))
+    assert call(workers, 3, 0.1, bad, need) == nadmm.NADMM_EINVAL
+    mixed = (nadmm.nadmm_problem * 2)(fake_problem(p=20), fake_problem(p=24))     # shards must agree in p and C
+    assert lib.nadmm_admm_workspace_bytes(mixed, 2, C.byref(params)) == 0
+    rho = (C.c_float * 2)(1.0, -1.0)
+    assert lib.nadmm_admm_consensus(2, 40, fake, fake, fake, rho, 0.1, 0.0, 0.0, None, fake, 1 << 16, None) == nadmm.NADMM_EINVAL
+    rho = (C.c_float * 2)(1.0, 1.0)
+    assert lib.nadmm_admm_consensus(2, 40, fake, fake, fake, rho, 0.1, 0.0, 0.0, None, fake, 16, None) == nadmm.NADMM_EWORKSPACE

@@ -1,0 +1,115 @@
+"""GPU parity of the ADMM outer solver (Algorithm 1 with fixed penalties, N workers simulated on one GPU)
+against the float64 oracle: the consensus step element by element, whole iterations after a fixed number
+of outer iterations, and the residual-based stop."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import admm_oracle as adm
+from oracle import nadmm_oracle as orc
+from paper_1807_07132_amd import nadmm, workloads
+from parity_utils import TOL_ITERATE, TOL_PRIMITIVE, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def shards_of(w, N, rhos):
+    """Row shards of one synthetic data set: GPU problems and oracle problems with loss scale 1/n_total."""
+    bounds = np.linspace(0, w.n, N + 1).astype(int)
+    s = 1.0 / w.n
+    gps, ops = [], []
+    for i in range(N):
+        A, b = w.A[bounds[i]:bounds[i + 1]], w.b[bounds[i]:bounds[i + 1]]
+        gps.append(nadmm.Problem(dev(A), dev(b), w.C, s, 0.0, float(rhos[i]), None, None))
+        ops.append(orc.Problem(A, b, w.C, s=s))
+    return gps, ops
+
+
+def test_consensus_step_matches_the_oracle():
+    rng = np.random.default_rng(0)
+    N, shape, lam = 5, (37, 6), 0.03
+    d = shape[0] * shape[1]
+    x = rng.standard_normal((N,) + shape).astype(np.float32)
+    u = (0.3 * rng.standard_normal((N,) + shape)).astype(np.float32)
+    z0 = (0.5 * rng.standard_normal(shape)).astype(np.float32)
+    rhos = [0.5, 1.0, 2.0, 0.25, 4.0]
+    xd, ud, zd = dev(x), dev(u), dev(z0)
+    out = nadmm.nadmm_admm_consensus(xd, ud, zd, rhos, lam, eps_abs=1e-3, eps_rel=1e-2)
+    # oracle in the paper's sign convention: y = -u
+    xs = [x[i].astype(np.float64) for i in range(N)]
+    ys = [-u[i].astype(np.float64) for i in range(N)]
+    z = adm.z_update(xs, ys, rhos, lam)
+    ys_new = [ys[i] + rhos[i] * (z - xs[i]) for i in range(N)]
+    assert rel_l2(host(zd), z) <= 1e-6
+    for i in range(N):
+        assert rel_l2(-host(ud)[i], ys_new[i]) <= 1e-6
+    r = np.sqrt(sum(np.sum((z - xs[i]) ** 2) for i in range(N)))
+    dn = np.sqrt(sum(np.sum((rhos[i] * (z - z0.astype(np.float64))) ** 2) for i in range(N)))
+    e_pri, e_dual = adm.tolerances(xs, ys_new, z, 1e-3, 1e-2)
+    got = host(out)
+    assert got == pytest.approx([r, dn, e_pri, e_dual], rel=1e-6)
+    assert d == zd.numel()
+
+
+ADMM_CASES = {
+    # name: (workload, N, rhos, lambda, outer iterations, Newton iterations, CG iterations)
+    "thin_4x750x24_C4": (lambda: workloads.generic(3000, 24, 4, seed=31), 4, [0.5, 0.5, 0.5, 0.5], 1e-3, 5, 2, 8),
+    "fused_3x1000x64_C5": (lambda: workloads.generic(3001, 64, 5, seed=32), 3, [0.3, 0.6, 1.2], 1e-2, 4, 2, 6),
+    "generic_2x400x45_C3": (lambda: workloads.generic(800, 45, 3, seed=33), 2, [1.0, 2.0], 0.0, 3, 1, 5),
+}
+
+
+@pytest.mark.parametrize("name", list(ADMM_CASES))
+def test_admm_fixed_iterations(name):
+    make, N, rhos, lam, K, T, Kcg = ADMM_CASES[name]
+    w = make()
+    print(f"admm parity: {name}", flush=True)
+    gps, ops = shards_of(w, N, rhos)
+    X0 = (0.05 * np.random.default_rng(7).standard_normal(w.X0.shape)).astype(np.float32)
+    params = nadmm.make_admm_params(K, nadmm.make_params(T, Kcg, w.max_ls, 0.0, 0.0, w.beta, w.gamma))
+    x = dev(np.stack([X0] * N))
+    z, u, st = nadmm.nadmm_admm_solve(gps, lam, x, params)
+    z_ref, xs_ref, ys_ref, hist = adm.admm(ops, lam, rhos, X0, K, T, Kcg, 0.0, 0.0, w.beta, w.gamma, w.max_ls)
+    assert st["outer_iters"] == K and not st["converged"]
+    assert rel_l2(host(z), z_ref) <= TOL_ITERATE
+    for i in range(N):
+        assert rel_l2(host(x)[i], xs_ref[i]) <= TOL_ITERATE
+        # multipliers: minus the paper's y; small in norm, so the error is taken relative to the scale of rho x
+        scale = max(np.linalg.norm(ys_ref[i]), rhos[i] * np.linalg.norm(xs_ref[i]) * 1e-2)
+        assert np.linalg.norm(-host(u)[i] - ys_ref[i]) <= TOL_ITERATE * scale
+    assert st["r_trace"] == pytest.approx([h["r_norm"] for h in hist], rel=5e-3)
+    assert st["d_trace"] == pytest.approx([h["d_norm"] for h in hist], rel=5e-3)
+    # the invariant of the z- and y-updates holds on the device results as well
+    np.testing.assert_allclose(host(u).sum(0), lam * host(z), atol=1e-5 * max(1.0, float(np.abs(host(u)).max())))
+
+
+def test_admm_stops_on_the_residual_test_and_later_iterations_are_no_ops():
+    w = workloads.generic(2400, 20, 3, seed=34)
+    N, rhos, lam = 3, [0.1, 0.1, 0.1], 5e-2
+    gps, ops = shards_of(w, N, rhos)
+    X0 = np.zeros_like(w.X0)
+    eps_abs, eps_rel = 1e-3, 1e-2
+    local = nadmm.make_params(3, 10, w.max_ls, 0.0, 0.0, w.beta, w.gamma)
+    z_ref, xs_ref, ys_ref, hist = adm.admm(ops, lam, rhos, X0, 60, 3, 10, 0.0, 0.0, w.beta, w.gamma, w.max_ls,
+                                           eps_abs=eps_abs, eps_rel=eps_rel)
+    k_ref = len(hist)
+    assert 1 < k_ref < 60
+    x = dev(np.stack([X0] * N))
+    z, u, st = nadmm.nadmm_admm_solve(gps, lam, x, nadmm.make_admm_params(60, local, eps_abs, eps_rel))
+    assert st["converged"] and abs(st["outer_iters"] - k_ref) <= 1
+    assert st["r_norm"] <= st["eps_pri"] and st["d_norm"] <= st["eps_dual"]
+    if st["outer_iters"] == k_ref:
+        assert rel_l2(host(z), z_ref) <= TOL_ITERATE
+        assert st["eps_pri"] == pytest.approx(hist[-1]["eps_pri"], rel=1e-3)
+    # same call limited to the iteration count it stopped at: identical results, i.e. nothing ran after the stop
+    x2 = dev(np.stack([X0] * N))
+    z2, u2, st2 = nadmm.nadmm_admm_solve(gps, lam, x2, nadmm.make_admm_params(st["outer_iters"], local, eps_abs, eps_rel))
+    assert torch.equal(z, z2) and torch.equal(x, x2) and torch.equal(u, u2)
