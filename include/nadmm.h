@@ -1,7 +1,8 @@
 /*
  * nadmm.h -- C ABI of the MI355X (gfx950) library for one ADMM worker's local
  * x-update of Newton-ADMM: inexact Newton-CG on L2-regularised multinomial
- * (softmax) logistic regression.
+ * (softmax) logistic regression; at the end, the ADMM outer solver with the
+ * workers simulated on the one device.
  *
  * Local objective (x-update of the ADMM iteration, Section 2.3; cross-entropy
  * with C-1 free weight vectors, Section 2.1):
