@@ -51,7 +51,7 @@ typedef enum nadmm_status {
   NADMM_EINVAL = -1,       /* null required pointer, n<1, p<1, C<2, lda<p, rho<=0, lambda<0,
                               beta or gamma outside (0,1), negative iteration limits */
   NADMM_EWORKSPACE = -2,   /* workspace missing, misaligned or too small */
-  NADMM_EUNSUPPORTED = -3, /* shape outside the compiled range (C-1 > 32, max_ls > 62, ...) */
+  NADMM_EUNSUPPORTED = -3, /* shape outside the compiled range (C-1 > 32, max_ls > 62, n > 2^36, p (C-1) > 2^28) */
   NADMM_EHIP = -4          /* a HIP call or kernel launch failed */
 } nadmm_status;
 

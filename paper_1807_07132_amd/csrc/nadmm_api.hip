@@ -35,7 +35,7 @@ int validate_problem(const nadmm_problem* p, bool need_labels) {
   if (need_labels && p->d_labels == nullptr) return NADMM_EINVAL;
   if (p->C - 1 > NADMM_MAX_FREE_CLASSES) return NADMM_EUNSUPPORTED;
   if ((int64_t)p->p * (p->C - 1) > ((int64_t)1 << 28)) return NADMM_EUNSUPPORTED;
-  if (p->n > ((int64_t)1 << 40)) return NADMM_EUNSUPPORTED;
+  if (p->n > ((int64_t)1 << 36)) return NADMM_EUNSUPPORTED;  // rows per workgroup are kept in 32 bits
   return NADMM_OK;
 }
 

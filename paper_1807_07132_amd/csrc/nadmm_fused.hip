@@ -333,13 +333,9 @@ int steps_of(int p) { return (p + kStepCols - 1) / kStepCols; }
 
 template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES>
 hipError_t launch_k(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_kernel<SPW, KIND, HAS0, HAS1, STORES>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static uint64_t lds_set = 0;  // per device
+  hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&fused_kernel<SPW, KIND, HAS0, HAS1, STORES>), &lds_set);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((fused_kernel<SPW, KIND, HAS0, HAS1, STORES>), dim3(grid), dim3(kThreads), lds_bytes, st, fa);
   return hipGetLastError();
 }

@@ -9,6 +9,21 @@
 
 namespace nadmm {
 
+// Raises a kernel's dynamic-LDS limit to the 160 KB of a gfx950 compute unit, once per device
+// (the attribute belongs to the kernel's code object on the current device).
+inline hipError_t ensure_lds_limit(const void* kernel, uint64_t* done_mask) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = (uint64_t)1 << (dev & 63);
+  if ((*done_mask & bit) == 0) {
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    *done_mask |= bit;
+  }
+  return hipSuccess;
+}
+
 constexpr int kWave = 64;
 constexpr int kMaxCand = NADMM_MAX_LS + 2;  // candidate step sizes 1, gamma, ..., gamma^(max_ls+1)
 constexpr int kCandSlots = kMaxCand + 1;    // + one slot for alpha = 0 (objective at X itself)

@@ -369,21 +369,12 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
   }
 }
 
-template <typename K>
-hipError_t set_lds_limit(K kernel) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             160 * 1024);
-}
-
 template <int SPW, int NB, bool HAS0, bool HAS1>
 hipError_t launch_logits_t(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
   const size_t lds = ((size_t)kWaves * (2 * NB * 2) * 4 * 64 + (size_t)kLogitBatchFloats) * sizeof(float);
-  static bool once = false;
-  if (!once) {
-    hipError_t e = set_lds_limit(&slice_logits_kernel<SPW, NB, HAS0, HAS1>);
-    if (e != hipSuccess) return e;
-    once = true;
-  }
+  static uint64_t lds_set = 0;  // per device
+  hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&slice_logits_kernel<SPW, NB, HAS0, HAS1>), &lds_set);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((slice_logits_kernel<SPW, NB, HAS0, HAS1>), grid, dim3(kThreads), lds, st, sa);
   return hipGetLastError();
 }
@@ -400,12 +391,9 @@ hipError_t launch_logits_nb(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
 template <int SPW, int NB>
 hipError_t launch_cols_t(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
   const size_t lds = (size_t)sa.steps_max * kStepBytes;
-  static bool once = false;
-  if (!once) {
-    hipError_t e = set_lds_limit(&slice_cols_kernel<SPW, NB>);
-    if (e != hipSuccess) return e;
-    once = true;
-  }
+  static uint64_t lds_set = 0;  // per device
+  hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&slice_cols_kernel<SPW, NB>), &lds_set);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((slice_cols_kernel<SPW, NB>), grid, dim3(kThreads), lds, st, sa);
   return hipGetLastError();
 }
