@@ -297,3 +297,28 @@ def test_non_default_stream(cache):
         hv = nadmm.nadmm_hessvec(gp, X, V, stream=s)
     s.synchronize()
     assert rel_l2(host(hv), orc.hessvec(op, w.X0, w.V)) <= TOL_PRIMITIVE
+
+
+def test_local_newton_replays_from_a_hip_graph(cache):
+    """The whole local solve is enqueued without host synchronisation or allocation, so it can be captured
+    once and replayed; every replay (with eager work in between) must give the eager result bit for bit."""
+    w, gp, op = setup_case(cache, "fused_2000x100_C7")
+    params = nadmm.make_params(2, 5, w.max_ls, 0.0, 0.0, w.beta, w.gamma)
+    ws = gp.workspace()
+    X0 = dev(w.X0.copy())
+    X_eager = X0.clone()
+    nadmm.nadmm_local_newton(gp, X_eager, params, want_stats=False, ws=ws)   # also the warm-up (kernel attributes)
+    torch.cuda.synchronize()
+    X = X0.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            nadmm.nadmm_local_newton(gp, X, params, want_stats=False, ws=ws, stream=side)
+    for _ in range(3):
+        X.copy_(X0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(X, X_eager)
+        hv = nadmm.nadmm_hessvec(gp, X0, dev(w.V), ws=ws)                      # eager work between the replays
+        assert rel_l2(host(hv), orc.hessvec(op, w.X0, w.V)) <= TOL_PRIMITIVE
