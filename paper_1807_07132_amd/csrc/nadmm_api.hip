@@ -79,7 +79,7 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   if (L->thin_parts > lblocks) lblocks = L->thin_parts;
   L->loss_part = off; off += align256((size_t)lblocks * sizeof(double));
   L->lpart = off; off += align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
-  L->dotpart = off; off += align256((size_t)reduce_out_blocks(s.d) * sizeof(double));
+  L->dotpart = off; off += align256((size_t)2 * reduce_out_blocks(s.d) * sizeof(double));  // two sums per workgroup
   L->rrpart = off; off += align256((size_t)cg_update_blocks(s.d) * sizeof(double));
   // per-slice partial logits of the column-sliced path
   L->zw = off; off += align256(L->sliced_ok ? sliced_zw_bytes(s) : 0);
@@ -313,7 +313,16 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     ra.flag = &ds->newton_active;
     int nparts = 0;
     if ((rc = sweep(prob, L, path, d_ws, ra, true, &nparts, st)) != NADMM_OK) return rc;
-    if ((rc = reduce(prob, L, d_ws, nparts, 1, d_X, g, nullptr, &ds->newton_active, st)) != NADMM_OK) return rc;
+    {
+      // gradient; the same kernel leaves the partial sums of the penalty terms and of ||g||^2 and starts CG (p = 0, r = d = -g)
+      ReduceArgs rg = reduce_args(prob, L, d_ws, nparts, 1, d_X, g, nullptr, &ds->newton_active);
+      rg.pen_part = at<double>(d_ws, L.dotpart);
+      rg.gg_part = rg.pen_part + reduce_out_blocks(L.s.d);
+      rg.cg_p = pdir;
+      rg.cg_r = r;
+      rg.cg_d = dvec;
+      NADMM_HIP(launch_reduce_out(rg, st));
+    }
 
     NewtonHeadArgs nh;
     std::memset(&nh, 0, sizeof(nh));
@@ -334,6 +343,9 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     nh.iter = t;
     nh.grad_tol = params->grad_tol;
     nh.newton_mode = 1;
+    nh.pen_part = at<double>(d_ws, L.dotpart);
+    nh.gg_part = nh.pen_part + reduce_out_blocks(L.s.d);
+    nh.npart = reduce_out_blocks(L.s.d);
     NADMM_HIP(launch_newton_head(nh, st));
 
     // CG on H p = -g with the probabilities of this iterate
@@ -477,7 +489,11 @@ int nadmm_loss_grad(const nadmm_problem* prob, const float* d_X, double* d_loss,
   ra.loss_part = at<double>(d_ws, L.loss_part);
   int nparts = 0;
   if ((rc = sweep(prob, L, path, d_ws, ra, d_grad != nullptr, &nparts, st)) != NADMM_OK) return rc;
-  if (d_grad && (rc = reduce(prob, L, d_ws, nparts, 1, d_X, d_grad, nullptr, nullptr, st)) != NADMM_OK) return rc;
+  if (d_grad) {
+    ReduceArgs rg = reduce_args(prob, L, d_ws, nparts, 1, d_X, d_grad, nullptr, nullptr);
+    rg.pen_part = at<double>(d_ws, L.dotpart);  // penalty terms, summed per workgroup on the way
+    NADMM_HIP(launch_reduce_out(rg, st));
+  }
 
   LossFinishArgs lf;
   lf.loss_part = at<double>(d_ws, L.loss_part);
@@ -489,6 +505,8 @@ int nadmm_loss_grad(const nadmm_problem* prob, const float* d_X, double* d_loss,
   lf.z = prob->d_z;
   lf.y = prob->d_y;
   lf.d = L.s.d;
+  lf.pen_part = d_grad ? at<double>(d_ws, L.dotpart) : nullptr;
+  lf.npart = reduce_out_blocks(L.s.d);
   lf.loss_out = d_loss;
   NADMM_HIP(launch_loss_finish(lf, st));
   return NADMM_OK;

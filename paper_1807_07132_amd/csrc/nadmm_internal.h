@@ -120,6 +120,11 @@ struct ReduceArgs {
   float lambda, rho;
   float* out;
   double* dot_part;       // kind 0, optional: per-workgroup sums of out[e] * V[e], reduce_out_blocks(d) entries
+  double* pen_part;       // kind 1, optional: per-workgroup sums of the penalty terms lambda/2 x^2 + rho/2 (x - z + y/rho)^2
+  double* gg_part;        // kind 1, optional: per-workgroup sums of out[e]^2
+  float* cg_p;            // kind 1, optional: CG start from the gradient just formed, p = 0, r = d = -out
+  float* cg_r;
+  float* cg_d;
   const int32_t* flag;
 };
 int reduce_out_blocks(int64_t d);
@@ -133,6 +138,8 @@ struct LossFinishArgs {
   const float* z;
   const float* y;
   int64_t d;
+  const double* pen_part;  // optional: penalty terms already summed per workgroup by the reduction (npart entries)
+  int32_t npart;
   double* loss_out;  // device scalar
 };
 hipError_t launch_loss_finish(const LossFinishArgs& a, hipStream_t st);
@@ -153,6 +160,9 @@ struct NewtonHeadArgs {
   int32_t iter;        // Newton iteration index
   float grad_tol;
   int32_t newton_mode; // 1: part of Algorithm 3 (stats, grad_tol); 0: plain CG initialisation from g
+  const double* pen_part;  // optional (with gg_part): partial sums left by the reduction that formed g, which
+  const double* gg_part;   //   has then also written p = 0, r = d = -g
+  int32_t npart;
 };
 hipError_t launch_newton_head(const NewtonHeadArgs& a, hipStream_t st);
 

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
 #pragma unroll
   for (int g = 1; g < 8; ++g) sum += sm[g][el];
   float out = a.scale * sum;
-  double prod = 0.0;
+  double prod = 0.0, pen = 0.0;
   if (ok) {
     if (a.kind == 0) {
       const float v = a.V[e];
@@ -69,13 +69,28 @@ __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
       const float zz = a.z ? a.z[e] : 0.f;
       const float yy = a.y ? a.y[e] : 0.f;
       out += a.lambda * x + a.rho * (x - zz) + yy;
+      const double xd = x, u = xd - (double)zz + (double)yy / (double)a.rho;
+      pen = 0.5 * (double)a.lambda * xd * xd + 0.5 * (double)a.rho * u * u;
+      prod = (double)out * (double)out;
+      if (a.cg_p != nullptr) {
+        a.cg_p[e] = 0.f;
+        a.cg_r[e] = -out;
+        a.cg_d[e] = -out;
+      }
     }
     a.out[e] = out;
   }
-  if (a.dot_part != nullptr) {  // the 32 products of this workgroup, summed in a fixed order by lane 0
+  // the 32 values of this workgroup, summed in a fixed order by lane 0
+  double* first = a.kind == 0 ? a.dot_part : a.gg_part;
+  if (first != nullptr) {
 #pragma unroll
     for (int off = 16; off > 0; off >>= 1) prod += __shfl_down(prod, off, 64);
-    if (el == 0) a.dot_part[blockIdx.x] = prod;
+    if (el == 0) first[blockIdx.x] = prod;
+  }
+  if (a.kind != 0 && a.pen_part != nullptr) {
+#pragma unroll
+    for (int off = 16; off > 0; off >>= 1) pen += __shfl_down(pen, off, 64);
+    if (el == 0) a.pen_part[blockIdx.x] = pen;
   }
 }
 
@@ -127,7 +142,8 @@ __device__ __forceinline__ double partial_sum_block(const double* part, int n, d
 __global__ __launch_bounds__(kTail) void loss_finish_kernel(const LossFinishArgs a) {
   __shared__ double sm[17];
   const double data = partial_sum_block(a.loss_part, a.nblocks, sm);
-  const double pen = penalty_block(a.X, a.z, a.y, a.d, a.lambda, a.rho, sm);
+  const double pen = a.pen_part ? partial_sum_block(a.pen_part, a.npart, sm)
+                                : penalty_block(a.X, a.z, a.y, a.d, a.lambda, a.rho, sm);
   if (threadIdx.x == 0) *a.loss_out = (double)a.scale * data + pen;
 }
 
@@ -154,30 +170,35 @@ __global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs
   if (a.newton_mode && st->newton_active == 0) return;
 
   double gg = 0.0;
-  for (int64_t e0 = threadIdx.x; e0 < a.d; e0 += (int64_t)kBlk * blockDim.x) {
-    float gv[kBlk];
+  if (a.gg_part != nullptr) {
+    gg = partial_sum_block(a.gg_part, a.npart, sm);  // the reduction has written p, r, d already
+  } else {
+    for (int64_t e0 = threadIdx.x; e0 < a.d; e0 += (int64_t)kBlk * blockDim.x) {
+      float gv[kBlk];
 #pragma unroll
-    for (int u = 0; u < kBlk; ++u) {
-      const int64_t e = e0 + (int64_t)u * blockDim.x;
-      gv[u] = e < a.d ? a.g[e] : 0.f;
-    }
+      for (int u = 0; u < kBlk; ++u) {
+        const int64_t e = e0 + (int64_t)u * blockDim.x;
+        gv[u] = e < a.d ? a.g[e] : 0.f;
+      }
 #pragma unroll
-    for (int u = 0; u < kBlk; ++u) {
-      const int64_t e = e0 + (int64_t)u * blockDim.x;
-      gg += (double)gv[u] * (double)gv[u];
-      if (e < a.d) {
-        a.pdir[e] = 0.f;
-        a.r[e] = -gv[u];
-        a.dvec[e] = -gv[u];
+      for (int u = 0; u < kBlk; ++u) {
+        const int64_t e = e0 + (int64_t)u * blockDim.x;
+        gg += (double)gv[u] * (double)gv[u];
+        if (e < a.d) {
+          a.pdir[e] = 0.f;
+          a.r[e] = -gv[u];
+          a.dvec[e] = -gv[u];
+        }
       }
     }
+    gg = block_sum(gg, sm);
   }
-  gg = block_sum(gg, sm);
 
   double loss = 0.0;
   if (a.newton_mode) {
     const double data = partial_sum_block(a.loss_part, a.nblocks, sm);
-    const double pen = penalty_block(a.X, a.z, a.y, a.d, a.lambda, a.rho, sm);
+    const double pen = a.pen_part ? partial_sum_block(a.pen_part, a.npart, sm)
+                                  : penalty_block(a.X, a.z, a.y, a.d, a.lambda, a.rho, sm);
     loss = (double)a.scale * data + pen;
   }
   if (threadIdx.x == 0) {
