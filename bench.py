@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--admm-workers", type=int, default=4,
                     help="simulated ADMM workers for the outer-iteration timing in extra (0 or 1: skip)")
     ap.add_argument("--admm-outer", type=int, default=2, help="outer iterations timed for that figure")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the measurements outside the timed steps (two copies of A, ADMM): profiling runs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--only", default="", help="comma list of hv,lg,solve: restrict the step (profiling runs)")
@@ -152,7 +154,7 @@ def main():
     # Outside the timed steps: matrices that fit the 256 MB Infinity Cache are also timed with two
     # independent copies of A used in turn, so that every call has to read its A from HBM.
     cold_hv_us = None
-    if do("hv") and recs and gp.A.numel() * 4 < 256e6:
+    if do("hv") and recs and not args.no_extras and gp.A.numel() * 4 < 256e6:
         gp2 = nadmm.Problem(gp.A.clone(), gp.labels, w.C, w.s, w.lam, w.rho, gp.z, gp.y)
         pair = (gp, gp2)
         for i in range(8):
@@ -170,7 +172,7 @@ def main():
     # Outside the timed steps: Algorithm 1 with the rows of A split over simulated workers (one after the
     # other on this GPU, fixed penalty): time of one outer iteration and of the consensus step alone.
     admm = None
-    if args.admm_workers > 1 and not only:
+    if args.admm_workers > 1 and not only and not args.no_extras:
         N = args.admm_workers
         bounds = [w.n * i // N for i in range(N + 1)]
         shards = [nadmm.Problem(gp.A[bounds[i]:bounds[i + 1]], gp.labels[bounds[i]:bounds[i + 1]], w.C, w.s, 0.0, w.rho)
