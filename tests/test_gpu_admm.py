@@ -64,6 +64,8 @@ ADMM_CASES = {
     "thin_4x750x24_C4": (lambda: workloads.generic(3000, 24, 4, seed=31), 4, [0.5, 0.5, 0.5, 0.5], 1e-3, 5, 2, 8),
     "fused_3x1000x64_C5": (lambda: workloads.generic(3001, 64, 5, seed=32), 3, [0.3, 0.6, 1.2], 1e-2, 4, 2, 6),
     "generic_2x400x45_C3": (lambda: workloads.generic(800, 45, 3, seed=33), 2, [1.0, 2.0], 0.0, 3, 1, 5),
+    "sliced_2x300x1100_C3": (lambda: workloads.generic(600, 1100, 3, seed=35, x_std=0.05), 2, [0.5, 1.0], 1e-2, 2, 1, 4),
+    "one_worker_900x32_C2": (lambda: workloads.generic(900, 32, 2, seed=36), 1, [0.7], 1e-2, 4, 2, 6),
 }
 
 
