@@ -59,6 +59,8 @@ CASES = {
     "sliced_3000x100_C26": lambda: workloads.generic(3000, 100, 26, seed=24, x_std=0.1),
     "sliced_1500x1100_C4": lambda: workloads.generic(1500, 1100, 4, seed=25, x_std=0.05),
     "sliced_33x1604_C33": lambda: workloads.generic(33, 1604, 33, seed=26, x_std=0.03),
+    "sliced_300x36_C33": lambda: workloads.generic(300, 36, 33, seed=27, x_std=0.2),    # 32 free classes: two full class blocks
+    "sliced_200x964_C3": lambda: workloads.generic(200, 964, 3, seed=28, x_std=0.05),  # one step past the fused kernel's limit
 }
 
 # 1 = two-pass vector kernels forced, 2 = fused matrix-core kernel forced, 4 = column-sliced two-sweep path forced,
