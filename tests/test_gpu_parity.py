@@ -343,3 +343,35 @@ def test_local_newton_replays_from_a_hip_graph(cache):
         assert torch.equal(X, X_eager)
         hv = nadmm.nadmm_hessvec(gp, X0, dev(w.V), ws=ws)                      # eager work between the replays
         assert rel_l2(host(hv), orc.hessvec(op, w.X0, w.V)) <= TOL_PRIMITIVE
+
+
+@pytest.mark.parametrize("shape", [(260, 64, 4), (300, 28, 2), (150, 1000, 3), (90, 21, 6)])
+def test_degenerate_inputs(cache, shape):
+    """All-zero data (every probability 1/C), one-class labels (reference class only / one free class only),
+    zero direction, no regulariser: closed forms and the oracle on every kernel path the shape admits."""
+    n, p, C = shape
+    w = workloads.generic(n, p, C, seed=40)
+    X, V = w.X0 if w.X0.any() else x_for(w), w.V
+    variants = {
+        "zero_data": (np.zeros_like(w.A), w.b),
+        "reference_class_only": (w.A, np.full_like(w.b, C - 1)),
+        "first_class_only": (w.A, np.zeros_like(w.b)),
+    }
+    for vname, (A, b) in variants.items():
+        op = orc.Problem(A, b, C, s=w.s, lam=0.0, rho=w.rho, z=w.z, y=w.y)
+        gp = nadmm.Problem(dev(A), dev(b), C, w.s, 0.0, w.rho, dev(w.z), dev(w.y))
+        for path in (1, 2, 3, 4):
+            nadmm.nadmm_set_kernel_path(path)
+            try:
+                nadmm.nadmm_query_kernel_path(gp)
+            except nadmm.NadmmError:
+                continue
+            loss, grad = nadmm.nadmm_loss_grad(gp, dev(X))
+            assert rel_abs(loss.item(), orc.loss(op, X)) <= TOL_PRIMITIVE, (vname, path)
+            assert rel_l2(host(grad), orc.grad(op, X)) <= TOL_PRIMITIVE, (vname, path)
+            hv = nadmm.nadmm_hessvec(gp, dev(X), dev(V))
+            assert rel_l2(host(hv), orc.hessvec(op, X, V)) <= TOL_PRIMITIVE, (vname, path)
+            if vname == "zero_data":     # H = rho I when A = 0 and lambda = 0
+                assert rel_l2(host(hv), w.rho * V.astype(np.float64)) <= 1e-6
+            hv0 = nadmm.nadmm_hessvec(gp, dev(X), dev(np.zeros_like(V)))
+            assert not host(hv0).any()
