@@ -375,3 +375,27 @@ def test_degenerate_inputs(cache, shape):
                 assert rel_l2(host(hv), w.rho * V.astype(np.float64)) <= 1e-6
             hv0 = nadmm.nadmm_hessvec(gp, dev(X), dev(np.zeros_like(V)))
             assert not host(hv0).any()
+
+
+def test_zero_iteration_budgets_and_longest_line_search(cache):
+    w, gp, op = setup_case(cache, "ragged_1237x45_C5")
+    X = x_for(w)
+    g32 = orc.grad(op, X).astype(np.float32)
+    # no CG iteration: the zero start is returned
+    p, iters, relres = nadmm.nadmm_cg_solve(gp, dev(X), dev(g32), 0, 0.0)
+    assert iters.item() == 0 and not host(p).any() and relres.item() == pytest.approx(1.0)
+    # no Newton iteration: X untouched
+    Xd = dev(X)
+    st = nadmm.nadmm_local_newton(gp, Xd, nadmm.make_params(0, 5, w.max_ls, 0.0, 0.0, w.beta, w.gamma))
+    assert st["newton_iters"] == 0 and np.array_equal(host(Xd), X)
+    # Newton iterations without CG: p = 0, the step changes nothing
+    st = nadmm.nadmm_local_newton(gp, Xd, nadmm.make_params(2, 0, w.max_ls, 0.0, 0.0, w.beta, w.gamma))
+    assert st["newton_iters"] == 2 and st["cg_iters_total"] == 0 and np.array_equal(host(Xd), X)
+    # the longest line search the library compiles for, on an ascent direction: i_max + 1 reductions, then the break
+    max_ls = nadmm.NADMM_MAX_LS
+    pdir = g32.copy()
+    alpha, f_new, ok = nadmm.nadmm_line_search(gp, dev(X), dev(pdir), dev(g32), math.nan, w.beta, 0.9, max_ls)
+    a_ref, f_ref, ok_ref, _ = orc.line_search(op, X, pdir, g32, w.beta, 0.9, max_ls)
+    assert not ok.item() and not ok_ref
+    assert alpha.item() == pytest.approx(0.9 ** (max_ls + 1), rel=1e-5) == pytest.approx(a_ref, rel=1e-5)
+    assert rel_abs(f_new.item(), f_ref) <= TOL_PRIMITIVE
