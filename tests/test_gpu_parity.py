@@ -399,3 +399,24 @@ def test_zero_iteration_budgets_and_longest_line_search(cache):
     assert not ok.item() and not ok_ref
     assert alpha.item() == pytest.approx(0.9 ** (max_ls + 1), rel=1e-5) == pytest.approx(a_ref, rel=1e-5)
     assert rel_abs(f_new.item(), f_ref) <= TOL_PRIMITIVE
+
+
+def test_two_streams_with_their_own_workspaces_do_not_interfere(cache):
+    w1, gp1, op1 = setup_case(cache, "fused_2000x100_C7")
+    w2, gp2, op2 = setup_case(cache, "ragged_1237x45_C5")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    params = nadmm.make_params(2, 5, 10, 0.0, 0.0, 1e-4, 0.5)
+    X1, X2 = dev(w1.X0.copy()), dev(w2.X0.copy())
+    ref1, ref2 = X1.clone(), X2.clone()
+    nadmm.nadmm_local_newton(gp1, ref1, params, want_stats=False)
+    nadmm.nadmm_local_newton(gp2, ref2, params, want_stats=False)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        X1.copy_(dev(w1.X0)); X2.copy_(dev(w2.X0))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s1):
+            nadmm.nadmm_local_newton(gp1, X1, params, want_stats=False, stream=s1)
+        with torch.cuda.stream(s2):
+            nadmm.nadmm_local_newton(gp2, X2, params, want_stats=False, stream=s2)
+        s1.synchronize(); s2.synchronize()
+        assert torch.equal(X1, ref1) and torch.equal(X2, ref2)
