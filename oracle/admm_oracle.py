@@ -32,7 +32,7 @@ i.e. the printed expressions with every squared norm replaced by the norm.
 The penalty parameters are fixed inputs (the spectral penalty selection of the
 paper is defined in a cited work only and is not part of this oracle).
 
-Parity status: pinned by tests/test_oracle_pins.py::test_admm_* (closed-form
+Parity status: pinned by tests/test_admm_oracle_pins.py (closed-form
 z-update against a direct minimisation, the invariant sum_i y_i = -lam z,
 convergence of z to the minimiser of the centralised problem, one worker
 without regulariser = repeated proximal steps).
