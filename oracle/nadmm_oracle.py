@@ -22,6 +22,11 @@ Conventions
         x = [x_1; ...; x_{C-1}] is the column-major flattening of X.  All
         vector operations used here (inner products, norms, axpy) do not
         depend on the flattening order.
+        A may also be a scipy.sparse matrix (the paper's data sets are "both
+        sparse and dense", Section 1): it is held as float64 compressed sparse
+        rows and every product with it below is scipy's sparse-times-dense
+        routine, a library primitive standing for the same matrix product.
+        Explicit entries repeated at one position are added up (scipy's rule).
     s   loss scale (1 = the paper's plain sum, 1/n = mean)
     z,y consensus variable and multiplier, same shape as X.  Sign convention of
         y: the penalty is ||X - z + y/rho||^2 (scaled form); the paper writes
@@ -30,7 +35,8 @@ Conventions
 Parity status: every function below is pinned by tests/test_oracle_pins.py
 (closed forms, library routines on the over-parametrised C-class form, finite
 differences, explicit brute-force Hessians, Krylov-subspace minimisation,
-direct solves and an independent minimiser).  The paper prints no worked
+direct solves and an independent minimiser; sparse storage of A against the
+dense results in tests/test_sparse_oracle_pins.py).  The paper prints no worked
 numerical example, so no value of the paper's is available as a pin.
 """
 from __future__ import annotations
@@ -39,6 +45,7 @@ from dataclasses import dataclass, field
 from typing import Optional
 
 import numpy as np
+import scipy.sparse as sp
 
 
 @dataclass
@@ -53,10 +60,13 @@ class Problem:
     rho: float = 1.0
     z: Optional[np.ndarray] = None
     y: Optional[np.ndarray] = None
-    A64: np.ndarray = field(init=False, repr=False)
+    A64: object = field(init=False, repr=False)   # float64 ndarray or scipy.sparse.csr_matrix
 
     def __post_init__(self):
-        self.A64 = np.asarray(self.A, dtype=np.float64)
+        if sp.issparse(self.A):
+            self.A64 = sp.csr_matrix(self.A, dtype=np.float64)
+        else:
+            self.A64 = np.asarray(self.A, dtype=np.float64)
         self.b = np.asarray(self.b, dtype=np.int64)
         n, p = self.A64.shape
         shape = (p, self.C - 1)

@@ -4,8 +4,10 @@ This module only draws inputs.  It holds none of the method's arithmetic and is
 imported neither by the HIP binding nor by the CPU oracle; tests, the smoke
 check and the benchmark hand the same float32 arrays to both sides.
 
-The real data sets (HIGGS, MNIST, CIFAR-10, E18) are not available; the five
-workloads below are synthetic stand-ins with their shapes.  Draws are made in
+The real data sets (HIGGS, MNIST, CIFAR-10, E18) are not available; the
+workloads below are synthetic stand-ins with their shapes.  `e18_like` is the
+sparse one: A is a scipy.sparse CSR matrix of float32 values and `extra["csc"]` holds the same matrix
+compressed by columns, the second view the GPU library asks for.  Draws are made in
 float64 with numpy's PCG64 and cast to float32; independent sub-streams are
 spawned from the seed in the fixed order A, labels, X, z, y, V.
 
@@ -18,6 +20,7 @@ from dataclasses import dataclass, field
 from typing import Optional
 
 import numpy as np
+import scipy.sparse as sp
 
 _ROW_CHUNK = 8192
 
@@ -25,7 +28,7 @@ _ROW_CHUNK = 8192
 @dataclass
 class Workload:
     name: str
-    A: np.ndarray           # n x p float32, row-major
+    A: object               # n x p float32: row-major ndarray, or scipy.sparse.csr_matrix
     b: np.ndarray           # n int32 labels in 0..C-1 (C-1 = reference class)
     C: int
     X0: np.ndarray          # p x (C-1) float32 starting point
@@ -43,6 +46,10 @@ class Workload:
     beta: float = 1e-4
     gamma: float = 0.5
     extra: dict = field(default_factory=dict)
+
+    @property
+    def sparse(self):
+        return sp.issparse(self.A)
 
     @property
     def n(self):
@@ -185,12 +192,76 @@ def generic(n, p, C, seed=0, lam=1e-3, rho=1.0, scale=1.0, x_std=0.3, mean=False
                     s=(1.0 / max(n, 1)) if mean else 1.0, max_newton=3, max_cg=5, max_ls=10)
 
 
+def _sparse_counts(rA, n, p, nnz_per_row, sigma):
+    """CSR/CSC pair with skewed column popularity: column weights are log-normal (a few columns are
+    present in most rows, most columns in few or none), positions are drawn with replacement and
+    repeated positions are merged, values are log(1 + k) of geometric counts k >= 1."""
+    w = np.exp(sigma * rA.standard_normal(p))
+    cdf = np.cumsum(w / w.sum())
+    cdf[-1] = 1.0
+    draws = int(n) * int(nnz_per_row)
+    key = np.empty(draws, dtype=np.int64)
+    step = 1 << 24
+    for k0 in range(0, draws, step):
+        k1 = min(draws, k0 + step)
+        cols = np.searchsorted(cdf, rA.random(k1 - k0), side="right").astype(np.int64)
+        np.minimum(cols, p - 1, out=cols)
+        key[k0:k1] = rA.integers(0, n, size=k1 - k0, dtype=np.int64) * p + cols
+    key = np.unique(key)                                   # sorted by (row, column), repeats merged
+    rows = (key // p).astype(np.int64)
+    cols = (key % p).astype(np.int32)
+    del key
+    val = np.log1p(rA.geometric(0.5, size=cols.size)).astype(np.float32)
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(np.bincount(rows, minlength=n), out=indptr[1:])
+    A = sp.csr_matrix((val, cols, indptr), shape=(n, p))
+    A.has_sorted_indices = True
+    return A
+
+
+def _with_csc(A):
+    At = A.tocsc()
+    At.sort_indices()
+    return At
+
+
+def e18_like(seed=0, n=40628, p=279998, nnz_per_row=2000):
+    """One of 32 workers' share of a data set shaped like E18 (Table 1: 1,300,128 samples, 279,998
+    features, 20 classes), stored sparse: about nnz_per_row entries per row, log-normal column
+    popularity (sigma 2), balanced labels."""
+    C = 20
+    rA, rb, rX, rz, ry, rV = _streams(seed)
+    A = _sparse_counts(rA, n, p, nnz_per_row, 2.0)
+    b = _balanced_labels(rb, n, C)
+    X0 = np.zeros((p, C - 1), dtype=np.float32)
+    z = _normal32(rz, (p, C - 1), 0.1)
+    y = _normal32(ry, (p, C - 1), 0.1)
+    V = _normal32(rV, (p, C - 1))
+    return Workload(f"e18_like_{n}x{p}_C{C}_sparse", A, b, C, X0, z, y, V, lam=1e-5, rho=1.0, s=1.0 / n,
+                    max_newton=10, max_cg=10, max_ls=10, extra={"csc": _with_csc(A)})
+
+
+def sparse_generic(n, p, C, nnz_per_row, seed=0, sigma=2.0, lam=1e-3, rho=1.0, x_std=0.3, mean=True):
+    """Free-shape sparse workload (same recipe as e18_like) for edge-case tests."""
+    rA, rb, rX, rz, ry, rV = _streams(seed)
+    A = _sparse_counts(rA, n, p, nnz_per_row, sigma)
+    b = rb.integers(0, C, size=n).astype(np.int32)
+    X0 = _normal32(rX, (p, C - 1), x_std)
+    z = _normal32(rz, (p, C - 1), 0.3)
+    y = _normal32(ry, (p, C - 1), 0.3)
+    V = _normal32(rV, (p, C - 1))
+    return Workload(f"sparse_{n}x{p}_C{C}", A, b, C, X0, z, y, V, lam=lam, rho=rho,
+                    s=(1.0 / max(n, 1)) if mean else 1.0, max_newton=3, max_cg=5, max_ls=10,
+                    extra={"csc": _with_csc(A)})
+
+
 CONFIGS = {
     "tiny": tiny,
     "image_like": image_like,
     "wide": wide,
     "tall_binary": tall_binary,
     "large_multiclass": large_multiclass,
+    "e18_like": e18_like,
 }
 
 
