@@ -23,7 +23,7 @@
  *     device memory in stream order.  Only nadmm_local_newton with a non-NULL
  *     h_stats synchronises the stream.
  *   - Layout of A: row-major n x p float32, row stride lda >= p elements, row i
- *     is sample a_i.  Labels: int32 in 0..C-1; class C-1 is the reference
+ *     is sample a_i; or sparse storage, see nadmm_sparse.  Labels: int32 in 0..C-1; class C-1 is the reference
  *     class with logit 0 (the paper's class C).  Label values and finiteness
  *     of A are not checked (out-of-range labels are treated as the reference
  *     class; no out-of-bounds access results).
@@ -49,9 +49,9 @@ extern "C" {
 typedef enum nadmm_status {
   NADMM_OK = 0,
   NADMM_EINVAL = -1,       /* null required pointer, n<1, p<1, C<2, lda<p, rho<=0, lambda<0,
-                              beta or gamma outside (0,1), negative iteration limits */
+                              beta or gamma outside (0,1), negative iteration limits, nnz<0 */
   NADMM_EWORKSPACE = -2,   /* workspace missing, misaligned or too small */
-  NADMM_EUNSUPPORTED = -3, /* shape outside the compiled range (C-1 > 32, max_ls > 62, n > 2^36, p (C-1) > 2^28) */
+  NADMM_EUNSUPPORTED = -3, /* shape outside the compiled range (C-1 > 32, max_ls > 62, n > 2^36 (sparse: 2^31 - 1), p (C-1) > 2^28) */
   NADMM_EHIP = -4          /* a HIP call or kernel launch failed */
 } nadmm_status;
 
@@ -59,9 +59,32 @@ typedef enum nadmm_status {
 #define NADMM_MAX_LS 62             /* largest supported max_ls */
 #define NADMM_TRACE_LEN 64          /* Newton iterations recorded in nadmm_stats */
 
+/*
+ * A in sparse storage (the paper reports on sparse as well as dense data sets, Section 1; its largest one,
+ * E18 of Table 1, has 279,998 features).  Two views of the same n x p matrix, both on the device and
+ * owned by the caller: compressed by rows for A V and A X, compressed by columns for A^T D (each
+ * output row of either product is then summed by one workgroup in a fixed order, without atomics).
+ *   row view:    entries k in [row_ptr[i], row_ptr[i+1]) belong to row i, at column col_idx[k], value val[k]
+ *   column view: entries k in [col_ptr[j], col_ptr[j+1]) belong to column j, at row row_idx[k], value val_t[k]
+ * Pointer arrays start at 0, do not decrease and end at nnz.  Entries of a row (column) may come in
+ * any order; an entry repeated at one position counts as the sum.  The arrays are not checked: an
+ * index outside its range is clamped into it and a pointer beyond nnz is cut off there (no
+ * out-of-bounds access results, the values computed are then meaningless); the two views are not
+ * compared with each other.  All arrays 4-byte (pointers: 8-byte) aligned; n <= 2^31 - 1.
+ */
+typedef struct nadmm_sparse {
+  int64_t        nnz;        /* stored entries, >= 0 */
+  const int64_t* d_row_ptr;  /* n + 1 */
+  const int32_t* d_col_idx;  /* nnz */
+  const float*   d_val;      /* nnz */
+  const int64_t* d_col_ptr;  /* p + 1 */
+  const int32_t* d_row_idx;  /* nnz */
+  const float*   d_val_t;    /* nnz */
+} nadmm_sparse;
+
 /* Borrowed views of one worker's data share and penalty parameters. */
 typedef struct nadmm_problem {
-  const float*   d_A;       /* n x p, row-major, device */
+  const float*   d_A;       /* n x p, row-major, device (ignored if `sparse` is given) */
   int64_t        n;         /* samples */
   int32_t        p;         /* features */
   int64_t        lda;       /* row stride of A in elements, >= p */
@@ -72,6 +95,8 @@ typedef struct nadmm_problem {
   float          rho;       /* > 0 */
   const float*   d_z;       /* p x (C-1), device; NULL = zeros */
   const float*   d_y;       /* p x (C-1), device; NULL = zeros */
+  const nadmm_sparse* sparse; /* HOST pointer, read during the call only; NULL = A is the dense array d_A.
+                                 If given, d_A and lda are ignored. */
 } nadmm_problem;
 
 /* Parameters of Algorithms 2 and 3 and of the CG iteration (Section 2.4). */
@@ -229,13 +254,14 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
  *       C-1 <= 16, p <= 960), 3 = thin-data single-pass kernel (p <= 32, p % 4 == 0,
  *       C-1 <= 3, lda == p), 4 = column-sliced two-sweep matrix-core kernels (the automatic
  *       choice where 2 and 3 do not apply: row stride a multiple of 4, A 16-byte aligned,
- *       C-1 <= 32).  A forced path that does not support the problem makes the
+ *       C-1 <= 32), 5 = sparse-storage kernels (the only path for a problem with `sparse` set,
+ *       and only for those).  A forced path that does not support the problem makes the
  *       compute calls return NADMM_EUNSUPPORTED.
  * Returns the previous value, or NADMM_EINVAL.
  */
 int nadmm_set_kernel_path(int path);
 
-/* Which path (1 to 4) is taken for this problem under the current setting; host-only. */
+/* Which path (1 to 5) is taken for this problem under the current setting; host-only. */
 int nadmm_query_kernel_path(const nadmm_problem* prob);
 
 #ifdef __cplusplus

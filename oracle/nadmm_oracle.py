@@ -22,8 +22,8 @@ Conventions
         x = [x_1; ...; x_{C-1}] is the column-major flattening of X.  All
         vector operations used here (inner products, norms, axpy) do not
         depend on the flattening order.
-        A may also be a scipy.sparse matrix (the paper's data sets are "both
-        sparse and dense", Section 1): it is held as float64 compressed sparse
+        A may also be a scipy.sparse matrix (the paper reports on sparse as well as
+        dense data sets, Section 1): it is held as float64 compressed sparse
         rows and every product with it below is scipy's sparse-times-dense
         routine, a library primitive standing for the same matrix product.
         Explicit entries repeated at one position are added up (scipy's rule).

@@ -15,7 +15,7 @@ OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnadmm.so")
 
 SOURCES = ["nadmm_api.hip", "nadmm_generic.hip", "nadmm_vec.hip", "nadmm_fused.hip", "nadmm_thin.hip", "nadmm_sliced.hip",
-           "nadmm_admm.hip"]
+           "nadmm_admm.hip", "nadmm_sparse.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

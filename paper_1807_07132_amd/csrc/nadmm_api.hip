@@ -21,15 +21,28 @@ struct Layout {
   size_t state, g, pdir, r, dvec, q;
   size_t drows, pcache, zx, zp;
   size_t partial, loss_part, lpart, dotpart, rrpart, zw;
+  size_t pack, win_rows, win_cols;  // sparse storage: packed dense operand, windows of the two views
   size_t total;
   int gen_row_blocks, gen_slabs, gen_chunks, gen_rpc;
   int fused_parts, thin_parts, sliced_parts;
   bool fused_ok, thin_ok, sliced_ok;
+  bool sparse;
+  int nwin_rows, nwin_cols;
 };
 
 int validate_problem(const nadmm_problem* p, bool need_labels) {
-  if (p == nullptr || p->d_A == nullptr) return NADMM_EINVAL;
-  if (p->n < 1 || p->p < 1 || p->C < 2 || p->lda < (int64_t)p->p) return NADMM_EINVAL;
+  if (p == nullptr) return NADMM_EINVAL;
+  if (p->n < 1 || p->p < 1 || p->C < 2) return NADMM_EINVAL;
+  if (p->sparse != nullptr) {
+    const nadmm_sparse* sp = p->sparse;
+    if (sp->nnz < 0 || sp->d_row_ptr == nullptr || sp->d_col_ptr == nullptr) return NADMM_EINVAL;
+    if (sp->nnz > 0 && (sp->d_col_idx == nullptr || sp->d_val == nullptr || sp->d_row_idx == nullptr ||
+                        sp->d_val_t == nullptr))
+      return NADMM_EINVAL;
+    if (p->n > (int64_t)INT32_MAX) return NADMM_EUNSUPPORTED;  // row indices are 32-bit
+  } else if (p->d_A == nullptr || p->lda < (int64_t)p->p) {
+    return NADMM_EINVAL;
+  }
   if (!(p->rho > 0.f) || !(p->lambda >= 0.f) || !std::isfinite(p->rho) || !std::isfinite(p->lambda)) return NADMM_EINVAL;
   if (!std::isfinite(p->loss_scale)) return NADMM_EINVAL;
   if (need_labels && p->d_labels == nullptr) return NADMM_EINVAL;
@@ -46,11 +59,13 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   s.NC = p->C - 1;
   s.d = (int64_t)s.p * s.NC;
   L->s = s;
+  L->sparse = p->sparse != nullptr;
   L->gen_row_blocks = generic_row_blocks(s.n);
   generic_col_grid(s, &L->gen_slabs, &L->gen_chunks, &L->gen_rpc);
-  L->fused_ok = fused_supported(s, p->lda, p->d_A);
+  if (L->sparse) L->gen_chunks = 1;  // the column view gives every element of A^T D whole
+  L->fused_ok = !L->sparse && fused_supported(s, p->lda, p->d_A);
   L->fused_parts = L->fused_ok ? fused_num_partials(s) : 0;
-  L->thin_ok = thin_supported(s, p->lda, p->d_A);
+  L->thin_ok = !L->sparse && thin_supported(s, p->lda, p->d_A);
   L->thin_parts = L->thin_ok ? thin_num_partials(s) : 0;
   const size_t vec = align256((size_t)s.d * sizeof(float));
   const size_t rows = align256((size_t)s.n * s.NC * sizeof(float));
@@ -65,7 +80,7 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   L->pcache = off; off += rows;
   L->zx = off; off += rows;
   L->zp = off; off += rows;
-  L->sliced_ok = sliced_supported(s, p->lda, p->d_A);
+  L->sliced_ok = !L->sparse && sliced_supported(s, p->lda, p->d_A);
   L->sliced_parts = 0;
   if (L->sliced_ok) {
     int sps = 0, S2 = 0;
@@ -81,8 +96,21 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   L->lpart = off; off += align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
   L->dotpart = off; off += align256((size_t)2 * reduce_out_blocks(s.d) * sizeof(double));  // two sums per workgroup
   L->rrpart = off; off += align256((size_t)cg_update_blocks(s.d) * sizeof(double));
-  // per-slice partial logits of the column-sliced path
-  L->zw = off; off += align256(L->sliced_ok ? sliced_zw_bytes(s) : 0);
+  // per-slice partial logits of the column-sliced path; the logits [Z | W] of the sparse path
+  L->zw = off; off += align256(L->sliced_ok ? sliced_zw_bytes(s) : (L->sparse ? (size_t)s.n * 2 * s.NC * sizeof(float) : 0));
+  L->pack = off;
+  L->win_rows = off;
+  L->win_cols = off;
+  L->nwin_rows = L->nwin_cols = 0;
+  if (L->sparse) {
+    const size_t npad = (size_t)sparse_pad(s.NC);
+    const size_t a = (size_t)s.p * 2 * npad, b = (size_t)s.n * npad;  // [X | V] or D, rows padded
+    off += align256((a > b ? a : b) * sizeof(float));
+    L->nwin_rows = sparse_windows(s.n, p->sparse->nnz);
+    L->nwin_cols = sparse_windows(s.p, p->sparse->nnz);
+    L->win_rows = off; off += align256((size_t)(L->nwin_rows + 1) * sizeof(int32_t));
+    L->win_cols = off; off += align256((size_t)(L->nwin_cols + 1) * sizeof(int32_t));
+  }
   L->total = off;
 }
 
@@ -106,8 +134,14 @@ int hip_fail(hipError_t e) {
   } while (0)
 
 // 1 = two-pass vector kernels, 2 = fused single pass (matrix cores), 3 = thin-data single pass,
-// 4 = column-sliced two-sweep matrix-core path
+// 4 = column-sliced two-sweep matrix-core path, 5 = sparse storage
 int choose_path(const Layout& L, int* path) {
+  if (L.sparse) {
+    if (g_path != 0 && g_path != 5) return NADMM_EUNSUPPORTED;
+    *path = 5;
+    return NADMM_OK;
+  }
+  if (g_path == 5) return NADMM_EUNSUPPORTED;
   if (g_path == 1) { *path = 1; return NADMM_OK; }
   if (g_path == 2) {
     if (!L.fused_ok) return NADMM_EUNSUPPORTED;
@@ -132,6 +166,23 @@ int loss_blocks(const Layout& L, int path) {
   return path == 3 ? L.thin_parts : (path == 2 ? L.fused_parts : L.gen_row_blocks);  // paths 1 and 4: row blocks
 }
 
+SparseView row_view(const nadmm_problem* prob) {
+  const nadmm_sparse* sp = prob->sparse;
+  return SparseView{sp->d_row_ptr, sp->d_col_idx, sp->d_val, prob->n, prob->p, sp->nnz};
+}
+SparseView col_view(const nadmm_problem* prob) {
+  const nadmm_sparse* sp = prob->sparse;
+  return SparseView{sp->d_col_ptr, sp->d_row_idx, sp->d_val_t, (int64_t)prob->p, (int32_t)prob->n, sp->nnz};
+}
+
+// Sparse storage: the windows of equal cost of both views, once per entry-point call (they depend on the
+// pointer arrays only, but the workspace is the caller's between calls).
+int sparse_plan(const nadmm_problem* prob, const Layout& L, void* ws, hipStream_t st) {
+  NADMM_HIP(launch_sparse_plan(row_view(prob), at<int32_t>(ws, L.win_rows), L.nwin_rows, st));
+  NADMM_HIP(launch_sparse_plan(col_view(prob), at<int32_t>(ws, L.win_cols), L.nwin_cols, st));
+  return NADMM_OK;
+}
+
 // One sweep over A: rows pass, and (if with_cols) partial sums of A^T rows_out.
 int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArgs ra, bool with_cols,
           int* nparts, hipStream_t st) {
@@ -140,6 +191,34 @@ int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArg
   ra.p = prob->p;
   ra.lda = prob->lda;
   ra.NC = L.s.NC;
+  if (path == 5) {
+    SpmmArgs sa;
+    sa.NC = L.s.NC;
+    sa.NCpad = sparse_pad(L.s.NC);
+    sa.flag = ra.flag;
+    sa.B = at<float>(ws, L.pack);
+    if (ra.B0 != nullptr || ra.B1 != nullptr) {  // [Z | W] = A [X | V]
+      NADMM_HIP(launch_sparse_pack(ra.B0, ra.B1, prob->p, L.s.NC, at<float>(ws, L.pack), ra.flag, st));
+      sa.S = row_view(prob);
+      sa.out = at<float>(ws, L.zw);
+      sa.nops = (ra.B0 != nullptr && ra.B1 != nullptr) ? 2 : 1;
+      sa.win = at<int32_t>(ws, L.win_rows);
+      sa.nwin = L.nwin_rows;
+      NADMM_HIP(launch_spmm(sa, st));
+    }
+    NADMM_HIP(launch_logit_rows(ra, at<float>(ws, L.zw), 1, st));
+    if (with_cols) {  // A^T D from the column view
+      NADMM_HIP(launch_sparse_pack(ra.rows_out, nullptr, prob->n, L.s.NC, at<float>(ws, L.pack), ra.flag, st));
+      sa.S = col_view(prob);
+      sa.out = at<float>(ws, L.partial);
+      sa.nops = 1;
+      sa.win = at<int32_t>(ws, L.win_cols);
+      sa.nwin = L.nwin_cols;
+      NADMM_HIP(launch_spmm(sa, st));
+      *nparts = 1;
+    }
+    return NADMM_OK;
+  }
   if (path == 2) {
     NADMM_HIP(launch_fused(ra, with_cols ? at<float>(ws, L.partial) : nullptr, L.fused_parts, st));
     *nparts = L.fused_parts;
@@ -297,6 +376,7 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
   float* r = at<float>(d_ws, L.r);
   float* dvec = at<float>(d_ws, L.dvec);
 
+  if (path == 5 && (rc = sparse_plan(prob, L, d_ws, st)) != NADMM_OK) return rc;
   NADMM_HIP(launch_state_init(ds, outer_flag, st));
   const int ncand = params->max_ls + 2;
 
@@ -445,7 +525,7 @@ const char* nadmm_status_string(int code) {
 const char* nadmm_last_hip_error(void) { return g_last_hip_error.c_str(); }
 
 int nadmm_set_kernel_path(int path) {
-  if (path < 0 || path > 4) return NADMM_EINVAL;
+  if (path < 0 || path > 5) return NADMM_EINVAL;
   const int prev = g_path;
   g_path = path;
   return prev;
@@ -480,6 +560,7 @@ int nadmm_loss_grad(const nadmm_problem* prob, const float* d_X, double* d_loss,
   int path = 0;
   if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
+  if (path == 5 && (rc = sparse_plan(prob, L, d_ws, st)) != NADMM_OK) return rc;
 
   RowArgs ra = blank_rows();
   ra.kind = d_grad ? kRowsGrad : kRowsLoss;
@@ -522,6 +603,7 @@ int nadmm_hessvec(const nadmm_problem* prob, const float* d_X, const float* d_V,
   if ((rc = check_ws(L, d_ws, ws_bytes)) != NADMM_OK) return rc;
   int path = 0;
   if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
+  if (path == 5 && (rc = sparse_plan(prob, L, d_ws, (hipStream_t)stream)) != NADMM_OK) return rc;
   return hv_apply(prob, L, path, d_ws, d_X, false, d_V, d_HV, nullptr, nullptr, nullptr, (hipStream_t)stream);
 }
 
@@ -537,6 +619,7 @@ int nadmm_cg_solve(const nadmm_problem* prob, const float* d_X, const float* d_g
   if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   DevState* ds = at<DevState>(d_ws, L.state);
+  if (path == 5 && (rc = sparse_plan(prob, L, d_ws, st)) != NADMM_OK) return rc;
 
   NADMM_HIP(launch_state_init(ds, nullptr, st));
   NewtonHeadArgs nh;
@@ -578,6 +661,7 @@ int nadmm_line_search(const nadmm_problem* prob, const float* d_X, const float* 
   if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   DevState* ds = at<DevState>(d_ws, L.state);
+  if (path == 5 && (rc = sparse_plan(prob, L, d_ws, st)) != NADMM_OK) return rc;
   NADMM_HIP(launch_state_init(ds, nullptr, st));
 
   RowArgs ra = blank_rows();

@@ -23,12 +23,48 @@ NADMM_MAX_LS = 62
 NADMM_MAX_FREE_CLASSES = 32
 
 
+class nadmm_sparse(C.Structure):
+    _fields_ = [
+        ("nnz", C.c_int64), ("d_row_ptr", C.c_void_p), ("d_col_idx", C.c_void_p), ("d_val", C.c_void_p),
+        ("d_col_ptr", C.c_void_p), ("d_row_idx", C.c_void_p), ("d_val_t", C.c_void_p),
+    ]
+
+
 class nadmm_problem(C.Structure):
     _fields_ = [
         ("d_A", C.c_void_p), ("n", C.c_int64), ("p", C.c_int32), ("lda", C.c_int64),
         ("d_labels", C.c_void_p), ("C", C.c_int32), ("loss_scale", C.c_float),
         ("lambda_", C.c_float), ("rho", C.c_float), ("d_z", C.c_void_p), ("d_y", C.c_void_p),
+        ("sparse", C.POINTER(nadmm_sparse)),
     ]
+
+
+class SparseA:
+    """Device-resident sparse storage of A: the row view (row_ptr int64 n+1, col_idx int32, val float32)
+    and the column view (col_ptr int64 p+1, row_idx int32, val_t float32) of the same n x p matrix."""
+
+    def __init__(self, n, p, row_ptr, col_idx, val, col_ptr, row_idx, val_t):
+        self.shape = (int(n), int(p))
+        self.nnz = int(val.numel())
+        for t, dt, cnt in ((row_ptr, torch.int64, n + 1), (col_idx, torch.int32, self.nnz), (val, torch.float32, self.nnz),
+                           (col_ptr, torch.int64, p + 1), (row_idx, torch.int32, self.nnz),
+                           (val_t, torch.float32, self.nnz)):
+            assert t.is_cuda and t.dtype == dt and t.is_contiguous() and t.numel() == cnt
+        self.tensors = (row_ptr, col_idx, val, col_ptr, row_idx, val_t)
+        self.device = val.device
+        self.c = nadmm_sparse(self.nnz, *[t.data_ptr() for t in self.tensors])
+
+    @classmethod
+    def from_scipy(cls, csr, csc, device="cuda"):
+        """Uploads a scipy.sparse CSR matrix and the CSC form of the same matrix (format conversion of the
+        index types only)."""
+        import numpy as np
+        dev = torch.device(device)
+        up = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a, dtype=dt)).to(dev)
+        n, p = csr.shape
+        assert csc.shape == csr.shape and csc.nnz == csr.nnz
+        return cls(n, p, up(csr.indptr, np.int64), up(csr.indices, np.int32), up(csr.data, np.float32),
+                   up(csc.indptr, np.int64), up(csc.indices, np.int32), up(csc.data, np.float32))
 
 
 class nadmm_params(C.Structure):
@@ -131,9 +167,12 @@ def _stream(stream):
 class Problem:
     """Device-resident data share.  Keeps the tensors alive and builds the C view."""
 
-    def __init__(self, A: torch.Tensor, labels: Optional[torch.Tensor], C_: int, loss_scale: float, lam: float,
+    def __init__(self, A, labels: Optional[torch.Tensor], C_: int, loss_scale: float, lam: float,
                  rho: float, z: Optional[torch.Tensor] = None, y: Optional[torch.Tensor] = None):
-        assert A.is_cuda and A.dtype == torch.float32 and A.dim() == 2 and A.stride(1) == 1
+        """A: n x p float32 device tensor (rows contiguous), or a SparseA."""
+        self.is_sparse = isinstance(A, SparseA)
+        if not self.is_sparse:
+            assert A.is_cuda and A.dtype == torch.float32 and A.dim() == 2 and A.stride(1) == 1
         self.A, self.labels, self.C, self.z, self.y = A, labels, int(C_), z, y
         self.n, self.p = A.shape
         self.NC = self.C - 1
@@ -143,17 +182,20 @@ class Problem:
         for t in (z, y):
             if t is not None:
                 assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == self.p * self.NC
-        self.c = nadmm_problem(A.data_ptr(), self.n, self.p, A.stride(0),
+        self.c = nadmm_problem(None if self.is_sparse else A.data_ptr(), self.n, self.p,
+                               self.p if self.is_sparse else A.stride(0),
                                labels.data_ptr() if labels is not None else None, self.C,
                                self.loss_scale, self.lam, self.rho,
-                               z.data_ptr() if z is not None else None, y.data_ptr() if y is not None else None)
+                               z.data_ptr() if z is not None else None, y.data_ptr() if y is not None else None,
+                               C.pointer(A.c) if self.is_sparse else None)
         self._ws = None
 
     @classmethod
     def from_workload(cls, w, device="cuda"):
         dev = torch.device(device)
         to = lambda a: torch.from_numpy(a).to(dev)
-        return cls(to(w.A), to(w.b), w.C, w.s, w.lam, w.rho, to(w.z), to(w.y))
+        A = SparseA.from_scipy(w.A, w.extra["csc"], dev) if w.sparse else to(w.A)
+        return cls(A, to(w.b), w.C, w.s, w.lam, w.rho, to(w.z), to(w.y))
 
     def workspace(self) -> torch.Tensor:
         if self._ws is None:

@@ -45,10 +45,11 @@ def test_struct_layout_matches_the_header(tmp_path):
     src = tmp_path / "sizes.c"
     src.write_text(
         '#include <stdio.h>\n#include <stddef.h>\n#include "nadmm.h"\n'
-        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(nadmm_problem), sizeof(nadmm_params),"
+        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(nadmm_problem), sizeof(nadmm_params),"
         " sizeof(nadmm_stats), offsetof(nadmm_problem, d_labels), offsetof(nadmm_problem, d_z),"
         " offsetof(nadmm_stats, loss_initial), offsetof(nadmm_stats, grad_norm), sizeof(nadmm_admm_params),"
-        " sizeof(nadmm_admm_stats), offsetof(nadmm_admm_params, local), offsetof(nadmm_admm_stats, d_trace));return 0;}\n")
+        " sizeof(nadmm_admm_stats), offsetof(nadmm_admm_params, local), offsetof(nadmm_admm_stats, d_trace),"
+        " offsetof(nadmm_problem, sparse), sizeof(nadmm_sparse), offsetof(nadmm_sparse, d_val_t));return 0;}\n")
     exe = tmp_path / "sizes"
     subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", f"-I{os.path.join(ROOT, 'include')}", str(src), "-o", str(exe)])
     got = [int(v) for v in subprocess.check_output([str(exe)]).split()]
@@ -56,12 +57,60 @@ def test_struct_layout_matches_the_header(tmp_path):
             nadmm.nadmm_problem.d_labels.offset, nadmm.nadmm_problem.d_z.offset,
             nadmm.nadmm_stats.loss_initial.offset, nadmm.nadmm_stats.grad_norm.offset,
             C.sizeof(nadmm.nadmm_admm_params), C.sizeof(nadmm.nadmm_admm_stats), nadmm.nadmm_admm_params.local.offset,
-            nadmm.nadmm_admm_stats.d_trace.offset]
+            nadmm.nadmm_admm_stats.d_trace.offset, nadmm.nadmm_problem.sparse.offset, C.sizeof(nadmm.nadmm_sparse),
+            nadmm.nadmm_sparse.d_val_t.offset]
     assert got == want
 
 
 def fake_problem(n=1000, p=20, Cc=3, lda=None, rho=1.0, lam=1e-3, A=0x1000, labels=0x2000):
-    return nadmm.nadmm_problem(A, n, p, p if lda is None else lda, labels, Cc, 1.0, lam, rho, None, None)
+    return nadmm.nadmm_problem(A, n, p, p if lda is None else lda, labels, Cc, 1.0, lam, rho, None, None, None)
+
+
+def fake_sparse(nnz=5000, **kw):
+    f = dict(nnz=nnz, d_row_ptr=0x4000, d_col_idx=0x5000, d_val=0x6000, d_col_ptr=0x7000, d_row_idx=0x8000,
+             d_val_t=0x9000)
+    f.update(kw)
+    return nadmm.nadmm_sparse(f["nnz"], f["d_row_ptr"], f["d_col_idx"], f["d_val"], f["d_col_ptr"], f["d_row_idx"],
+                              f["d_val_t"])
+
+
+def sparse_problem(sp, **kw):
+    prob = fake_problem(A=None, **kw)
+    prob.sparse = C.pointer(sp)
+    return prob
+
+
+def test_sparse_problems_on_the_host(lib):
+    fake = C.c_void_p(0x3000)
+    sp = fake_sparse()
+    prob = sparse_problem(sp, n=1000, p=3000, Cc=5)
+    need = lib.nadmm_workspace_bytes(C.byref(prob), None)
+    assert need > 0 and need % 256 == 0
+    assert lib.nadmm_query_kernel_path(C.byref(prob)) == 5
+    # no dense array is needed, and a dense problem never takes the sparse path
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem())) in (1, 2, 3, 4)
+    prev = lib.nadmm_set_kernel_path(5)
+    try:
+        assert lib.nadmm_query_kernel_path(C.byref(fake_problem())) == nadmm.NADMM_EUNSUPPORTED
+        assert lib.nadmm_query_kernel_path(C.byref(prob)) == 5
+        lib.nadmm_set_kernel_path(1)
+        assert lib.nadmm_query_kernel_path(C.byref(prob)) == nadmm.NADMM_EUNSUPPORTED
+    finally:
+        lib.nadmm_set_kernel_path(prev)
+    # more stored entries need more windows, hence more workspace
+    sp_big = fake_sparse(nnz=50_000_000)
+    assert lib.nadmm_workspace_bytes(C.byref(sparse_problem(sp_big, n=1000, p=3000, Cc=5)), None) > need
+    for bad in (fake_sparse(nnz=-1), fake_sparse(d_row_ptr=None), fake_sparse(d_col_ptr=None), fake_sparse(d_val=None),
+                fake_sparse(d_row_idx=None), fake_sparse(d_val_t=None), fake_sparse(d_col_idx=None)):
+        pb = sparse_problem(bad, n=1000, p=3000, Cc=5)
+        assert lib.nadmm_workspace_bytes(C.byref(pb), None) == 0
+        assert lib.nadmm_hessvec(C.byref(pb), fake, fake, fake, fake, 1 << 30, None) == nadmm.NADMM_EINVAL
+    # an empty matrix needs no index or value arrays
+    empty = fake_sparse(nnz=0, d_col_idx=None, d_val=None, d_row_idx=None, d_val_t=None)
+    assert lib.nadmm_workspace_bytes(C.byref(sparse_problem(empty, n=1000, p=3000, Cc=5)), None) > 0
+    huge = sparse_problem(sp, n=(1 << 31), p=30, Cc=3)
+    assert lib.nadmm_hessvec(C.byref(huge), fake, fake, fake, fake, 1 << 30, None) == nadmm.NADMM_EUNSUPPORTED
+    assert lib.nadmm_hessvec(C.byref(prob), fake, fake, fake, fake, need - 1, None) == nadmm.NADMM_EWORKSPACE
 
 
 def test_workspace_bytes(lib):

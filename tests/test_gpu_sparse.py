@@ -1,0 +1,244 @@
+"""GPU parity of the sparse-storage path: every entry point of the C ABI on A given as compressed rows
+plus compressed columns, against the float64 CPU oracle on the same matrix, element by element.
+
+Tolerances as for the dense paths: 1e-4 relative (L2) for loss, gradient and Hessian-vector product,
+1e-3 for Newton-CG iterates.  Shapes cover every compiled width of the packed operand rows (C-1 from 1
+to 32), rows and columns shorter than a wave, longer than the length at which a workgroup's waves
+share a row, and longer than a whole window of work, empty rows and columns, and an empty matrix.
+"""
+import dataclasses
+import math
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+import torch
+
+from oracle import admm_oracle as adm
+from oracle import nadmm_oracle as orc
+from paper_1807_07132_amd import nadmm, workloads
+from parity_utils import TOL_ITERATE, TOL_PRIMITIVE, oracle_newton_following, oracle_problem, rel_abs, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+CASES = {
+    # many short rows, half of the columns empty
+    "short_300x500_C5": lambda: workloads.sparse_generic(300, 500, 5, 12, seed=3),
+    # the benchmark's class count (packed rows of 20 and 40 floats), rows of about two wave steps
+    "e18_shape_2000x9000_C20": lambda: workloads.sparse_generic(2000, 9000, 20, 120, seed=4, x_std=0.1),
+    # rows of about 1300 entries: shared by the waves of a workgroup, one window holds three of them
+    "long_rows_150x6000_C3": lambda: workloads.sparse_generic(150, 6000, 3, 1500, seed=5, sigma=1.0, x_std=0.05),
+    # rows longer than a window of work (about 5400 entries each)
+    "huge_rows_40x20000_C4": lambda: workloads.sparse_generic(40, 20000, 4, 6000, seed=6, sigma=0.5, x_std=0.02),
+    # few columns: every column is present in most of the 5000 rows (columns far longer than a window)
+    "long_cols_5000x40_C10": lambda: workloads.sparse_generic(5000, 40, 10, 20, seed=7),
+    "binary_3000x800_C2": lambda: workloads.sparse_generic(3000, 800, 2, 30, seed=8),
+    "max_classes_400x700_C33": lambda: workloads.sparse_generic(400, 700, 33, 25, seed=9, x_std=0.1),
+    "single_row_1x50_C4": lambda: workloads.sparse_generic(1, 50, 4, 9, seed=10),
+    "single_column_300x1_C3": lambda: workloads.sparse_generic(300, 1, 3, 1, seed=11),
+}
+# one class count from each width of the packed rows (4, 8, ..., 32 floats; twice that with two operands)
+WIDTH_CASES = [2, 6, 10, 14, 18, 24, 27, 32]
+
+
+@pytest.fixture(scope="module")
+def cache():
+    return {}
+
+
+def setup_case(cache, name):
+    if name not in cache:
+        w = CASES[name]()
+        cache[name] = (w, nadmm.Problem.from_workload(w), oracle_problem(w))
+    return cache[name]
+
+
+def x_for(w):
+    return w.X0 if w.X0.any() else (np.random.default_rng(11).standard_normal(w.X0.shape) * 0.2).astype(np.float32)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_loss_gradient_and_hessvec(cache, name):
+    w, gp, op = setup_case(cache, name)
+    assert nadmm.nadmm_query_kernel_path(gp) == 5
+    for X in (x_for(w), np.zeros_like(w.X0)):
+        loss, grad = nadmm.nadmm_loss_grad(gp, dev(X))
+        loss_only, none = nadmm.nadmm_loss_grad(gp, dev(X), want_grad=False)
+        f_ref, g_ref = orc.loss_grad(op, X)
+        assert none is None
+        assert rel_abs(loss.item(), f_ref) <= TOL_PRIMITIVE
+        assert rel_abs(loss_only.item(), f_ref) <= TOL_PRIMITIVE
+        assert rel_l2(host(grad), g_ref) <= TOL_PRIMITIVE
+    X = x_for(w)
+    hv = nadmm.nadmm_hessvec(gp, dev(X), dev(w.V))
+    assert rel_l2(host(hv), orc.hessvec(op, X, w.V)) <= TOL_PRIMITIVE
+    hv2 = nadmm.nadmm_hessvec(gp, dev(X), dev(w.V))      # fixed order of additions: bit-identical
+    assert torch.equal(hv, hv2)
+
+
+@pytest.mark.parametrize("C", WIDTH_CASES)
+def test_every_packed_width(C):
+    w = workloads.sparse_generic(700, 900, C, 40, seed=20 + C, x_std=0.1)
+    gp, op = nadmm.Problem.from_workload(w), oracle_problem(w)
+    X = w.X0
+    loss, grad = nadmm.nadmm_loss_grad(gp, dev(X))
+    f_ref, g_ref = orc.loss_grad(op, X)
+    assert rel_abs(loss.item(), f_ref) <= TOL_PRIMITIVE
+    assert rel_l2(host(grad), g_ref) <= TOL_PRIMITIVE
+    assert rel_l2(host(nadmm.nadmm_hessvec(gp, dev(X), dev(w.V))), orc.hessvec(op, X, w.V)) <= TOL_PRIMITIVE
+
+
+def test_sparse_and_dense_storage_of_one_matrix_agree(cache):
+    w, gp, op = setup_case(cache, "short_300x500_C5")
+    dense = nadmm.Problem(dev(w.A.toarray()), dev(w.b), w.C, w.s, w.lam, w.rho, dev(w.z), dev(w.y))
+    assert nadmm.nadmm_query_kernel_path(dense) != 5
+    X = x_for(w)
+    a = host(nadmm.nadmm_hessvec(gp, dev(X), dev(w.V)))
+    b = host(nadmm.nadmm_hessvec(dense, dev(X), dev(w.V)))
+    assert rel_l2(a, b) <= 1e-5
+    nadmm.nadmm_set_kernel_path(1)
+    try:
+        with pytest.raises(nadmm.NadmmError) as e:       # a dense-storage kernel cannot be forced on it
+            nadmm.nadmm_hessvec(gp, dev(X), dev(w.V))
+        assert e.value.code == nadmm.NADMM_EUNSUPPORTED
+    finally:
+        nadmm.nadmm_set_kernel_path(0)
+
+
+def test_unsorted_and_repeated_entries():
+    rng = np.random.default_rng(31)
+    n, p, C = 500, 300, 4
+    lens = rng.integers(0, 40, size=n)
+    indptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    indices = rng.integers(0, p, size=indptr[-1]).astype(np.int32)     # any order, positions repeat
+    data = rng.standard_normal(indptr[-1]).astype(np.float32)
+    A = sp.csr_matrix((data, indices, indptr), shape=(n, p))
+    assert not A.has_canonical_format
+    perm = rng.permutation(A.nnz)                                      # column view in scrambled order within columns
+    coo = A.tocoo()
+    order = perm[np.argsort(coo.col[perm], kind="stable")]
+    cptr = np.concatenate([[0], np.cumsum(np.bincount(coo.col, minlength=p))]).astype(np.int64)
+    At = sp.csc_matrix((coo.data[order], coo.row[order].astype(np.int32), cptr), shape=(n, p))
+    b = rng.integers(0, C, size=n).astype(np.int32)
+    X = (rng.standard_normal((p, C - 1)) * 0.3).astype(np.float32)
+    V = rng.standard_normal((p, C - 1)).astype(np.float32)
+    gp = nadmm.Problem(nadmm.SparseA.from_scipy(A, At), dev(b), C, 1.0 / n, 1e-3, 1.0, None, None)
+    op = orc.Problem(A, b, C, s=1.0 / n, lam=1e-3, rho=1.0)
+    loss, grad = nadmm.nadmm_loss_grad(gp, dev(X))
+    assert rel_abs(loss.item(), orc.loss(op, X)) <= TOL_PRIMITIVE
+    assert rel_l2(host(grad), orc.grad(op, X)) <= TOL_PRIMITIVE
+    assert rel_l2(host(nadmm.nadmm_hessvec(gp, dev(X), dev(V))), orc.hessvec(op, X, V)) <= TOL_PRIMITIVE
+
+
+def test_mostly_empty_rows_and_columns():
+    # 30000 rows with 2000 entries in all: windows of work that hold hundreds of empty rows
+    rng = np.random.default_rng(32)
+    n, p, C = 30000, 4000, 3
+    A = sp.random(n, p, density=2000 / (n * p), random_state=33, format="csr", dtype=np.float32)
+    b = rng.integers(0, C, size=n).astype(np.int32)
+    X = (rng.standard_normal((p, C - 1)) * 0.5).astype(np.float32)
+    V = rng.standard_normal((p, C - 1)).astype(np.float32)
+    gp = nadmm.Problem(nadmm.SparseA.from_scipy(A, A.tocsc()), dev(b), C, 1.0 / n, 1e-3, 1.0, None, None)
+    op = orc.Problem(A, b, C, s=1.0 / n, lam=1e-3, rho=1.0)
+    loss, grad = nadmm.nadmm_loss_grad(gp, dev(X))
+    assert rel_abs(loss.item(), orc.loss(op, X)) <= TOL_PRIMITIVE
+    assert rel_l2(host(grad), orc.grad(op, X)) <= TOL_PRIMITIVE
+    assert rel_l2(host(nadmm.nadmm_hessvec(gp, dev(X), dev(V))), orc.hessvec(op, X, V)) <= TOL_PRIMITIVE
+
+
+def test_empty_matrix():
+    n, p, C = 70, 30, 5
+    A = sp.csr_matrix((n, p), dtype=np.float32)
+    rng = np.random.default_rng(2)
+    b = rng.integers(0, C, size=n).astype(np.int32)
+    X = rng.standard_normal((p, C - 1)).astype(np.float32)
+    V = rng.standard_normal((p, C - 1)).astype(np.float32)
+    gp = nadmm.Problem(nadmm.SparseA.from_scipy(A, A.tocsc()), dev(b), C, 1.0, 0.25, 2.0, None, None)
+    loss, grad = nadmm.nadmm_loss_grad(gp, dev(X))
+    x64 = X.astype(np.float64)
+    assert loss.item() == pytest.approx(n * math.log(C) + 0.5 * (0.25 + 2.0) * np.sum(x64 * x64), rel=1e-6)
+    assert rel_l2(host(grad), 2.25 * x64) <= 1e-6
+    assert rel_l2(host(nadmm.nadmm_hessvec(gp, dev(X), dev(V))), 2.25 * V.astype(np.float64)) <= 1e-6
+
+
+@pytest.mark.parametrize("name", ["short_300x500_C5", "e18_shape_2000x9000_C20", "long_rows_150x6000_C3",
+                                  "long_cols_5000x40_C10"])
+def test_cg_fixed_iterations(cache, name):
+    w, gp, op = setup_case(cache, name)
+    X = x_for(w)
+    g32 = orc.grad(op, X).astype(np.float32)
+    for K in (1, 5):
+        p, iters, relres = nadmm.nadmm_cg_solve(gp, dev(X), dev(g32), K, 0.0)
+        p_ref, k_ref, rel_ref = orc.cg(op, X, g32, K, 0.0)
+        assert iters.item() == k_ref == K
+        assert rel_l2(host(p), p_ref) <= TOL_ITERATE
+        if rel_ref > 1e-5:
+            assert relres.item() == pytest.approx(rel_ref, rel=5e-3)
+        else:
+            assert relres.item() < 1e-5
+
+
+@pytest.mark.parametrize("name", ["short_300x500_C5", "long_cols_5000x40_C10", "binary_3000x800_C2"])
+def test_line_search(cache, name):
+    w, gp, op = setup_case(cache, name)
+    X = x_for(w)
+    g = orc.grad(op, X)
+    for scale, max_ls in ((1.0, 10), (300.0, 12), (-1.0, 3)):
+        p = (-scale * g).astype(np.float32)
+        g32 = g.astype(np.float32)
+        a_ref, f_ref, ok_ref, _ = orc.line_search(op, X, p, g32, w.beta, w.gamma, max_ls)
+        for f0 in (math.nan, orc.loss(op, X)):
+            alpha, f_new, ok = nadmm.nadmm_line_search(gp, dev(X), dev(p), dev(g32), f0, w.beta, w.gamma, max_ls)
+            assert alpha.item() == pytest.approx(a_ref, rel=1e-6)
+            assert bool(ok.item()) == ok_ref
+            assert rel_abs(f_new.item(), f_ref) <= TOL_PRIMITIVE
+
+
+@pytest.mark.parametrize("name", ["short_300x500_C5", "e18_shape_2000x9000_C20", "long_rows_150x6000_C3",
+                                  "long_cols_5000x40_C10", "binary_3000x800_C2", "single_row_1x50_C4"])
+def test_local_newton(cache, name):
+    w, gp, op = setup_case(cache, name)
+    T, K = 3, 5
+    params = nadmm.make_params(T, K, w.max_ls, 0.0, 0.0, w.beta, w.gamma)
+    X = dev(w.X0.copy())
+    st = nadmm.nadmm_local_newton(gp, X, params)
+    w2 = dataclasses.replace(w, max_cg=K)
+    X_ref, st_ref, _ = oracle_newton_following(op, w.X0, w2, st["alpha"], max_newton=T)
+    assert st["newton_iters"] == st_ref["newton_iters"] == T
+    assert st["cg_iters_total"] == st_ref["cg_iters_total"]
+    assert st["alpha"] == pytest.approx([it["alpha"] for it in st_ref["iters"]], rel=1e-6)
+    assert rel_l2(host(X), X_ref) <= TOL_ITERATE
+    assert rel_abs(st["loss_final"], st_ref["loss_final"]) <= TOL_PRIMITIVE
+
+
+def test_admm_on_sparse_shards():
+    w = workloads.sparse_generic(1200, 400, 4, 25, seed=41)
+    N, lam = 3, 1e-3
+    rhos = [0.5, 1.0, 2.0]
+    bounds = np.linspace(0, w.n, N + 1).astype(int)
+    s = 1.0 / w.n
+    gps, ops = [], []
+    for i in range(N):
+        A = w.A[bounds[i]:bounds[i + 1]]
+        b = w.b[bounds[i]:bounds[i + 1]]
+        gps.append(nadmm.Problem(nadmm.SparseA.from_scipy(A, A.tocsc()), dev(b), w.C, s, 0.0, rhos[i], None, None))
+        ops.append(orc.Problem(A, b, w.C, s=s))
+    local = nadmm.make_params(2, 5, 10, 0.0, 0.0, 1e-4, 0.5)
+    params = nadmm.make_admm_params(3, local)
+    x = torch.zeros((N,) + w.X0.shape, dtype=torch.float32, device="cuda")
+    z, u, st = nadmm.nadmm_admm_solve(gps, lam, x, params)
+    z_ref, xs_ref, ys_ref, hist = adm.admm(ops, lam, rhos, np.zeros_like(w.X0), 3, 2, 5, 0.0, 0.0, 1e-4, 0.5, 10)
+    assert st["outer_iters"] == 3
+    assert rel_l2(host(z), z_ref) <= TOL_ITERATE
+    for i in range(N):
+        assert rel_l2(host(x)[i], xs_ref[i]) <= TOL_ITERATE
+    assert st["r_norm"] == pytest.approx(hist[-1]["r_norm"], rel=5e-3)
