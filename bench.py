@@ -37,7 +37,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="image_like")
     ap.add_argument("--n", type=int, default=None, help="override the number of rows (testing only)")
-    ap.add_argument("--path", type=int, default=0, help="kernel path: 0 auto, 1 two-pass, 2 fused, 3 thin, 4 column-sliced")
+    ap.add_argument("--path", type=int, default=0,
+                    help="kernel path: 0 auto, 1 two-pass, 2 fused, 3 thin, 4 column-sliced, 5 sparse storage")
     ap.add_argument("--admm-workers", type=int, default=4,
                     help="simulated ADMM workers for the outer-iteration timing in extra (0 or 1: skip)")
     ap.add_argument("--admm-outer", type=int, default=2, help="outer iterations timed for that figure")
@@ -74,8 +75,8 @@ def cpu_baseline(w, seconds):
     threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
     avail = len(os.sched_getaffinity(0))
     return {"value": reps / el, "unit": "Hv/s", "cores": min(threads, avail), "kind": "oracle",
-            "sample": f"{reps} float64 numpy Hessian-vector products at the full workload shape "
-                      f"({w.n}x{w.p}, C={w.C}) in {el:.1f} s"}
+            "sample": f"{reps} float64 numpy{'/scipy.sparse' if w.sparse else ''} Hessian-vector products at the "
+                      f"full workload shape ({w.n}x{w.p}, C={w.C}) in {el:.1f} s"}
 
 
 def main():
@@ -135,9 +136,10 @@ def main():
         return t
 
     if args.copy_calibration:
-        dst = torch.empty_like(gp.A)
+        src = gp.A.tensors[2] if w.sparse else gp.A       # sparse storage: the value array of the row view
+        dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(gp.A)
+            dst.copy_(src)
         torch.cuda.synchronize()
         del dst
 
@@ -154,7 +156,7 @@ def main():
     # Outside the timed steps: matrices that fit the 256 MB Infinity Cache are also timed with two
     # independent copies of A used in turn, so that every call has to read its A from HBM.
     cold_hv_us = None
-    if do("hv") and recs and not args.no_extras and gp.A.numel() * 4 < 256e6:
+    if do("hv") and recs and not args.no_extras and not w.sparse and gp.A.numel() * 4 < 256e6:
         gp2 = nadmm.Problem(gp.A.clone(), gp.labels, w.C, w.s, w.lam, w.rho, gp.z, gp.y)
         pair = (gp, gp2)
         for i in range(8):
@@ -175,8 +177,12 @@ def main():
     if args.admm_workers > 1 and not only and not args.no_extras:
         N = args.admm_workers
         bounds = [w.n * i // N for i in range(N + 1)]
-        shards = [nadmm.Problem(gp.A[bounds[i]:bounds[i + 1]], gp.labels[bounds[i]:bounds[i + 1]], w.C, w.s, 0.0, w.rho)
-                  for i in range(N)]
+        if w.sparse:
+            rows = [w.A[bounds[i]:bounds[i + 1]] for i in range(N)]
+            mats = [nadmm.SparseA.from_scipy(r, r.tocsc()) for r in rows]
+        else:
+            mats = [gp.A[bounds[i]:bounds[i + 1]] for i in range(N)]
+        shards = [nadmm.Problem(mats[i], gp.labels[bounds[i]:bounds[i + 1]], w.C, w.s, 0.0, w.rho) for i in range(N)]
         ap = nadmm.make_admm_params(args.admm_outer, params)
         aws = torch.empty(nadmm.nadmm_admm_workspace_bytes(shards, ap), dtype=torch.uint8, device="cuda")
         xw = torch.stack([X] * N).contiguous()
@@ -203,10 +209,17 @@ def main():
 
     n, p, NC = w.n, w.p, w.C - 1
     d = p * NC
-    bytes_hv = 4.0 * n * p + 3 * 4.0 * d
-    bytes_lg = 4.0 * n * p + 4.0 * n + 4 * 4.0 * d
+    # algorithmic bytes: one read of A (sparse storage: the values and column indices of the row view and its
+    # row pointers, once) plus the vectors in and out
+    bytes_A = (8.0 * w.A.nnz + 8.0 * (n + 1)) if w.sparse else 4.0 * n * p
+    entries = float(w.A.nnz) if w.sparse else float(n) * p
+    bytes_hv = bytes_A + 3 * 4.0 * d
+    bytes_lg = bytes_A + 4.0 * n + 4 * 4.0 * d
     extra = {"kernel_path": {1: "two-pass fp32 vector kernels", 2: "fused single pass (matrix cores)",
-                             3: "thin-data single pass", 4: "column-sliced two sweeps (matrix cores)"}[path]}
+                             3: "thin-data single pass", 4: "column-sliced two sweeps (matrix cores)",
+                             5: "sparse storage: row view, then column view"}[path]}
+    if w.sparse:
+        extra["stored_entries"] = int(w.A.nnz)
     value = None
     roof = None
     if "hv" in tot:
@@ -218,7 +231,7 @@ def main():
                 "kernel": "Hessian-vector product (all kernels of one nadmm_hessvec call)",
                 "us_per_launch": per_hv_s * 1e6, "algorithmic_bytes": bytes_hv}
         extra["hv_us"] = per_hv_s * 1e6
-        flops = 4.0 * n * p * NC  # useful flops of one Hessian-vector product (the logits A X are overhead)
+        flops = 4.0 * entries * NC  # useful flops of one Hessian-vector product (the logits A X are overhead)
         extra["hv_tflops_useful"] = flops / per_hv_s / 1e12
         extra["hv_frac_fp32_vector_peak"] = flops / per_hv_s / 1e12 / 157.3
         if cold_hv_us is not None:
@@ -234,7 +247,7 @@ def main():
         passes = w.max_newton * (w.max_cg + 2)
         extra["local_solve_seconds"] = per_solve_s
         extra["local_solve_passes_over_A"] = passes
-        extra["local_solve_hbm_frac"] = passes * 4.0 * n * p / per_solve_s / 1e9 / HBM_PEAK_GBS
+        extra["local_solve_hbm_frac"] = passes * bytes_A / per_solve_s / 1e9 / HBM_PEAK_GBS
 
     if admm is not None:
         extra["admm"] = admm

@@ -476,6 +476,7 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     lt.X_apply = d_X;
     lt.iter = t;
     lt.flag = &ds->newton_active;
+    lt.qpart = at<double>(d_ws, L.dotpart);
     NADMM_HIP(launch_ls_tail(lt, st));
   }
 
@@ -713,6 +714,7 @@ int nadmm_line_search(const nadmm_problem* prob, const float* d_X, const float* 
   lt.loss_new_out = d_loss_new;
   lt.ok_out = d_armijo_ok;
   lt.iter = -1;
+  lt.qpart = at<double>(d_ws, L.dotpart);
   NADMM_HIP(launch_ls_tail(lt, st));
   return NADMM_OK;
 }

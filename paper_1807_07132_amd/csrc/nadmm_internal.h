@@ -231,6 +231,8 @@ struct LsTailArgs {
   int32_t* ok_out;
   int32_t iter;           // Newton iteration index or -1
   const int32_t* flag;
+  double* qpart;          // scratch of 2 reduce_out_blocks(d) doubles (long vectors: the sums over d are formed by
+                          // several workgroups and pass through it); NULL = single-workgroup form at any length
 };
 hipError_t launch_ls_tail(const LsTailArgs& a, hipStream_t st);
 

@@ -94,6 +94,74 @@ __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
   }
 }
 
+// The same reduction for long vectors (d > kWideFrom: sparse data with hundreds of thousands of features),
+// where there are few partials per element and many elements: a workgroup covers kWideChunk consecutive
+// elements, 8 per thread with all loads of a partial in flight together, and adds the partials in order.
+constexpr int64_t kWideFrom = (int64_t)1 << 18;
+constexpr int kWidePer = 8;
+constexpr int kWideChunk = 256 * kWidePer;
+
+__global__ __launch_bounds__(256) void reduce_out_wide_kernel(const ReduceArgs a) {
+  if (a.flag != nullptr && *a.flag == 0) return;
+  __shared__ double sm[17];
+  const int64_t base = (int64_t)blockIdx.x * kWideChunk + threadIdx.x;
+  float sum[kWidePer];
+#pragma unroll
+  for (int u = 0; u < kWidePer; ++u) sum[u] = 0.f;
+  for (int k = 0; k < a.nparts; ++k) {
+    const float* __restrict__ pp = a.partial + (size_t)k * a.d;
+    float v[kWidePer];
+#pragma unroll
+    for (int u = 0; u < kWidePer; ++u) {
+      const int64_t e = base + u * 256;
+      v[u] = e < a.d ? pp[e] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < kWidePer; ++u) sum[u] += v[u];
+  }
+  float xv[kWidePer], zv[kWidePer], yv[kWidePer];
+#pragma unroll
+  for (int u = 0; u < kWidePer; ++u) {
+    const int64_t e = base + u * 256;
+    const bool ok = e < a.d;
+    xv[u] = ok ? (a.kind == 0 ? a.V[e] : a.X[e]) : 0.f;
+    zv[u] = (ok && a.kind != 0 && a.z) ? a.z[e] : 0.f;
+    yv[u] = (ok && a.kind != 0 && a.y) ? a.y[e] : 0.f;
+  }
+  double prod = 0.0, pen = 0.0;
+#pragma unroll
+  for (int u = 0; u < kWidePer; ++u) {
+    const int64_t e = base + u * 256;
+    if (e >= a.d) continue;
+    float out = a.scale * sum[u];
+    if (a.kind == 0) {
+      out = fmaf(a.lambda + a.rho, xv[u], out);
+      prod += (double)out * (double)xv[u];
+    } else {
+      const float x = xv[u];
+      out += a.lambda * x + a.rho * (x - zv[u]) + yv[u];
+      const double xd = x, uu = xd - (double)zv[u] + (double)yv[u] / (double)a.rho;
+      pen += 0.5 * (double)a.lambda * xd * xd + 0.5 * (double)a.rho * uu * uu;
+      prod += (double)out * (double)out;
+      if (a.cg_p != nullptr) {
+        a.cg_p[e] = 0.f;
+        a.cg_r[e] = -out;
+        a.cg_d[e] = -out;
+      }
+    }
+    a.out[e] = out;
+  }
+  double* first = a.kind == 0 ? a.dot_part : a.gg_part;
+  if (first != nullptr) {
+    prod = block_sum(prod, sm);
+    if (threadIdx.x == 0) first[blockIdx.x] = prod;
+  }
+  if (a.kind != 0 && a.pen_part != nullptr) {
+    pen = block_sum(pen, sm);
+    if (threadIdx.x == 0) a.pen_part[blockIdx.x] = pen;
+  }
+}
+
 // The single-workgroup tail kernels walk vectors of d elements.  Loads go out in blocks of kBlk per
 // vector and thread before any of them is used, so that a pass costs a few memory round trips
 // instead of one per element and thread.
@@ -507,8 +575,72 @@ __global__ __launch_bounds__(256) void ls_eval_kernel(const LsEvalArgs a) {
   }
 }
 
-// Algorithm 2 on the candidate objective values; optionally applies X += alpha p.
-__global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a) {
+// Long vectors (d > kWideFrom): the sums over d that the line search needs, per workgroup, and the update
+// X += alpha p as kernels of their own around the single-workgroup decision kernel below.
+// qpart: [4][nq] partial sums of the penalty coefficients q0, q1, q2 and of the slope <p, g>.
+__global__ __launch_bounds__(256) void ls_vec_part_kernel(const LsTailArgs a, int nq) {
+  if (a.flag != nullptr && *a.flag == 0) return;
+  __shared__ double sm[17];
+  double q0 = 0.0, q1 = 0.0, q2 = 0.0, sl = 0.0;
+  const double inv_rho = 1.0 / (double)a.rho;
+  for (int64_t base = (int64_t)blockIdx.x * kWideChunk + threadIdx.x; base < a.d; base += (int64_t)gridDim.x * kWideChunk) {
+    float xv[kWidePer], zv[kWidePer], yv[kWidePer], pvv[kWidePer], gv[kWidePer];
+#pragma unroll
+    for (int u = 0; u < kWidePer; ++u) {
+      const int64_t e = base + u * 256;
+      const bool ok = e < a.d;
+      xv[u] = ok ? a.X[e] : 0.f;
+      zv[u] = (ok && a.z) ? a.z[e] : 0.f;
+      yv[u] = (ok && a.y) ? a.y[e] : 0.f;
+      pvv[u] = ok ? a.pdir[e] : 0.f;
+      gv[u] = ok ? a.g[e] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < kWidePer; ++u) {  // the padding (all zero) adds nothing
+      const double x = xv[u];
+      const double uu = x - (double)zv[u] + (double)yv[u] * inv_rho;
+      const double pv = pvv[u];
+      q0 += 0.5 * (double)a.lambda * x * x + 0.5 * (double)a.rho * uu * uu;
+      q1 += (double)a.lambda * x * pv + (double)a.rho * uu * pv;
+      q2 += 0.5 * ((double)a.lambda + (double)a.rho) * pv * pv;
+      sl += pv * (double)gv[u];
+    }
+  }
+  q0 = block_sum(q0, sm);
+  q1 = block_sum(q1, sm);
+  q2 = block_sum(q2, sm);
+  sl = block_sum(sl, sm);
+  if (threadIdx.x == 0) {
+    a.qpart[blockIdx.x] = q0;
+    a.qpart[nq + blockIdx.x] = q1;
+    a.qpart[2 * nq + blockIdx.x] = q2;
+    a.qpart[3 * nq + blockIdx.x] = sl;
+  }
+}
+
+__global__ __launch_bounds__(256) void ls_apply_kernel(const DevState* st, const float* __restrict__ pdir,
+                                                       float* __restrict__ X, int64_t d, const int32_t* flag) {
+  if (flag != nullptr && *flag == 0) return;
+  const float alpha = st->alpha;
+  for (int64_t base = (int64_t)blockIdx.x * kWideChunk + threadIdx.x; base < d; base += (int64_t)gridDim.x * kWideChunk) {
+    float pv[kWidePer], xv[kWidePer];
+#pragma unroll
+    for (int u = 0; u < kWidePer; ++u) {
+      const int64_t e = base + u * 256;
+      pv[u] = e < d ? pdir[e] : 0.f;
+      xv[u] = e < d ? X[e] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < kWidePer; ++u) {
+      const int64_t e = base + u * 256;
+      if (e < d) X[e] = fmaf(alpha, pv[u], xv[u]);
+    }
+  }
+}
+
+// Algorithm 2 on the candidate objective values; optionally applies X += alpha p.  nq > 0: the sums
+// over d come as partial sums from ls_vec_part_kernel and X is updated by ls_apply_kernel.
+__global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a, int nq) {
   __shared__ double sm[17];
   __shared__ double cand[kCandSlots];
   __shared__ float s_alpha;
@@ -535,7 +667,7 @@ __global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a) {
   // penalty along the line: q0 + alpha q1 + alpha^2 q2, and the slope <p, g>
   double q0 = 0.0, q1 = 0.0, q2 = 0.0, sl = 0.0;
   const double inv_rho = 1.0 / (double)a.rho;
-  for (int64_t e0 = threadIdx.x; e0 < a.d; e0 += (int64_t)kBlk * blockDim.x) {
+  for (int64_t e0 = threadIdx.x; nq == 0 && e0 < a.d; e0 += (int64_t)kBlk * blockDim.x) {
     float xv[kBlk], zv[kBlk], yv[kBlk], pvv[kBlk], gv[kBlk];
 #pragma unroll
     for (int u = 0; u < kBlk; ++u) {
@@ -558,10 +690,17 @@ __global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a) {
       sl += pv * (double)gv[u];
     }
   }
-  q0 = block_sum(q0, sm);
-  q1 = block_sum(q1, sm);
-  q2 = block_sum(q2, sm);
-  sl = block_sum(sl, sm);
+  if (nq > 0) {
+    q0 = partial_sum_block(a.qpart, nq, sm);
+    q1 = partial_sum_block(a.qpart + nq, nq, sm);
+    q2 = partial_sum_block(a.qpart + 2 * nq, nq, sm);
+    sl = partial_sum_block(a.qpart + 3 * nq, nq, sm);
+  } else {
+    q0 = block_sum(q0, sm);
+    q1 = block_sum(q1, sm);
+    q2 = block_sum(q2, sm);
+    sl = block_sum(sl, sm);
+  }
 
   if (threadIdx.x == 0) {
     double f0;
@@ -597,7 +736,7 @@ __global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a) {
     }
   }
   __syncthreads();
-  if (a.X_apply != nullptr) {
+  if (a.X_apply != nullptr && nq == 0) {
     const float alpha = s_alpha;
     for (int64_t e0 = threadIdx.x; e0 < a.d; e0 += (int64_t)kBlk * blockDim.x) {
       float pvv[kBlk], xv[kBlk];
@@ -629,11 +768,14 @@ hipError_t dispatch_ncp(int NC, F&& f) {
 
 }  // namespace
 
-int reduce_out_blocks(int64_t d) { return (int)((d + 31) / 32); }
+int reduce_out_blocks(int64_t d) {
+  return d > kWideFrom ? (int)((d + kWideChunk - 1) / kWideChunk) : (int)((d + 31) / 32);
+}
 
 hipError_t launch_reduce_out(const ReduceArgs& a, hipStream_t st) {
   const int blocks = reduce_out_blocks(a.d);
-  hipLaunchKernelGGL(reduce_out_kernel, dim3(blocks), dim3(256), 0, st, a);
+  if (a.d > kWideFrom) hipLaunchKernelGGL(reduce_out_wide_kernel, dim3(blocks), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL(reduce_out_kernel, dim3(blocks), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
@@ -654,7 +796,7 @@ hipError_t launch_newton_head(const NewtonHeadArgs& a, hipStream_t st) {
 
 int cg_update_blocks(int64_t d) {
   int64_t b = (d + kCgChunk - 1) / kCgChunk;
-  return (int)(b < 64 ? b : 64);
+  return (int)(b < 1024 ? b : 1024);
 }
 
 hipError_t launch_cg_update(const CgUpdateArgs& a, hipStream_t st) {
@@ -704,8 +846,18 @@ hipError_t launch_ls_eval(const LsEvalArgs& a, hipStream_t st) {
   });
 }
 
+int ls_tail_parts(int64_t d) {
+  if (d <= kWideFrom) return 0;
+  const int b = reduce_out_blocks(d) / 2;  // 4 sums per part fit the 2 reduce_out_blocks(d) doubles of the dot-product partials
+  return b < 256 ? b : 256;
+}
+
 hipError_t launch_ls_tail(const LsTailArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(ls_tail_kernel, dim3(1), dim3(kTail), 0, st, a);
+  const int nq = a.qpart != nullptr ? ls_tail_parts(a.d) : 0;
+  if (nq > 0) hipLaunchKernelGGL(ls_vec_part_kernel, dim3(nq), dim3(256), 0, st, a, nq);
+  hipLaunchKernelGGL(ls_tail_kernel, dim3(1), dim3(kTail), 0, st, a, nq);
+  if (nq > 0 && a.X_apply != nullptr)
+    hipLaunchKernelGGL(ls_apply_kernel, dim3(nq), dim3(256), 0, st, (const DevState*)a.st, a.pdir, a.X_apply, a.d, a.flag);
   return hipGetLastError();
 }
 

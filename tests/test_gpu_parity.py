@@ -61,6 +61,8 @@ CASES = {
     "sliced_33x1604_C33": lambda: workloads.generic(33, 1604, 33, seed=26, x_std=0.03),
     "sliced_300x36_C33": lambda: workloads.generic(300, 36, 33, seed=27, x_std=0.2),    # 32 free classes: two full class blocks
     "sliced_200x964_C3": lambda: workloads.generic(200, 964, 3, seed=28, x_std=0.05),  # one step past the fused kernel's limit
+    # d = p (C-1) = 280000: the long-vector forms of the reduction, the CG update and the line-search tail
+    "long_vectors_40x70000_C5": lambda: workloads.generic(40, 70000, 5, seed=29, x_std=0.01, mean=True),
 }
 
 # 1 = two-pass vector kernels forced, 2 = fused matrix-core kernel forced, 4 = column-sliced two-sweep path forced,
@@ -134,7 +136,7 @@ def test_hessvec(cache, name, path):
 @pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("name", ["tiny", "image_like_3k", "tall_binary_50k", "ragged_1237x45_C5", "ragged_333x130_C12",
                                   "fused_2000x100_C7", "fused_130x960_C4", "thin_5000x4_C2", "thin_256x8_C2", "sliced_1500x1100_C4",
-                                  "sliced_33x1604_C33", "wide_700"])
+                                  "sliced_33x1604_C33", "wide_700", "long_vectors_40x70000_C5"])
 def test_cg_fixed_iterations(cache, name, path):
     w, gp, op = setup_case(cache, name)
     force_path(gp, path)
@@ -174,7 +176,7 @@ def test_cg_tolerance_mode(cache, name):
 
 @pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("name", ["tiny", "image_like_3k", "tall_binary_50k", "ragged_517x65_C3", "fused_8200x64_C2",
-                                  "thin_70001x32_C3", "sliced_3000x100_C26"])
+                                  "thin_70001x32_C3", "sliced_3000x100_C26", "long_vectors_40x70000_C5"])
 def test_line_search(cache, name, path):
     w, gp, op = setup_case(cache, name)
     force_path(gp, path)
@@ -193,7 +195,7 @@ def test_line_search(cache, name, path):
 
 NEWTON_CASES = ["tiny", "image_like_3k", "wide_700", "tall_binary_50k", "large_multiclass_900", "ragged_1237x45_C5",
                 "single_row_1x7_C4", "fused_9001x260_C10", "fused_4100x36_C17", "thin_70001x32_C3", "thin_300x12_C4", "sliced_3000x100_C26",
-                "sliced_1500x1100_C4"]
+                "sliced_1500x1100_C4", "long_vectors_40x70000_C5"]
 
 
 @pytest.mark.parametrize("path", PATHS)

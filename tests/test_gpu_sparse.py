@@ -43,6 +43,8 @@ CASES = {
     "long_cols_5000x40_C10": lambda: workloads.sparse_generic(5000, 40, 10, 20, seed=7),
     "binary_3000x800_C2": lambda: workloads.sparse_generic(3000, 800, 2, 30, seed=8),
     "max_classes_400x700_C33": lambda: workloads.sparse_generic(400, 700, 33, 25, seed=9, x_std=0.1),
+    # d = p (C-1) = 270000: the long-vector forms of the reduction, the CG update and the line-search tail
+    "long_vectors_500x90000_C4": lambda: workloads.sparse_generic(500, 90000, 4, 60, seed=12, x_std=0.1),
     "single_row_1x50_C4": lambda: workloads.sparse_generic(1, 50, 4, 9, seed=10),
     "single_column_300x1_C3": lambda: workloads.sparse_generic(300, 1, 3, 1, seed=11),
 }
@@ -171,7 +173,7 @@ def test_empty_matrix():
 
 
 @pytest.mark.parametrize("name", ["short_300x500_C5", "e18_shape_2000x9000_C20", "long_rows_150x6000_C3",
-                                  "long_cols_5000x40_C10"])
+                                  "long_cols_5000x40_C10", "long_vectors_500x90000_C4"])
 def test_cg_fixed_iterations(cache, name):
     w, gp, op = setup_case(cache, name)
     X = x_for(w)
@@ -187,7 +189,8 @@ def test_cg_fixed_iterations(cache, name):
             assert relres.item() < 1e-5
 
 
-@pytest.mark.parametrize("name", ["short_300x500_C5", "long_cols_5000x40_C10", "binary_3000x800_C2"])
+@pytest.mark.parametrize("name", ["short_300x500_C5", "long_cols_5000x40_C10", "binary_3000x800_C2",
+                                  "long_vectors_500x90000_C4"])
 def test_line_search(cache, name):
     w, gp, op = setup_case(cache, name)
     X = x_for(w)
@@ -204,7 +207,8 @@ def test_line_search(cache, name):
 
 
 @pytest.mark.parametrize("name", ["short_300x500_C5", "e18_shape_2000x9000_C20", "long_rows_150x6000_C3",
-                                  "long_cols_5000x40_C10", "binary_3000x800_C2", "single_row_1x50_C4"])
+                                  "long_cols_5000x40_C10", "binary_3000x800_C2", "single_row_1x50_C4",
+                                  "long_vectors_500x90000_C4"])
 def test_local_newton(cache, name):
     w, gp, op = setup_case(cache, name)
     T, K = 3, 5
