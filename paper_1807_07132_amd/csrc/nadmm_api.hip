@@ -103,7 +103,7 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   L->win_cols = off;
   L->nwin_rows = L->nwin_cols = 0;
   if (L->sparse) {
-    const size_t npad = (size_t)sparse_pad(s.NC);
+    const size_t npad = (size_t)4 * sparse_group(s.NC);
     const size_t a = (size_t)s.p * 2 * npad, b = (size_t)s.n * npad;  // [X | V] or D, rows padded
     off += align256((a > b ? a : b) * sizeof(float));
     L->nwin_rows = sparse_windows(s.n, p->sparse->nnz);
@@ -194,7 +194,7 @@ int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArg
   if (path == 5) {
     SpmmArgs sa;
     sa.NC = L.s.NC;
-    sa.NCpad = sparse_pad(L.s.NC);
+    sa.nq = (L.s.NC + 3) / 4;
     sa.flag = ra.flag;
     sa.B = at<float>(ws, L.pack);
     if (ra.B0 != nullptr || ra.B1 != nullptr) {  // [Z | W] = A [X | V]

@@ -294,21 +294,21 @@ struct SparseView {
   int32_t ncols;
   int64_t nnz;
 };
-// out = S B for a packed dense operand B: ncols rows of nops blocks of NCpad floats (NCpad = sparse_pad(NC), the
-// padding is zero); out: nrows x nops x NC (no padding)
+// out = S B for a packed dense operand B: ncols rows of nops blocks of 4 sparse_group(NC) floats (zero
+// padded); out: nrows x nops x NC (no padding)
 struct SpmmArgs {
   SparseView S;
   const float* B;
   float* out;
-  int32_t NC, NCpad, nops;
+  int32_t NC, nq, nops;  // nq = ceil(NC / 4) quads of a block hold data
   const int32_t* win;  // first row of each window of equal cost, nwin + 1 entries (launch_sparse_plan)
   int32_t nwin;
   const int32_t* flag;
 };
-int sparse_pad(int NC);
+int sparse_group(int NC);
 int sparse_windows(int64_t nrows, int64_t nnz);
 hipError_t launch_sparse_plan(const SparseView& S, int32_t* win, int nwin, hipStream_t st);
-// dst[r] = [src0[r] | src1[r]] with every block padded to sparse_pad(NC) floats; one of src0, src1 may be NULL
+// dst[r] = [src0[r] | src1[r]] with every block padded to 4 sparse_group(NC) floats; one of src0, src1 may be NULL
 hipError_t launch_sparse_pack(const float* src0, const float* src1, int64_t rows, int NC, float* dst,
                               const int32_t* flag, hipStream_t st);
 hipError_t launch_spmm(const SpmmArgs& a, hipStream_t st);

@@ -1,8 +1,10 @@
-"""GPU parity at the full sizes of the five benchmark workloads, in the launch configuration
-bench.py times (automatic kernel path, default stream, library workspace).
+"""GPU parity at the full sizes of the benchmark workloads (the five dense ones and the sparse one
+shaped like E18), in the launch configuration bench.py times (automatic kernel path, default
+stream, library workspace).
 
-d = p (C-1) is at most 38000, so the float64 oracle computes every output element (no sampling
-needed); the oracle's cost is one or two dense products per call.  The Newton iteration is
+The float64 oracle computes every output element (no sampling needed): d = p (C-1) is at most
+38000 for the dense workloads, whose oracle cost is one or two dense products per call, and the
+sparse workload's products with A are scipy's sparse ones (a few seconds each).  The Newton iteration is
 compared after a reduced number of iterations where the full budget would take the CPU minutes.
 """
 import dataclasses
@@ -25,6 +27,7 @@ FULL = {
     "wide": (4, 2, 10),
     "tall_binary": (3, 3, 10),
     "large_multiclass": (4, 1, 5),
+    "e18_like": (5, 1, 3),
 }
 
 
