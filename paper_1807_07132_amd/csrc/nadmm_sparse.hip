@@ -6,9 +6,9 @@
 //
 // The rows of B are first copied into a buffer in which every row takes a power-of-two number G of
 // 16-byte quads (zero padded), so that a row lies in one 128-byte cache line.  A wave reads 64 (index,
-// value) pairs with two coalesced loads and hands them out by lane shuffles; G neighbouring lanes then
-// share an entry, each loading one quad of the row of B that the entry points to, so that a load
-// instruction touches 64 / G rows once each, and each lane keeps the partial sums of its quad; at the
+// value) pairs with two coalesced loads and hands them out by lane shuffles; as many neighbouring lanes
+// as a row of B has quads then share an entry, each loading one quad of the row that the entry points to,
+// so that a load instruction touches each of its rows once, and each lane keeps the partial sums of its quad; at the
 // end of a row of S the lanes holding the same quad are added across the wave.  Work is cut into
 // windows of equal cost (stored entries plus a fixed cost per row) by a binary search over the row
 // pointers; a workgroup owns the rows that start in its window: short rows go to single waves, long
@@ -75,15 +75,15 @@ __device__ __forceinline__ RowSpan row_span(const SparseView& S, int64_t r) {
   return RowSpan{k0, k1};
 }
 
-// 64 stored entries from kb on, one per lane (value 0 and a valid index beyond k1)
+// the stored entries of a chunk from kb on, one per lane (value 0 and a valid index beyond the end)
 struct Chunk {
   int col;
   float v;
 };
-__device__ __forceinline__ Chunk fetch_chunk(const SparseView& S, int64_t kb, int64_t k1, int lane) {
+__device__ __forceinline__ Chunk fetch_chunk(const SparseView& S, int64_t kb, int64_t k1, int64_t kend, int lane) {
   const int64_t k = kb + lane;
-  const bool ok = k < k1;
-  const int64_t kc = ok ? k : k1 - 1;
+  const bool ok = k < kend;  // kend = k1, or 0 in lanes that never hold an entry
+  const int64_t kc = k < k1 ? k : k1 - 1;
   const int c = S.idx[kc];
   Chunk ch;
   ch.v = ok ? S.val[kc] : 0.f;
@@ -91,39 +91,49 @@ __device__ __forceinline__ Chunk fetch_chunk(const SparseView& S, int64_t kb, in
   return ch;
 }
 
+// Lanes per wave that hold entries, for rows of NQ quads: S = 64 / NQ entries share a load instruction
+// (lane = s NQ + q reads quad q of the B row of entry s), a chunk is T = 64 / S such groups.
+template <int NQ>
+struct Shape64 {
+  static constexpr int S = 64 / NQ;
+  static constexpr int T = 64 / S;
+  static constexpr int CE = S * T;  // entries per chunk: 64, or a little less where NQ does not divide 64
+};
+
 // The sum of value * (row of B) over the entries of the chunks kb0, kb0 + stride, ... of [.., k1).
-// G lanes share an entry: lane (s, q) = (lane / G, lane % G) reads quad q of the B row of entry s of each
-// group of 64 / G entries, so that one load instruction touches every row once (several loads of one lane
-// to one cache line would wait on each other in the vector L1).  Returns, in every lane, the sums of its
-// quad q over the whole wave.
-template <int G, int NOPS>
+// NQ neighbouring lanes share an entry, one quad of its B row each, so that one load instruction touches
+// every row once (several loads of one lane to one cache line would wait on each other in the vector
+// L1).  Returns, in lanes 0 .. NQ-1, the sums of quad q = lane over the whole wave.
+template <int NQ, int NOPS>
 __device__ __forceinline__ void row_sum(const SpmmArgs& a, int64_t kb0, int64_t k1, int stride, int lane,
                                         mfma_detail::f32x4 (&acc)[NOPS]) {
   using mfma_detail::f32x4;
-  constexpr int S = 64 / G;  // entries per load instruction
-  const int s = lane / G, q = lane % G;
-  const bool qok = q < a.nq;
+  constexpr int S = Shape64<NQ>::S, T = Shape64<NQ>::T, CE = Shape64<NQ>::CE;
+  constexpr int G = NQ <= 1 ? 1 : (NQ <= 2 ? 2 : (NQ <= 4 ? 4 : 8));  // quads per row slot of B
+  const int s = lane / NQ, q = lane - s * NQ;
+  const bool active = lane < S * NQ;
   const f32x4* __restrict__ Bq = reinterpret_cast<const f32x4*>(a.B) + q;
 #pragma unroll
   for (int op = 0; op < NOPS; ++op) acc[op] = f32x4{0.f, 0.f, 0.f, 0.f};
   if (kb0 >= k1) return;
-  Chunk cur = fetch_chunk(a.S, kb0, k1, lane);
+  const int64_t kend = (lane < CE) ? k1 : 0;  // lanes beyond the chunk hold no entry
+  Chunk cur = fetch_chunk(a.S, kb0, k1, kend, lane);
   for (int64_t kb = kb0; kb < k1; kb += stride) {
     const int64_t left = k1 - kb;
-    const int nsub = left >= 64 ? G : (int)((left + S - 1) / S);
-    f32x4 b[G][NOPS];
-    float vv[G];
+    const int nsub = left >= CE ? T : (int)((left + S - 1) / S);
+    f32x4 b[T][NOPS];
+    float vv[T];
 #pragma unroll
-    for (int t = 0; t < G; ++t) {
+    for (int t = 0; t < T; ++t) {
       const int c = __shfl(cur.col, t * S + s, 64);
       vv[t] = __shfl(cur.v, t * S + s, 64);
       const f32x4* __restrict__ row = Bq + (size_t)c * (NOPS * G);
 #pragma unroll
-      for (int op = 0; op < NOPS; ++op) b[t][op] = (t < nsub && qok) ? row[op * G] : f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int op = 0; op < NOPS; ++op) b[t][op] = (t < nsub && active) ? row[op * G] : f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    if (kb + stride < k1) cur = fetch_chunk(a.S, kb + stride, k1, lane);  // in flight during the products
+    if (kb + stride < k1) cur = fetch_chunk(a.S, kb + stride, k1, kend, lane);  // in flight during the products
 #pragma unroll
-    for (int t = 0; t < G; ++t) {
+    for (int t = 0; t < T; ++t) {
 #pragma unroll
       for (int op = 0; op < NOPS; ++op) {
 #pragma unroll
@@ -131,18 +141,29 @@ __device__ __forceinline__ void row_sum(const SpmmArgs& a, int64_t kb0, int64_t 
       }
     }
   }
+  // add the S lanes of each quad: halving tree over s, fixed order
+  int cnt = S;
 #pragma unroll
-  for (int off = G; off < 64; off <<= 1) {
+  for (int h = 32; h >= 1; h >>= 1) {
+    if (h < cnt) {
+      const bool take = s + h < cnt;
 #pragma unroll
-    for (int op = 0; op < NOPS; ++op) {
+      for (int op = 0; op < NOPS; ++op) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) acc[op][e] += __shfl_xor(acc[op][e], off, 64);
+        for (int e = 0; e < 4; ++e) {
+          const float o = __shfl_down(acc[op][e], h * NQ, 64);
+          acc[op][e] += take ? o : 0.f;
+        }
+      }
+      cnt = h;
     }
   }
 }
 
-template <int G, int NOPS>
+template <int NQ, int NOPS>
 __global__ __launch_bounds__(kSpThreads) void spmm_kernel(const SpmmArgs a) {
+  constexpr int G = 8;  // bound of NQ, for the LDS staging of long rows
+  constexpr int CE = Shape64<NQ>::CE;
   using mfma_detail::f32x4;
   if (a.flag != nullptr && *a.flag == 0) return;
   __shared__ int long_rows[kMaxLong];
@@ -170,8 +191,8 @@ __global__ __launch_bounds__(kSpThreads) void spmm_kernel(const SpmmArgs a) {
   for (int sl = 0; sl < nlong; ++sl) {
     const RowSpan sp = row_span(a.S, long_rows[sl]);
     f32x4 acc[NOPS];
-    row_sum<G, NOPS>(a, sp.k0 + 64 * wave, sp.k1, 64 * kSpWaves, lane, acc);
-    if (lane < G) {
+    row_sum<NQ, NOPS>(a, sp.k0 + CE * wave, sp.k1, CE * kSpWaves, lane, acc);
+    if (lane < NQ) {
 #pragma unroll
       for (int op = 0; op < NOPS; ++op) {
 #pragma unroll
@@ -184,8 +205,8 @@ __global__ __launch_bounds__(kSpThreads) void spmm_kernel(const SpmmArgs a) {
     const RowSpan sp = row_span(a.S, r);
     if (sp.k1 - sp.k0 >= kLong) continue;
     f32x4 acc[NOPS];
-    row_sum<G, NOPS>(a, sp.k0, sp.k1, 64, lane, acc);
-    if (lane < G) {
+    row_sum<NQ, NOPS>(a, sp.k0, sp.k1, CE, lane, acc);
+    if (lane < NQ) {
       float* __restrict__ orow = a.out + (size_t)r * ldo;
 #pragma unroll
       for (int op = 0; op < NOPS; ++op) {
@@ -211,9 +232,9 @@ __global__ __launch_bounds__(kSpThreads) void spmm_kernel(const SpmmArgs a) {
   }
 }
 
-template <int G, int NOPS>
-hipError_t launch_g(const SpmmArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL((spmm_kernel<G, NOPS>), dim3(a.nwin), dim3(kSpThreads), 0, st, a);
+template <int NQ, int NOPS>
+hipError_t launch_q(const SpmmArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL((spmm_kernel<NQ, NOPS>), dim3(a.nwin), dim3(kSpThreads), 0, st, a);
   return hipGetLastError();
 }
 
@@ -248,17 +269,24 @@ hipError_t launch_sparse_pack(const float* src0, const float* src1, int64_t rows
 }
 
 hipError_t launch_spmm(const SpmmArgs& a, hipStream_t st) {
-  const int G = sparse_group(a.NC);
-  if (a.nq != (a.NC + 3) / 4 || a.nops < 1 || a.nops > 2) return hipErrorInvalidValue;
-  switch (G * 2 + (a.nops - 1)) {
-    case 2: return launch_g<1, 1>(a, st);
-    case 3: return launch_g<1, 2>(a, st);
-    case 4: return launch_g<2, 1>(a, st);
-    case 5: return launch_g<2, 2>(a, st);
-    case 8: return launch_g<4, 1>(a, st);
-    case 9: return launch_g<4, 2>(a, st);
-    case 16: return launch_g<8, 1>(a, st);
-    case 17: return launch_g<8, 2>(a, st);
+  if (a.nq != (a.NC + 3) / 4 || a.nq < 1 || a.nq > 8 || a.nops < 1 || a.nops > 2) return hipErrorInvalidValue;
+  switch (a.nq * 2 + (a.nops - 1)) {
+    case 2: return launch_q<1, 1>(a, st);
+    case 3: return launch_q<1, 2>(a, st);
+    case 4: return launch_q<2, 1>(a, st);
+    case 5: return launch_q<2, 2>(a, st);
+    case 6: return launch_q<3, 1>(a, st);
+    case 7: return launch_q<3, 2>(a, st);
+    case 8: return launch_q<4, 1>(a, st);
+    case 9: return launch_q<4, 2>(a, st);
+    case 10: return launch_q<5, 1>(a, st);
+    case 11: return launch_q<5, 2>(a, st);
+    case 12: return launch_q<6, 1>(a, st);
+    case 13: return launch_q<6, 2>(a, st);
+    case 14: return launch_q<7, 1>(a, st);
+    case 15: return launch_q<7, 2>(a, st);
+    case 16: return launch_q<8, 1>(a, st);
+    case 17: return launch_q<8, 2>(a, st);
     default: return hipErrorInvalidValue;
   }
 }
