@@ -198,13 +198,28 @@ int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArg
     sa.flag = ra.flag;
     sa.B = at<float>(ws, L.pack);
     if (ra.B0 != nullptr || ra.B1 != nullptr) {  // [Z | W] = A [X | V]
-      NADMM_HIP(launch_sparse_pack(ra.B0, ra.B1, prob->p, L.s.NC, at<float>(ws, L.pack), ra.flag, st));
+      const bool both = ra.B0 != nullptr && ra.B1 != nullptr;
       sa.S = row_view(prob);
       sa.out = at<float>(ws, L.zw);
-      sa.nops = (ra.B0 != nullptr && ra.B1 != nullptr) ? 2 : 1;
       sa.win = at<int32_t>(ws, L.win_rows);
       sa.nwin = L.nwin_rows;
-      NADMM_HIP(launch_spmm(sa, st));
+      sa.ldo = (both ? 2 : 1) * L.s.NC;
+      if (both && sparse_group(L.s.NC) > 4) {
+        // a row of X and a row of V do not share a 128-byte cache line: two products of one operand each
+        // fetch a line per stored entry and are faster than one product that fetches two
+        sa.nops = 1;
+        NADMM_HIP(launch_sparse_pack(ra.B0, nullptr, prob->p, L.s.NC, at<float>(ws, L.pack), ra.flag, st));
+        sa.ooff = 0;
+        NADMM_HIP(launch_spmm(sa, st));
+        NADMM_HIP(launch_sparse_pack(ra.B1, nullptr, prob->p, L.s.NC, at<float>(ws, L.pack), ra.flag, st));
+        sa.ooff = L.s.NC;
+        NADMM_HIP(launch_spmm(sa, st));
+      } else {
+        NADMM_HIP(launch_sparse_pack(ra.B0, ra.B1, prob->p, L.s.NC, at<float>(ws, L.pack), ra.flag, st));
+        sa.nops = both ? 2 : 1;
+        sa.ooff = 0;
+        NADMM_HIP(launch_spmm(sa, st));
+      }
     }
     NADMM_HIP(launch_logit_rows(ra, at<float>(ws, L.zw), 1, st));
     if (with_cols) {  // A^T D from the column view
@@ -212,6 +227,8 @@ int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArg
       sa.S = col_view(prob);
       sa.out = at<float>(ws, L.partial);
       sa.nops = 1;
+      sa.ldo = L.s.NC;
+      sa.ooff = 0;
       sa.win = at<int32_t>(ws, L.win_cols);
       sa.nwin = L.nwin_cols;
       NADMM_HIP(launch_spmm(sa, st));

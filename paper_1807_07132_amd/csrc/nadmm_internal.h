@@ -295,12 +295,13 @@ struct SparseView {
   int64_t nnz;
 };
 // out = S B for a packed dense operand B: ncols rows of nops blocks of 4 sparse_group(NC) floats (zero
-// padded); out: nrows x nops x NC (no padding)
+// padded); row r of the product goes to out[r * ldo + ooff + op * NC + c], op < nops, c < NC
 struct SpmmArgs {
   SparseView S;
   const float* B;
   float* out;
   int32_t NC, nq, nops;  // nq = ceil(NC / 4) quads of a block hold data
+  int32_t ldo, ooff;
   const int32_t* win;  // first row of each window of equal cost, nwin + 1 entries (launch_sparse_plan)
   int32_t nwin;
   const int32_t* flag;

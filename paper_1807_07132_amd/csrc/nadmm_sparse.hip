@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kSpThreads) void spmm_kernel(const SpmmArgs a) {
   if (r1 <= r0) return;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int ldo = NOPS * a.NC;
+  const int ldo = a.ldo;
 
   if (threadIdx.x == 0) nlong_sh = 0;
   __syncthreads();
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(kSpThreads) void spmm_kernel(const SpmmArgs a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int c = 4 * lane + e;
-          if (c < a.NC) orow[op * a.NC + c] = acc[op][e];
+          if (c < a.NC) orow[a.ooff + op * a.NC + c] = acc[op][e];
         }
       }
     }
@@ -228,7 +228,7 @@ __global__ __launch_bounds__(kSpThreads) void spmm_kernel(const SpmmArgs a) {
     float sum = pj[0];
 #pragma unroll
     for (int w = 1; w < kSpWaves; ++w) sum += pj[w * kPer];
-    if (c < a.NC) a.out[(size_t)long_rows[sl] * ldo + op * a.NC + c] = sum;
+    if (c < a.NC) a.out[(size_t)long_rows[sl] * ldo + a.ooff + op * a.NC + c] = sum;
   }
 }
 
@@ -269,7 +269,8 @@ hipError_t launch_sparse_pack(const float* src0, const float* src1, int64_t rows
 }
 
 hipError_t launch_spmm(const SpmmArgs& a, hipStream_t st) {
-  if (a.nq != (a.NC + 3) / 4 || a.nq < 1 || a.nq > 8 || a.nops < 1 || a.nops > 2) return hipErrorInvalidValue;
+  // two operands only where both rows share a 128-byte line (C-1 <= 16); wider ones are multiplied one by one
+  if (a.nq != (a.NC + 3) / 4 || a.nq < 1 || a.nq > 8 || a.nops < 1 || a.nops > (a.nq <= 4 ? 2 : 1)) return hipErrorInvalidValue;
   switch (a.nq * 2 + (a.nops - 1)) {
     case 2: return launch_q<1, 1>(a, st);
     case 3: return launch_q<1, 2>(a, st);
@@ -280,13 +281,9 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t st) {
     case 8: return launch_q<4, 1>(a, st);
     case 9: return launch_q<4, 2>(a, st);
     case 10: return launch_q<5, 1>(a, st);
-    case 11: return launch_q<5, 2>(a, st);
     case 12: return launch_q<6, 1>(a, st);
-    case 13: return launch_q<6, 2>(a, st);
     case 14: return launch_q<7, 1>(a, st);
-    case 15: return launch_q<7, 2>(a, st);
     case 16: return launch_q<8, 1>(a, st);
-    case 17: return launch_q<8, 2>(a, st);
     default: return hipErrorInvalidValue;
   }
 }
