@@ -27,6 +27,8 @@ MEASURED_HV_TRAFFIC = {
     ("tall_binary_1375000x28_C2", 3): 154.4e6,
     ("wide_50000x3072_C10", 4): 1286.5e6,
     ("large_multiclass_250000x2000_C20", 4): 4435.8e6,
+    # sparse storage: bytes between the L2 caches and the memory side, most of them operand rows served by the Infinity Cache
+    ("e18_like_40628x279998_C20_sparse", 5): 12480.0e6,
 }
 
 
