@@ -207,6 +207,22 @@ def main():
         torch.cuda.synchronize()
         admm = {"workers": N, "outer_iterations_timed": args.admm_outer, "seconds_per_outer_iteration": t_admm,
                 "consensus_step_us": e0.elapsed_time(e1) * 1e3 / 20}
+        if not w.sparse:
+            # outer iterations until the residual test stops the solver, from the workload's penalty: kept fixed, and
+            # adapted by residual balancing (mu = 10, tau = 2)
+            eps_abs, eps_rel, cap = 1e-4, 1e-3, 64
+            runs = {}
+            for name, rule in (("fixed_penalty", 0), ("residual_balancing", 1)):
+                apr = nadmm.make_admm_params(cap, params, eps_abs, eps_rel, penalty_rule=rule)
+                xw.copy_(torch.stack([X] * N))
+                e0, e1 = ev(), ev()
+                e0.record()
+                _, _, st = nadmm.nadmm_admm_solve(shards, w.lam, xw, apr, ws=aws)
+                e1.record()
+                torch.cuda.synchronize()
+                runs[name] = {"outer_iterations": st["outer_iters"], "stopped_by_residual_test": st["converged"],
+                              "seconds": e0.elapsed_time(e1) / 1e3, "final_penalty_factor": st["rho_scale"]}
+            admm["to_tolerance"] = {"eps_abs": eps_abs, "eps_rel": eps_rel, "max_outer": cap, **runs}
         del shards, aws, xw, uw, zw
 
     n, p, NC = w.n, w.p, w.C - 1

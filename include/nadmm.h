@@ -200,6 +200,12 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
  *   eps_pri  = sqrt(N) eps_abs + eps_rel max{ sqrt(sum_i ||x_i||^2), sqrt(N) ||z|| }
  *   eps_dual = sqrt(d) eps_abs + eps_rel sqrt(sum_i ||u_i||^2)
  * (the printed tolerances with every squared norm read as the norm).
+ *
+ * Adaptive penalty: Section 2.3 names residual balancing as the customary rule and uses a spectral rule
+ * whose formulas are in a cited work only; penalty_rule = 1 is residual balancing in its published form
+ * (Boyd et al. 2011, the paper's reference for it), applied to all workers by one common factor c on the
+ * given rho_i: after an iteration with ||r|| > mu ||d||, c <- tau c; with ||d|| > mu ||r||, c <- c / tau.
+ * The multipliers are kept unscaled, so a change of penalty leaves them as they are.
  * ------------------------------------------------------------------------------------------------ */
 #define NADMM_MAX_WORKERS 64
 
@@ -208,6 +214,9 @@ typedef struct nadmm_admm_params {
   float        eps_abs;     /* both tolerances 0: run max_outer iterations */
   float        eps_rel;
   nadmm_params local;       /* Algorithm 3, run on every worker in every iteration */
+  int32_t      penalty_rule;/* 0: the penalties rho_i stay as given; 1: residual balancing (below) */
+  float        rb_mu;       /* rule 1: imbalance that triggers a change, >= 1 (customary 10) */
+  float        rb_tau;      /* rule 1: factor of a change, > 1 (customary 2) */
 } nadmm_admm_params;
 
 typedef struct nadmm_admm_stats {
@@ -216,6 +225,8 @@ typedef struct nadmm_admm_stats {
   double  r_norm, d_norm, eps_pri, eps_dual;     /* of the last iteration */
   double  r_trace[NADMM_TRACE_LEN];              /* per iteration (first NADMM_TRACE_LEN) */
   double  d_trace[NADMM_TRACE_LEN];
+  double  rho_scale;                             /* common factor on the rho_i after the last iteration */
+  double  rho_scale_trace[NADMM_TRACE_LEN];      /* factor in force during each iteration */
 } nadmm_admm_stats;
 
 /*

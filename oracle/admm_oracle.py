@@ -29,13 +29,23 @@ compared with
     eps_dual = sqrt(d) eps_abs + eps_rel * sqrt(sum_i ||y_i||^2)
 
 i.e. the printed expressions with every squared norm replaced by the norm.
-The penalty parameters are fixed inputs (the spectral penalty selection of the
-paper is defined in a cited work only and is not part of this oracle).
+The penalty parameters are inputs.  They stay fixed, or follow residual
+balancing, which Section 2.3 names as the customary adaptive rule (the spectral
+selection that the paper itself uses is defined in a cited work only and is not
+part of this oracle).  The paper gives no formula for residual balancing; the
+rule below is the published one of the reference it cites for it, applied by
+one common factor c to all rho_i: after an iteration whose residuals satisfy
+||r|| > mu ||d||, c <- tau c; if ||d|| > mu ||r||, c <- c / tau; else unchanged.
+The multipliers y_i are the unscaled ones, so they are not touched by a change.
 
 Parity status: pinned by tests/test_admm_oracle_pins.py (closed-form
 z-update against a direct minimisation, the invariant sum_i y_i = -lam z,
 convergence of z to the minimiser of the centralised problem, one worker
-without regulariser = repeated proximal steps).
+without regulariser = repeated proximal steps; residual balancing: never
+triggered = the fixed-penalty iterates, the invariant and the limit point are
+kept, a badly scaled penalty is moved towards balance and fewer iterations are
+needed than with the fixed one).  The rule's constants and its common-factor
+form are this build's reading, not the paper's text.
 """
 from __future__ import annotations
 
@@ -66,10 +76,12 @@ def tolerances(xs, ys, z, eps_abs: float, eps_rel: float):
 
 def admm(shards: List[orc.Problem], lam: float, rhos: Sequence[float], X0, max_outer: int,
          max_newton: int, max_cg: int, cg_tol: float, grad_tol: float, beta: float, gamma: float, max_ls: int,
-         eps_abs: float = 0.0, eps_rel: float = 0.0, forced_alphas=None):
+         eps_abs: float = 0.0, eps_rel: float = 0.0, forced_alphas=None,
+         penalty_rule: int = 0, rb_mu: float = 10.0, rb_tau: float = 2.0):
     """Algorithm 1 with fixed penalties.  `shards[i]` carries A_i, b_i, C and the loss scale s; its lam,
     rho, z, y fields are overwritten per iteration.  `forced_alphas[k][i]`, if given, is handed to the
     local solve of worker i in outer iteration k (see nadmm_oracle.local_newton).
+    penalty_rule 0: the penalties stay rhos; 1: residual balancing (module docstring).
     Returns (z, xs, ys, history); ys in the paper's sign convention."""
     N = len(shards)
     X0 = np.asarray(X0, dtype=np.float64)
@@ -77,7 +89,10 @@ def admm(shards: List[orc.Problem], lam: float, rhos: Sequence[float], X0, max_o
     ys = [np.zeros_like(X0) for _ in range(N)]
     z = np.zeros_like(X0)
     hist = []
+    rhos0 = [float(r) for r in rhos]
+    c = 1.0
     for k in range(max_outer):
+        rhos = [c * r for r in rhos0]
         local = []
         for i in range(N):
             prob = replace(shards[i], lam=0.0, rho=float(rhos[i]), z=z, y=-ys[i])
@@ -91,8 +106,13 @@ def admm(shards: List[orc.Problem], lam: float, rhos: Sequence[float], X0, max_o
         r = np.sqrt(sum(float(np.sum((z - xs[i]) ** 2)) for i in range(N)))
         dn = np.sqrt(sum(float(np.sum((rhos[i] * (z - z_prev)) ** 2)) for i in range(N)))
         e_pri, e_dual = tolerances(xs, ys, z, eps_abs, eps_rel)
-        hist.append(dict(r_norm=r, d_norm=dn, eps_pri=e_pri, eps_dual=e_dual, z=z.copy(),
+        hist.append(dict(r_norm=r, d_norm=dn, eps_pri=e_pri, eps_dual=e_dual, z=z.copy(), rho_scale=c,
                          xs=[x.copy() for x in xs], ys=[y.copy() for y in ys], local=local))
         if r <= e_pri and dn <= e_dual:
             break
+        if penalty_rule == 1:
+            if r > rb_mu * dn:
+                c = c * rb_tau
+            elif dn > rb_mu * r:
+                c = c / rb_tau
     return z, xs, ys, hist

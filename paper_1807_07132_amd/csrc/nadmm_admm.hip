@@ -22,11 +22,13 @@ __global__ __launch_bounds__(kThreads) void admm_init_kernel(AdmmState* st, floa
   for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < d; e += stride) z[e] = 0.f;
   if (st != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
     st->active = 1;
+    st->rho_scale = 1.f;
     nadmm_admm_stats* s = &st->stats;
     s->outer_iters = 0;
     s->converged = 0;
     s->r_norm = 0.0; s->d_norm = 0.0; s->eps_pri = 0.0; s->eps_dual = 0.0;
-    for (int i = 0; i < NADMM_TRACE_LEN; ++i) { s->r_trace[i] = 0.0; s->d_trace[i] = 0.0; }
+    s->rho_scale = 1.0;
+    for (int i = 0; i < NADMM_TRACE_LEN; ++i) { s->r_trace[i] = 0.0; s->d_trace[i] = 0.0; s->rho_scale_trace[i] = 0.0; }
   }
 }
 
@@ -34,23 +36,27 @@ __global__ __launch_bounds__(kThreads) void admm_init_kernel(AdmmState* st, floa
 __global__ __launch_bounds__(kThreads) void admm_consensus_kernel(const AdmmConsensusArgs a) {
   if (a.st != nullptr && a.st->active == 0) return;
   __shared__ double sm[kThreads / 64][kSums];
+  __shared__ float rho[NADMM_MAX_WORKERS];  // penalties of this iteration: the given ones times the common factor
+  const float scale = a.st != nullptr ? a.st->rho_scale : 1.f;
+  if (threadIdx.x < a.N) rho[threadIdx.x] = a.rho[threadIdx.x] * scale;
+  __syncthreads();
   double rho_sum = 0.0, rho_sq = 0.0;
   for (int i = 0; i < a.N; ++i) {
-    rho_sum += (double)a.rho[i];
-    rho_sq += (double)a.rho[i] * (double)a.rho[i];
+    rho_sum += (double)rho[i];
+    rho_sq += (double)rho[i] * (double)rho[i];
   }
   const float inv = (float)(1.0 / ((double)a.lambda + rho_sum));
   double acc[kSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < a.d; e += stride) {
     float num = 0.f;
-    for (int i = 0; i < a.N; ++i) num += fmaf(a.rho[i], a.x[(size_t)i * a.d + e], a.u[(size_t)i * a.d + e]);
+    for (int i = 0; i < a.N; ++i) num += fmaf(rho[i], a.x[(size_t)i * a.d + e], a.u[(size_t)i * a.d + e]);
     const float zn = num * inv;
     const float zo = a.z[e];
     a.z[e] = zn;
     for (int i = 0; i < a.N; ++i) {
       const float xi = a.x[(size_t)i * a.d + e];
-      const float un = fmaf(a.rho[i], xi - zn, a.u[(size_t)i * a.d + e]);
+      const float un = fmaf(rho[i], xi - zn, a.u[(size_t)i * a.d + e]);
       a.u[(size_t)i * a.d + e] = un;
       const double r = (double)zn - (double)xi;
       acc[0] += r * r;
@@ -109,11 +115,18 @@ __global__ __launch_bounds__(kThreads) void admm_finish_kernel(const AdmmConsens
     nadmm_admm_stats* s = &a.st->stats;
     s->outer_iters = a.iter + 1;
     s->r_norm = r_norm; s->d_norm = d_norm; s->eps_pri = eps_pri; s->eps_dual = eps_dual;
-    if (a.iter < NADMM_TRACE_LEN) { s->r_trace[a.iter] = r_norm; s->d_trace[a.iter] = d_norm; }
+    float scale = a.st->rho_scale;
+    if (a.iter < NADMM_TRACE_LEN) { s->r_trace[a.iter] = r_norm; s->d_trace[a.iter] = d_norm; s->rho_scale_trace[a.iter] = (double)scale; }
     if (r_norm <= eps_pri && d_norm <= eps_dual) {
       s->converged = 1;
       a.st->active = 0;
+    } else if (a.penalty_rule == 1) {
+      // residual balancing: a larger penalty shrinks the primal residual, a smaller one the dual residual
+      if (r_norm > (double)a.rb_mu * d_norm) scale *= a.rb_tau;
+      else if (d_norm > (double)a.rb_mu * r_norm) scale /= a.rb_tau;
+      a.st->rho_scale = scale;
     }
+    s->rho_scale = (double)scale;
   }
 }
 

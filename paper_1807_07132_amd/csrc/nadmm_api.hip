@@ -28,6 +28,7 @@ struct Layout {
   bool fused_ok, thin_ok, sliced_ok;
   bool sparse;
   int nwin_rows, nwin_cols;
+  const float* rho_scale;  // device scalar factor on rho (outer solver with an adaptive penalty), or NULL
 };
 
 int validate_problem(const nadmm_problem* p, bool need_labels) {
@@ -59,6 +60,7 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   s.NC = p->C - 1;
   s.d = (int64_t)s.p * s.NC;
   L->s = s;
+  L->rho_scale = nullptr;
   L->sparse = p->sparse != nullptr;
   L->gen_row_blocks = generic_row_blocks(s.n);
   generic_col_grid(s, &L->gen_slabs, &L->gen_chunks, &L->gen_rpc);
@@ -295,6 +297,7 @@ ReduceArgs reduce_args(const nadmm_problem* prob, const Layout& L, void* ws, int
   r.y = prob->d_y;
   r.lambda = prob->lambda;
   r.rho = prob->rho;
+  r.rho_scale = L.rho_scale;
   r.out = out;
   r.dot_part = dot_part;
   r.flag = flag;
@@ -443,6 +446,7 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     nh.pen_part = at<double>(d_ws, L.dotpart);
     nh.gg_part = nh.pen_part + reduce_out_blocks(L.s.d);
     nh.npart = reduce_out_blocks(L.s.d);
+    nh.rho_scale = L.rho_scale;
     NADMM_HIP(launch_newton_head(nh, st));
 
     // CG on H p = -g with the probabilities of this iterate
@@ -493,6 +497,7 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     lt.X_apply = d_X;
     lt.iter = t;
     lt.flag = &ds->newton_active;
+    lt.rho_scale = L.rho_scale;
     lt.qpart = at<double>(d_ws, L.dotpart);
     NADMM_HIP(launch_ls_tail(lt, st));
   }
@@ -607,6 +612,7 @@ int nadmm_loss_grad(const nadmm_problem* prob, const float* d_X, double* d_loss,
   lf.pen_part = d_grad ? at<double>(d_ws, L.dotpart) : nullptr;
   lf.npart = reduce_out_blocks(L.s.d);
   lf.loss_out = d_loss;
+  lf.rho_scale = nullptr;
   NADMM_HIP(launch_loss_finish(lf, st));
   return NADMM_OK;
 }
@@ -798,6 +804,10 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
   if (params->max_outer < 0 || !(lambda >= 0.f) || !std::isfinite(lambda) || !(params->eps_abs >= 0.f) ||
       !(params->eps_rel >= 0.f))
     return NADMM_EINVAL;
+  if (params->penalty_rule != 0 && params->penalty_rule != 1) return NADMM_EINVAL;
+  if (params->penalty_rule == 1 && (!(params->rb_mu >= 1.f) || !(params->rb_tau > 1.f) || !std::isfinite(params->rb_mu) ||
+                                    !std::isfinite(params->rb_tau)))
+    return NADMM_EINVAL;
   if ((rc = validate_params(&params->local)) != NADMM_OK) return rc;
   if (d_ws == nullptr || ((uintptr_t)d_ws & 255) != 0 || ws_bytes < AL.total) return NADMM_EWORKSPACE;
   hipStream_t st = (hipStream_t)stream;
@@ -816,11 +826,13 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
     wk[i].d_z = d_z;
     wk[i].d_y = d_u + (size_t)i * d;
     make_layout(&wk[i], &Ls[i]);
+    Ls[i].rho_scale = &as->rho_scale;
     if ((rc = choose_path(Ls[i], &paths[i])) != NADMM_OK) return rc;
     ca.rho[i] = wk[i].rho;
   }
   ca.st = as; ca.x = d_x; ca.u = d_u; ca.z = d_z; ca.N = N; ca.d = d;
   ca.lambda = lambda; ca.eps_abs = params->eps_abs; ca.eps_rel = params->eps_rel;
+  ca.penalty_rule = params->penalty_rule; ca.rb_mu = params->rb_mu; ca.rb_tau = params->rb_tau;
   ca.part = at<double>(d_ws, AL.part);
 
   NADMM_HIP(launch_admm_init(as, d_u, d_z, N, d, st));

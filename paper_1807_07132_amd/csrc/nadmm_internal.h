@@ -118,6 +118,7 @@ struct ReduceArgs {
   const float* z;
   const float* y;
   float lambda, rho;
+  const float* rho_scale; // optional device scalar: the penalty is rho * *rho_scale (adaptive penalty of the outer solver)
   float* out;
   double* dot_part;       // kind 0, optional: per-workgroup sums of out[e] * V[e], reduce_out_blocks(d) entries
   double* pen_part;       // kind 1, optional: per-workgroup sums of the penalty terms lambda/2 x^2 + rho/2 (x - z + y/rho)^2
@@ -141,6 +142,7 @@ struct LossFinishArgs {
   const double* pen_part;  // optional: penalty terms already summed per workgroup by the reduction (npart entries)
   int32_t npart;
   double* loss_out;  // device scalar
+  const float* rho_scale;  // optional device scalar factor on rho
 };
 hipError_t launch_loss_finish(const LossFinishArgs& a, hipStream_t st);
 
@@ -163,6 +165,7 @@ struct NewtonHeadArgs {
   const double* pen_part;  // optional (with gg_part): partial sums left by the reduction that formed g, which
   const double* gg_part;   //   has then also written p = 0, r = d = -g
   int32_t npart;
+  const float* rho_scale;  // optional device scalar factor on rho
 };
 hipError_t launch_newton_head(const NewtonHeadArgs& a, hipStream_t st);
 
@@ -231,6 +234,7 @@ struct LsTailArgs {
   int32_t* ok_out;
   int32_t iter;           // Newton iteration index or -1
   const int32_t* flag;
+  const float* rho_scale; // optional device scalar factor on rho
   double* qpart;          // scratch of 2 reduce_out_blocks(d) doubles (long vectors: the sums over d are formed by
                           // several workgroups and pass through it); NULL = single-workgroup form at any length
 };
@@ -242,7 +246,8 @@ hipError_t launch_state_init(DevState* st, const int32_t* outer_flag, hipStream_
 // ---- ADMM outer solver (nadmm_admm.hip) ----
 struct AdmmState {
   int32_t active;     // 0 once the residual test has stopped the iteration
-  int32_t pad_;
+  float rho_scale;    // common factor on every worker's penalty (residual balancing); written by the finishing
+                      // kernel of a consensus step, read by the kernels launched after it
   nadmm_admm_stats stats;
 };
 struct AdmmConsensusArgs {
@@ -254,6 +259,8 @@ struct AdmmConsensusArgs {
   int64_t d;
   float rho[NADMM_MAX_WORKERS];
   float lambda, eps_abs, eps_rel;
+  int32_t penalty_rule;    // 0 fixed, 1 residual balancing
+  float rb_mu, rb_tau;
   double* part;            // admm_blocks(d) x 5 partial sums
   double* out;             // optional: r_norm, d_norm, eps_pri, eps_dual
   int32_t iter;

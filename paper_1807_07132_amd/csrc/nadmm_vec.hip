@@ -34,6 +34,7 @@ __device__ __forceinline__ double block_sum(double v, double* sm /* >= 17 double
 // thread groups each sum every 8th partial (independent loads in flight), then the 8 group sums
 // are added in a fixed order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
+  const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;  // outer solver: common factor on the penalty
   if (a.flag != nullptr && *a.flag == 0) return;
   __shared__ float sm[8][32];
   const int el = threadIdx.x & 31, grp = threadIdx.x >> 5;
@@ -62,15 +63,15 @@ __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
   if (ok) {
     if (a.kind == 0) {
       const float v = a.V[e];
-      out = fmaf(a.lambda + a.rho, v, out);
+      out = fmaf(a.lambda + rho_, v, out);
       prod = (double)out * (double)v;
     } else {
       const float x = a.X[e];
       const float zz = a.z ? a.z[e] : 0.f;
       const float yy = a.y ? a.y[e] : 0.f;
-      out += a.lambda * x + a.rho * (x - zz) + yy;
-      const double xd = x, u = xd - (double)zz + (double)yy / (double)a.rho;
-      pen = 0.5 * (double)a.lambda * xd * xd + 0.5 * (double)a.rho * u * u;
+      out += a.lambda * x + rho_ * (x - zz) + yy;
+      const double xd = x, u = xd - (double)zz + (double)yy / (double)rho_;
+      pen = 0.5 * (double)a.lambda * xd * xd + 0.5 * (double)rho_ * u * u;
       prod = (double)out * (double)out;
       if (a.cg_p != nullptr) {
         a.cg_p[e] = 0.f;
@@ -102,6 +103,7 @@ constexpr int kWidePer = 8;
 constexpr int kWideChunk = 256 * kWidePer;
 
 __global__ __launch_bounds__(256) void reduce_out_wide_kernel(const ReduceArgs a) {
+  const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;  // outer solver: common factor on the penalty
   if (a.flag != nullptr && *a.flag == 0) return;
   __shared__ double sm[17];
   const int64_t base = (int64_t)blockIdx.x * kWideChunk + threadIdx.x;
@@ -135,13 +137,13 @@ __global__ __launch_bounds__(256) void reduce_out_wide_kernel(const ReduceArgs a
     if (e >= a.d) continue;
     float out = a.scale * sum[u];
     if (a.kind == 0) {
-      out = fmaf(a.lambda + a.rho, xv[u], out);
+      out = fmaf(a.lambda + rho_, xv[u], out);
       prod += (double)out * (double)xv[u];
     } else {
       const float x = xv[u];
-      out += a.lambda * x + a.rho * (x - zv[u]) + yv[u];
-      const double xd = x, uu = xd - (double)zv[u] + (double)yv[u] / (double)a.rho;
-      pen += 0.5 * (double)a.lambda * xd * xd + 0.5 * (double)a.rho * uu * uu;
+      out += a.lambda * x + rho_ * (x - zv[u]) + yv[u];
+      const double xd = x, uu = xd - (double)zv[u] + (double)yv[u] / (double)rho_;
+      pen += 0.5 * (double)a.lambda * xd * xd + 0.5 * (double)rho_ * uu * uu;
       prod += (double)out * (double)out;
       if (a.cg_p != nullptr) {
         a.cg_p[e] = 0.f;
@@ -208,10 +210,11 @@ __device__ __forceinline__ double partial_sum_block(const double* part, int n, d
 }
 
 __global__ __launch_bounds__(kTail) void loss_finish_kernel(const LossFinishArgs a) {
+  const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;  // outer solver: common factor on the penalty
   __shared__ double sm[17];
   const double data = partial_sum_block(a.loss_part, a.nblocks, sm);
   const double pen = a.pen_part ? partial_sum_block(a.pen_part, a.npart, sm)
-                                : penalty_block(a.X, a.z, a.y, a.d, a.lambda, a.rho, sm);
+                                : penalty_block(a.X, a.z, a.y, a.d, a.lambda, rho_, sm);
   if (threadIdx.x == 0) *a.loss_out = (double)a.scale * data + pen;
 }
 
@@ -233,6 +236,7 @@ __global__ void state_init_kernel(DevState* st, const int32_t* outer_flag) {
 // After a gradient evaluation: finish the objective, ||g||, the stopping test of
 // Algorithm 3, and start CG from p = 0, r = d = -g.
 __global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs a) {
+  const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;  // outer solver: common factor on the penalty
   __shared__ double sm[17];
   DevState* st = a.st;
   if (a.newton_mode && st->newton_active == 0) return;
@@ -266,7 +270,7 @@ __global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs
   if (a.newton_mode) {
     const double data = partial_sum_block(a.loss_part, a.nblocks, sm);
     const double pen = a.pen_part ? partial_sum_block(a.pen_part, a.npart, sm)
-                                  : penalty_block(a.X, a.z, a.y, a.d, a.lambda, a.rho, sm);
+                                  : penalty_block(a.X, a.z, a.y, a.d, a.lambda, rho_, sm);
     loss = (double)a.scale * data + pen;
   }
   if (threadIdx.x == 0) {
@@ -454,6 +458,7 @@ __global__ __launch_bounds__(kCgThreads) void cg_direction_kernel(const CgUpdate
 // Thread t sums the partials k = g, g + G, ... of element e = t mod d (g = t / d, G = 1024 / d groups),
 // the G group sums are added in order.
 __global__ __launch_bounds__(kTail) void cg_reduce_update_kernel(const ReduceArgs ra, const CgUpdateArgs a) {
+  const float rho_ = ra.rho_scale != nullptr ? ra.rho * *ra.rho_scale : ra.rho;  // outer solver: common factor on the penalty
   __shared__ double sm[17];
   __shared__ float gsum[kTail];
   DevState* st = a.st;
@@ -483,7 +488,7 @@ __global__ __launch_bounds__(kTail) void cg_reduce_update_kernel(const ReduceArg
     float s2 = 0.f;
     for (int g2 = 0; g2 < groups; ++g2) s2 += gsum[g2 * d + t];
     dv = a.dvec[t];
-    qv = fmaf(ra.lambda + ra.rho, dv, ra.scale * s2);
+    qv = fmaf(ra.lambda + rho_, dv, ra.scale * s2);
   }
   const double dq = block_sum((double)dv * (double)qv, sm);
   const double rr = st->rr;
@@ -579,10 +584,11 @@ __global__ __launch_bounds__(256) void ls_eval_kernel(const LsEvalArgs a) {
 // X += alpha p as kernels of their own around the single-workgroup decision kernel below.
 // qpart: [4][nq] partial sums of the penalty coefficients q0, q1, q2 and of the slope <p, g>.
 __global__ __launch_bounds__(256) void ls_vec_part_kernel(const LsTailArgs a, int nq) {
+  const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;  // outer solver: common factor on the penalty
   if (a.flag != nullptr && *a.flag == 0) return;
   __shared__ double sm[17];
   double q0 = 0.0, q1 = 0.0, q2 = 0.0, sl = 0.0;
-  const double inv_rho = 1.0 / (double)a.rho;
+  const double inv_rho = 1.0 / (double)rho_;
   for (int64_t base = (int64_t)blockIdx.x * kWideChunk + threadIdx.x; base < a.d; base += (int64_t)gridDim.x * kWideChunk) {
     float xv[kWidePer], zv[kWidePer], yv[kWidePer], pvv[kWidePer], gv[kWidePer];
 #pragma unroll
@@ -600,9 +606,9 @@ __global__ __launch_bounds__(256) void ls_vec_part_kernel(const LsTailArgs a, in
       const double x = xv[u];
       const double uu = x - (double)zv[u] + (double)yv[u] * inv_rho;
       const double pv = pvv[u];
-      q0 += 0.5 * (double)a.lambda * x * x + 0.5 * (double)a.rho * uu * uu;
-      q1 += (double)a.lambda * x * pv + (double)a.rho * uu * pv;
-      q2 += 0.5 * ((double)a.lambda + (double)a.rho) * pv * pv;
+      q0 += 0.5 * (double)a.lambda * x * x + 0.5 * (double)rho_ * uu * uu;
+      q1 += (double)a.lambda * x * pv + (double)rho_ * uu * pv;
+      q2 += 0.5 * ((double)a.lambda + (double)rho_) * pv * pv;
       sl += pv * (double)gv[u];
     }
   }
@@ -641,6 +647,7 @@ __global__ __launch_bounds__(256) void ls_apply_kernel(const DevState* st, const
 // Algorithm 2 on the candidate objective values; optionally applies X += alpha p.  nq > 0: the sums
 // over d come as partial sums from ls_vec_part_kernel and X is updated by ls_apply_kernel.
 __global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a, int nq) {
+  const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;  // outer solver: common factor on the penalty
   __shared__ double sm[17];
   __shared__ double cand[kCandSlots];
   __shared__ float s_alpha;
@@ -666,7 +673,7 @@ __global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a, int 
   }
   // penalty along the line: q0 + alpha q1 + alpha^2 q2, and the slope <p, g>
   double q0 = 0.0, q1 = 0.0, q2 = 0.0, sl = 0.0;
-  const double inv_rho = 1.0 / (double)a.rho;
+  const double inv_rho = 1.0 / (double)rho_;
   for (int64_t e0 = threadIdx.x; nq == 0 && e0 < a.d; e0 += (int64_t)kBlk * blockDim.x) {
     float xv[kBlk], zv[kBlk], yv[kBlk], pvv[kBlk], gv[kBlk];
 #pragma unroll
@@ -684,9 +691,9 @@ __global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a, int 
       const double x = xv[u];
       const double uu = x - (double)zv[u] + (double)yv[u] * inv_rho;
       const double pv = pvv[u];
-      q0 += 0.5 * (double)a.lambda * x * x + 0.5 * (double)a.rho * uu * uu;
-      q1 += (double)a.lambda * x * pv + (double)a.rho * uu * pv;
-      q2 += 0.5 * ((double)a.lambda + (double)a.rho) * pv * pv;
+      q0 += 0.5 * (double)a.lambda * x * x + 0.5 * (double)rho_ * uu * uu;
+      q1 += (double)a.lambda * x * pv + (double)rho_ * uu * pv;
+      q2 += 0.5 * ((double)a.lambda + (double)rho_) * pv * pv;
       sl += pv * (double)gv[u];
     }
   }

@@ -89,14 +89,16 @@ NADMM_MAX_WORKERS = 64
 
 
 class nadmm_admm_params(C.Structure):
-    _fields_ = [("max_outer", C.c_int32), ("eps_abs", C.c_float), ("eps_rel", C.c_float), ("local", nadmm_params)]
+    _fields_ = [("max_outer", C.c_int32), ("eps_abs", C.c_float), ("eps_rel", C.c_float), ("local", nadmm_params),
+                ("penalty_rule", C.c_int32), ("rb_mu", C.c_float), ("rb_tau", C.c_float)]
 
 
 class nadmm_admm_stats(C.Structure):
     _fields_ = [
         ("outer_iters", C.c_int32), ("converged", C.c_int32), ("r_norm", C.c_double), ("d_norm", C.c_double),
         ("eps_pri", C.c_double), ("eps_dual", C.c_double), ("r_trace", C.c_double * NADMM_TRACE_LEN),
-        ("d_trace", C.c_double * NADMM_TRACE_LEN),
+        ("d_trace", C.c_double * NADMM_TRACE_LEN), ("rho_scale", C.c_double),
+        ("rho_scale_trace", C.c_double * NADMM_TRACE_LEN),
     ]
 
 
@@ -298,8 +300,11 @@ def nadmm_local_newton(prob: Problem, X: torch.Tensor, params: nadmm_params, wan
                 loss=list(st.loss[:k]), grad_norm=list(st.grad_norm[:k]))
 
 
-def make_admm_params(max_outer: int, local: nadmm_params, eps_abs=0.0, eps_rel=0.0) -> nadmm_admm_params:
-    return nadmm_admm_params(int(max_outer), float(eps_abs), float(eps_rel), local)
+def make_admm_params(max_outer: int, local: nadmm_params, eps_abs=0.0, eps_rel=0.0, penalty_rule=0, rb_mu=10.0,
+                     rb_tau=2.0) -> nadmm_admm_params:
+    """penalty_rule 0: fixed penalties; 1: residual balancing with imbalance threshold rb_mu and factor rb_tau."""
+    return nadmm_admm_params(int(max_outer), float(eps_abs), float(eps_rel), local, int(penalty_rule), float(rb_mu),
+                             float(rb_tau))
 
 
 def _worker_array(workers):
@@ -350,4 +355,5 @@ def nadmm_admm_solve(workers, lam: float, x: torch.Tensor, params: nadmm_admm_pa
         return z, u, None
     k = min(st.outer_iters, NADMM_TRACE_LEN)
     return z, u, dict(outer_iters=st.outer_iters, converged=bool(st.converged), r_norm=st.r_norm, d_norm=st.d_norm,
-                      eps_pri=st.eps_pri, eps_dual=st.eps_dual, r_trace=list(st.r_trace[:k]), d_trace=list(st.d_trace[:k]))
+                      eps_pri=st.eps_pri, eps_dual=st.eps_dual, r_trace=list(st.r_trace[:k]), d_trace=list(st.d_trace[:k]),
+                      rho_scale=st.rho_scale, rho_scale_trace=list(st.rho_scale_trace[:k]))

@@ -45,11 +45,12 @@ def test_struct_layout_matches_the_header(tmp_path):
     src = tmp_path / "sizes.c"
     src.write_text(
         '#include <stdio.h>\n#include <stddef.h>\n#include "nadmm.h"\n'
-        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(nadmm_problem), sizeof(nadmm_params),"
+        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(nadmm_problem), sizeof(nadmm_params),"
         " sizeof(nadmm_stats), offsetof(nadmm_problem, d_labels), offsetof(nadmm_problem, d_z),"
         " offsetof(nadmm_stats, loss_initial), offsetof(nadmm_stats, grad_norm), sizeof(nadmm_admm_params),"
         " sizeof(nadmm_admm_stats), offsetof(nadmm_admm_params, local), offsetof(nadmm_admm_stats, d_trace),"
-        " offsetof(nadmm_problem, sparse), sizeof(nadmm_sparse), offsetof(nadmm_sparse, d_val_t));return 0;}\n")
+        " offsetof(nadmm_problem, sparse), sizeof(nadmm_sparse), offsetof(nadmm_sparse, d_val_t),"
+        " offsetof(nadmm_admm_params, rb_tau), offsetof(nadmm_admm_stats, rho_scale_trace));return 0;}\n")
     exe = tmp_path / "sizes"
     subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", f"-I{os.path.join(ROOT, 'include')}", str(src), "-o", str(exe)])
     got = [int(v) for v in subprocess.check_output([str(exe)]).split()]
@@ -58,7 +59,8 @@ def test_struct_layout_matches_the_header(tmp_path):
             nadmm.nadmm_stats.loss_initial.offset, nadmm.nadmm_stats.grad_norm.offset,
             C.sizeof(nadmm.nadmm_admm_params), C.sizeof(nadmm.nadmm_admm_stats), nadmm.nadmm_admm_params.local.offset,
             nadmm.nadmm_admm_stats.d_trace.offset, nadmm.nadmm_problem.sparse.offset, C.sizeof(nadmm.nadmm_sparse),
-            nadmm.nadmm_sparse.d_val_t.offset]
+            nadmm.nadmm_sparse.d_val_t.offset, nadmm.nadmm_admm_params.rb_tau.offset,
+            nadmm.nadmm_admm_stats.rho_scale_trace.offset]
     assert got == want
 
 
@@ -215,6 +217,9 @@ def test_admm_host_validation(lib):
     assert call(workers, 3, -0.1, params, need) == nadmm.NADMM_EINVAL
     bad = nadmm.make_admm_params(-1, nadmm.make_params(2, 5, 10))
     assert call(workers, 3, 0.1, bad, need) == nadmm.NADMM_EINVAL
+    for kw in (dict(penalty_rule=2), dict(penalty_rule=1, rb_mu=0.5), dict(penalty_rule=1, rb_tau=1.0),
+               dict(penalty_rule=1, rb_tau=float("nan"))):
+        assert call(workers, 3, 0.1, nadmm.make_admm_params(3, nadmm.make_params(2, 5, 10), **kw), need) == nadmm.NADMM_EINVAL
     mixed = (nadmm.nadmm_problem * 2)(fake_problem(p=20), fake_problem(p=24))     # shards must agree in p and C
     assert lib.nadmm_admm_workspace_bytes(mixed, 2, C.byref(params)) == 0
     rho = (C.c_float * 2)(1.0, -1.0)

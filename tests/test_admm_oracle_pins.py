@@ -108,3 +108,50 @@ def test_admm_one_worker_without_regulariser_is_the_method_of_multipliers():
         np.testing.assert_allclose(hist[k]["xs"][0], x, rtol=0, atol=5e-7)
         np.testing.assert_allclose(hist[k]["z"], x, rtol=0, atol=5e-7)       # z = x when y = 0 and lam = 0
         np.testing.assert_allclose(hist[k]["ys"][0], 0.0, rtol=0, atol=1e-12)
+
+
+def _central_minimiser(full, lam, shape):
+    central = orc.Problem(full.A, full.b, full.C, s=full.s, lam=0.0, rho=lam)
+
+    def fg(xf):
+        f, g = orc.loss_grad(central, xf.reshape(shape))
+        return f, g.ravel()
+
+    res = scipy.optimize.minimize(fg, np.zeros(int(np.prod(shape))), jac=True, method="L-BFGS-B",
+                                  options=dict(maxiter=5000, ftol=1e-15, gtol=1e-12))
+    return res.x.reshape(shape)
+
+
+def test_residual_balancing_that_never_triggers_is_the_fixed_penalty_iteration():
+    shards, _, _ = make_shards(N=3, seed=5)
+    lam, rhos = 0.05, [0.3, 0.6, 0.9]
+    X0 = np.zeros((4, 2))
+    args = (shards, lam, rhos, X0, 8, 2, 5, 0.0, 0.0, 1e-4, 0.5, 10)
+    z0, xs0, ys0, h0 = adm.admm(*args)
+    z1, xs1, ys1, h1 = adm.admm(*args, penalty_rule=1, rb_mu=1e30, rb_tau=2.0)
+    assert np.array_equal(z0, z1) and all(np.array_equal(a, b) for a, b in zip(ys0, ys1))
+    assert [h["rho_scale"] for h in h1] == [1.0] * 8
+
+
+def test_residual_balancing_keeps_the_invariant_and_the_limit_and_repairs_a_bad_penalty():
+    shards, full, _ = make_shards(N=3, seed=3)
+    lam = 0.02
+    X0 = np.zeros((4, 2))
+    ref = _central_minimiser(full, lam, X0.shape)
+    local = (5, 30, 1e-10, 1e-12, 1e-4, 0.5, 20)
+    for rho, up in ((1e-3, True), (50.0, False)):
+        z, xs, ys, hist = adm.admm(shards, lam, [rho, 2 * rho, rho], X0, 250, *local, eps_abs=1e-6, eps_rel=1e-5,
+                                   penalty_rule=1, rb_mu=10.0, rb_tau=2.0)
+        scales = [h["rho_scale"] for h in hist]
+        assert len(hist) < 250                                   # stopped by the residual test
+        assert np.linalg.norm(z - ref) <= 1e-3 * np.linalg.norm(ref)
+        assert scales[0] == 1.0 and (scales[-1] >= 16.0 if up else scales[-1] <= 1.0 / 16.0)
+        for h in hist:                                           # the z- and y-updates stay consistent under changing penalties
+            np.testing.assert_allclose(sum(h["ys"]), -lam * h["z"], rtol=0, atol=1e-12)
+        # the residuals end within the balance that the rule aims at, which the fixed penalty is far from
+        ratio = hist[-1]["r_norm"] / hist[-1]["d_norm"]
+        assert 1.0 / 20.0 <= ratio <= 20.0
+        zf, _, _, hf = adm.admm(shards, lam, [rho, 2 * rho, rho], X0, 250, *local, eps_abs=1e-6, eps_rel=1e-5)
+        assert len(hf) == 250                                    # the fixed penalty has not met the same tolerances
+        rf = hf[-1]["r_norm"] / max(hf[-1]["d_norm"], 1e-300)
+        assert rf > 1e3 if up else rf < 1e-2

@@ -115,3 +115,49 @@ def test_admm_stops_on_the_residual_test_and_later_iterations_are_no_ops():
     x2 = dev(np.stack([X0] * N))
     z2, u2, st2 = nadmm.nadmm_admm_solve(gps, lam, x2, nadmm.make_admm_params(st["outer_iters"], local, eps_abs, eps_rel))
     assert torch.equal(z, z2) and torch.equal(x, x2) and torch.equal(u, u2)
+
+
+@pytest.mark.parametrize("case", ["small_penalty_thin", "large_penalty_fused", "sparse_shards"])
+def test_admm_residual_balancing(case):
+    """Adaptive penalty by residual balancing: the common factor on the penalties changes between outer iterations
+    on the device (it reaches the local solves and the consensus step through device memory); iterates, residuals
+    and the factor's history against the oracle after a fixed number of outer iterations."""
+    if case == "small_penalty_thin":
+        w, N, rhos, lam, K = workloads.generic(3000, 24, 4, seed=41), 4, [1e-3, 2e-3, 1e-3, 1e-3], 1e-3, 10
+    elif case == "large_penalty_fused":
+        w, N, rhos, lam, K = workloads.generic(3001, 64, 5, seed=42), 3, [40.0, 40.0, 80.0], 1e-2, 10
+    else:
+        w, N, rhos, lam, K = workloads.sparse_generic(1500, 600, 4, 30, seed=43), 3, [1e-3, 1e-3, 1e-3], 1e-3, 8
+    print(f"admm residual balancing: {case}", flush=True)
+    s = 1.0 / w.n
+    bounds = np.linspace(0, w.n, N + 1).astype(int)
+    gps, ops = [], []
+    for i in range(N):
+        A, b = w.A[bounds[i]:bounds[i + 1]], w.b[bounds[i]:bounds[i + 1]]
+        Ad = nadmm.SparseA.from_scipy(A, A.tocsc()) if w.sparse else dev(A)
+        gps.append(nadmm.Problem(Ad, dev(b), w.C, s, 0.0, float(rhos[i]), None, None))
+        ops.append(orc.Problem(A, b, w.C, s=s))
+    X0 = np.zeros_like(w.X0)
+    # the sparse shards with a penalty of 1e-3 are ill-conditioned: 8 CG iterations leave the Newton directions far from
+    # converged and float32 rounding then shows at several 1e-3 in the iterates, with fixed penalties as well; 30 do not
+    T, Kcg, mu, tau = 2, (30 if w.sparse else 8), 4.0, 2.0
+    params = nadmm.make_admm_params(K, nadmm.make_params(T, Kcg, w.max_ls, 0.0, 0.0, w.beta, w.gamma),
+                                    penalty_rule=1, rb_mu=mu, rb_tau=tau)
+    x = dev(np.stack([X0] * N))
+    z, u, st = nadmm.nadmm_admm_solve(gps, lam, x, params)
+    z_ref, xs_ref, ys_ref, hist = adm.admm(ops, lam, rhos, X0, K, T, Kcg, 0.0, 0.0, w.beta, w.gamma, w.max_ls,
+                                           penalty_rule=1, rb_mu=mu, rb_tau=tau)
+    ref_scales = [h["rho_scale"] for h in hist]
+    assert len(set(ref_scales)) >= 3                      # the rule acted several times in this run
+    # a comparison of two norms decides each change: the histories must agree unless a comparison was a tie
+    ties = [k for k, h in enumerate(hist) if min(abs(h["r_norm"] - mu * h["d_norm"]), abs(h["d_norm"] - mu * h["r_norm"]))
+            <= 1e-3 * max(h["r_norm"], h["d_norm"])]
+    assert not ties, "test parameters put a balancing decision on a tie"
+    assert st["rho_scale_trace"] == ref_scales
+    assert st["outer_iters"] == K
+    assert rel_l2(host(z), z_ref) <= TOL_ITERATE
+    for i in range(N):
+        assert rel_l2(host(x)[i], xs_ref[i]) <= TOL_ITERATE
+    assert st["r_trace"] == pytest.approx([h["r_norm"] for h in hist], rel=5e-3)
+    assert st["d_trace"] == pytest.approx([h["d_norm"] for h in hist], rel=5e-3)
+    np.testing.assert_allclose(host(u).sum(0), lam * host(z), atol=1e-5 * max(1.0, float(np.abs(host(u)).max())))
