@@ -188,7 +188,7 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
                        nadmm_stats* h_stats, void* d_ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
- * ADMM outer solver with N workers simulated on one GPU (Algorithm 1 with fixed penalty parameters;
+ * ADMM outer solver with N workers simulated on one GPU (Algorithm 1 with fixed or residual-balanced penalty parameters;
  * Section 2.3: x-, z-, y-updates, closed-form z-update for g(z) = lambda/2 ||z||^2; Section 2.3.1:
  * residuals and stopping).  The workers' local solves run one after the other on the one device.
  *

@@ -1,4 +1,4 @@
-"""Plain float64 oracle of the ADMM outer solver (Algorithm 1) with a fixed penalty parameter.
+"""Plain float64 oracle of the ADMM outer solver (Algorithm 1) with fixed or residual-balanced penalty parameters.
 
 TEST INFRASTRUCTURE ONLY -- see the package docstring.  The steps are taken in
 the paper's order and notation (Section 2.3, equations x-update, z-update,
@@ -78,7 +78,7 @@ def admm(shards: List[orc.Problem], lam: float, rhos: Sequence[float], X0, max_o
          max_newton: int, max_cg: int, cg_tol: float, grad_tol: float, beta: float, gamma: float, max_ls: int,
          eps_abs: float = 0.0, eps_rel: float = 0.0, forced_alphas=None,
          penalty_rule: int = 0, rb_mu: float = 10.0, rb_tau: float = 2.0):
-    """Algorithm 1 with fixed penalties.  `shards[i]` carries A_i, b_i, C and the loss scale s; its lam,
+    """Algorithm 1.  `shards[i]` carries A_i, b_i, C and the loss scale s; its lam,
     rho, z, y fields are overwritten per iteration.  `forced_alphas[k][i]`, if given, is handed to the
     local solve of worker i in outer iteration k (see nadmm_oracle.local_newton).
     penalty_rule 0: the penalties stay rhos; 1: residual balancing (module docstring).

@@ -1,4 +1,4 @@
-"""Pins of the float64 ADMM oracle (Algorithm 1, fixed penalties) against what the mathematics fixes:
+"""Pins of the float64 ADMM oracle (Algorithm 1, fixed penalties and residual balancing) against what the mathematics fixes:
 the z-update against a direct numerical minimisation of its defining problem, the multiplier invariant
 that follows from the z- and y-updates, convergence to the minimiser of the centralised problem found by
 an independent optimiser, and the one-worker case against the proximal-point iteration it reduces to."""

@@ -1,4 +1,4 @@
-"""GPU parity of the ADMM outer solver (Algorithm 1 with fixed penalties, N workers simulated on one GPU)
+"""GPU parity of the ADMM outer solver (Algorithm 1 with fixed or residual-balanced penalties, N workers simulated on one GPU)
 against the float64 oracle: the consensus step element by element, whole iterations after a fixed number
 of outer iterations, and the residual-based stop."""
 import numpy as np
