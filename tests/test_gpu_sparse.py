@@ -246,3 +246,29 @@ def test_admm_on_sparse_shards():
     for i in range(N):
         assert rel_l2(host(x)[i], xs_ref[i]) <= TOL_ITERATE
     assert st["r_norm"] == pytest.approx(hist[-1]["r_norm"], rel=5e-3)
+
+
+def test_sparse_local_newton_replays_from_a_hip_graph(cache):
+    """The sparse local solve is enqueued without host synchronisation, allocation or memset (window tables, packed
+    operands and the products are all kernels), so it can be captured once and replayed; every replay, with eager work
+    in between, must give the eager result bit for bit."""
+    w, gp, op = setup_case(cache, "e18_shape_2000x9000_C20")
+    params = nadmm.make_params(2, 4, w.max_ls, 0.0, 0.0, w.beta, w.gamma)
+    ws = gp.workspace()
+    X0 = dev(w.X0.copy())
+    X_eager = X0.clone()
+    nadmm.nadmm_local_newton(gp, X_eager, params, want_stats=False, ws=ws)
+    torch.cuda.synchronize()
+    X = X0.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            nadmm.nadmm_local_newton(gp, X, params, want_stats=False, ws=ws, stream=side)
+    for _ in range(3):
+        X.copy_(X0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(X, X_eager)
+        hv = nadmm.nadmm_hessvec(gp, X0, dev(w.V), ws=ws)
+        assert rel_l2(host(hv), orc.hessvec(op, w.X0, w.V)) <= TOL_PRIMITIVE
