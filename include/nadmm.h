@@ -125,6 +125,7 @@ typedef struct nadmm_stats {
   double  grad_norm[NADMM_TRACE_LEN]; /* ||g|| at the start of each iteration */
 } nadmm_stats;
 
+/* 100 * major + minor; 102: sparse storage of A, residual balancing (struct layouts changed since 100) */
 int         nadmm_version(void);
 const char* nadmm_status_string(int code);
 

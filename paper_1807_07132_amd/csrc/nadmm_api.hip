@@ -532,7 +532,7 @@ static int admm_layout(const nadmm_problem* w, int32_t N, AdmmLayout* AL, int64_
 
 extern "C" {
 
-int nadmm_version(void) { return 100; }
+int nadmm_version(void) { return 102; }
 
 const char* nadmm_status_string(int code) {
   switch (code) {
