@@ -44,8 +44,11 @@ convergence of z to the minimiser of the centralised problem, one worker
 without regulariser = repeated proximal steps; residual balancing: never
 triggered = the fixed-penalty iterates, the invariant and the limit point are
 kept, a badly scaled penalty is moved towards balance and fewer iterations are
-needed than with the fixed one).  The rule's constants and its common-factor
-form are this build's reading, not the paper's text.
+needed than with the fixed one; the tolerances on numbers worked by hand, and
+the balancing update step by step on a two-worker scalar example whose first
+iteration has a closed form and whose later x-updates are checked by
+substitution into the scalar stationarity condition).  The rule's constants and
+its common-factor form are this build's reading, not the paper's text.
 """
 from __future__ import annotations
 
