@@ -23,7 +23,15 @@
  *     device memory in stream order.  Only nadmm_local_newton with a non-NULL
  *     h_stats synchronises the stream.
  *   - Layout of A: row-major n x p float32, row stride lda >= p elements, row i
- *     is sample a_i; or sparse storage, see nadmm_sparse.  Labels: int32 in 0..C-1; class C-1 is the reference
+ *     is sample a_i; or sparse storage, see nadmm_sparse.  The matrix-core kernels read rows in
+ *     16-byte pieces, so d_A must be readable for (n-1) lda + 4 ceil(p/4) elements: up to three
+ *     elements past the last sample when p is not a multiple of 4 (an n x lda allocation always
+ *     is; what those elements hold does not matter).  Which kernels run depends on the stride:
+ *     lda a multiple of 4 and d_A 16-byte aligned take the single-pass or two-sweep matrix-core
+ *     kernels (50-60 % resp. about 30 % of the HBM roofline); any other stride or alignment
+ *     falls to the two-pass float32 vector kernels, which are correct for every shape but 10 to
+ *     20 times slower (2-4 % of the roofline): pad rows to a multiple of 4 elements.
+ *     nadmm_query_kernel_path() tells which path a problem takes.  Labels: int32 in 0..C-1; class C-1 is the reference
  *     class with logit 0 (the paper's class C).  Label values and finiteness
  *     of A are not checked (out-of-range labels are treated as the reference
  *     class; no out-of-bounds access results).

@@ -77,7 +77,8 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   const int64_t r_begin = (int64_t)blockIdx.x * fa.rows_per_wg;
   int64_t r_end = r_begin + fa.rows_per_wg;
   if (r_end > a.n) r_end = a.n;
-  const int col_max = (int)a.lda - 4;  // last 16-byte aligned column offset that stays inside a row
+  const int col_max = ((p + 3) & ~3) - 4;  // last 16-byte aligned column offset that holds a column of A: no load goes
+                                           // past element 4 ceil(p/4) of a row (<= lda, a multiple of 4)
 
   // ---- prefetch registers: [step][row block][half of the 8 columns] ----
   // Addresses are clamped into the matrix, so the loads need no branches; rows
@@ -108,7 +109,8 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
 
   // ---- [X|V] operands of this wave's steps, split and packed once (branch-free loads,
   //      issued while the first tile is already on its way) ----
-  u32x4 bx_hi[SPW], bx_lo[SPW], bv_hi[SPW], bv_lo[SPW];
+  //      X in three bf16 parts: the logit product is taken to full fp32 accuracy (mfma6)
+  u32x4 bx_hi[SPW], bx_lo[SPW], bx_lo2[SPW], bv_hi[SPW], bv_lo[SPW];
 #pragma unroll
   for (int i = 0; i < SPW; ++i) {
     const int s = wave + kWaves * i;
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
       x[e] = ok ? x[e] : 0.f;
       v[e] = ok ? v[e] : 0.f;
     }
-    split8(x, bx_hi[i], bx_lo[i]);
+    split8_3(x, bx_hi[i], bx_lo[i], bx_lo2[i]);
     split8(v, bv_hi[i], bv_lo[i]);
   }
 
@@ -170,8 +172,13 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
         u32x4 ahi[2], alo[2];
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
-          split8(av[rb], ahi[rb], alo[rb]);
-          if (has0) accZ[rb] = mfma3(ahi[rb], alo[rb], bx_hi[i], bx_lo[i], accZ[rb]);
+          if (has0) {
+            u32x4 alo2;
+            split8_3(av[rb], ahi[rb], alo[rb], alo2);
+            accZ[rb] = mfma6(ahi[rb], alo[rb], alo2, bx_hi[i], bx_lo[i], bx_lo2[i], accZ[rb]);
+          } else {
+            split8(av[rb], ahi[rb], alo[rb]);
+          }
           if (has1) accW[rb] = mfma3(ahi[rb], alo[rb], bv_hi[i], bv_lo[i], accW[rb]);
         }
         // the registers are free again: prefetch the next tile (past the range the rows clamp to the last row)
@@ -224,7 +231,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     float P, M = 0.f, alpha = 1.f, d;
     if (has0) {
       const float zc = cv ? z : 0.f;
-      M = row16_max(zc);                   // max{0, Z_1..Z_{C-1}}: padded lanes supply the 0
+      M = fmaxf(row16_max(zc), 0.f);       // max{0, Z_1..Z_{C-1}} (eq. max_x); with 16 free classes no padded lane supplies the 0
       const float E = cv ? expf(zc - M) : 0.f;
       alpha = row16_sum(E) + expf(-M);
       P = E / alpha;

@@ -33,6 +33,22 @@ __device__ __forceinline__ void split8(const float (&a)[8], u32x4& hi, u32x4& lo
   lo = u32x4{l[0], l[1], l[2], l[3]};
 }
 
+// 8 floats -> three packed bf16 parts, x = hi + mid + lo + O(2^-24 |x|): the residual after each rounding is
+// exact in fp32, so the three parts carry the whole fp32 significand
+__device__ __forceinline__ void split8_3(const float (&a)[8], u32x4& hi, u32x4& mid, u32x4& lo) {
+  unsigned h[4], m[4], l[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    h[k] = pack2(a[2 * k], a[2 * k + 1]);
+    const float r0 = a[2 * k] - low_as_float(h[k]), r1 = a[2 * k + 1] - high_as_float(h[k]);
+    m[k] = pack2(r0, r1);
+    l[k] = pack2(r0 - low_as_float(m[k]), r1 - high_as_float(m[k]));
+  }
+  hi = u32x4{h[0], h[1], h[2], h[3]};
+  mid = u32x4{m[0], m[1], m[2], m[3]};
+  lo = u32x4{l[0], l[1], l[2], l[3]};
+}
+
 __device__ __forceinline__ f32x4 mfma(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
@@ -40,6 +56,18 @@ __device__ __forceinline__ f32x4 mfma(u32x4 a, u32x4 b, f32x4 c) {
 __device__ __forceinline__ f32x4 mfma3(u32x4 ahi, u32x4 alo, u32x4 bhi, u32x4 blo, f32x4 c) {
   c = mfma(alo, bhi, c);
   c = mfma(ahi, blo, c);
+  return mfma(ahi, bhi, c);
+}
+
+// c += (ahi + amid + alo) (bhi + bmid + blo) keeping the six terms of relative weight >= 2^-16 (the
+// dropped ones are below 2^-23): the product is then as accurate as an fp32 one.  Used for the logits
+// Z = A X only, whose absolute error exp() turns into a relative error of the probabilities (Section 2.2).
+__device__ __forceinline__ f32x4 mfma6(u32x4 ahi, u32x4 amid, u32x4 alo, u32x4 bhi, u32x4 bmid, u32x4 blo, f32x4 c) {
+  c = mfma(alo, bhi, c);
+  c = mfma(ahi, blo, c);
+  c = mfma(amid, bmid, c);
+  c = mfma(amid, bhi, c);
+  c = mfma(ahi, bmid, c);
   return mfma(ahi, bhi, c);
 }
 

@@ -72,9 +72,11 @@ __device__ __forceinline__ void load_step_regs(const RowArgs& a, float4 (&pf)[2]
   }
 }
 
-// Registers of one step -> bf16 high/low operands of both row blocks; columns past p are zeroed.
+// Registers of one step -> bf16 high/low operands of both row blocks (and, if THREE, the third parts
+// that the full-accuracy logit product needs); columns past p are zeroed.
+template <bool THREE>
 __device__ __forceinline__ void convert_step(const float4 (&pf)[2][2], int col, int col_max, int p, bool ragged,
-                                             u32x4 (&ahi)[2], u32x4 (&alo)[2]) {
+                                             u32x4 (&ahi)[2], u32x4 (&alo)[2], u32x4 (&alo2)[2]) {
   float av[2][8];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
@@ -93,8 +95,13 @@ __device__ __forceinline__ void convert_step(const float4 (&pf)[2][2], int col, 
       }
     }
   }
-  split8(av[0], ahi[0], alo[0]);
-  split8(av[1], ahi[1], alo[1]);
+  if (THREE) {
+    split8_3(av[0], ahi[0], alo[0], alo2[0]);
+    split8_3(av[1], ahi[1], alo[1], alo2[1]);
+  } else {
+    split8(av[0], ahi[0], alo[0]);
+    split8(av[1], ahi[1], alo[1]);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -117,7 +124,7 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
   const int NC = a.NC, p = a.p;
   const int slice = blockIdx.x;
   const WaveSteps ws = wave_steps(sa, slice, wave);
-  const int col_max = (int)a.lda - 4;
+  const int col_max = ((p + 3) & ~3) - 4;  // no load goes past element 4 ceil(p/4) of a row
 
   const int64_t r_begin = (int64_t)blockIdx.y * sa.rows_per_wg;
   int64_t r_end = r_begin + sa.rows_per_wg;
@@ -132,8 +139,8 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
   for (int i = 0; i < SPW; ++i)
     if (step_exists(i)) load_step_regs(a, pf[i], r_begin, r_end, col_of(i), col_max, m);
 
-  // operands [X|V] of this wave's steps: hi / lo, per class block
-  u32x4 bx_hi[SPW][NB], bx_lo[SPW][NB], bv_hi[SPW][NB], bv_lo[SPW][NB];
+  // operands [X|V] of this wave's steps: hi / lo, per class block; X in three parts (full-accuracy logits)
+  u32x4 bx_hi[SPW][NB], bx_lo[SPW][NB], bx_lo2[SPW][NB], bv_hi[SPW][NB], bv_lo[SPW][NB];
 #pragma unroll
   for (int i = 0; i < SPW; ++i)
 #pragma unroll
@@ -152,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
         x[e] = ok ? xv : 0.f;
         v[e] = ok ? vv : 0.f;
       }
-      split8(x, bx_hi[i][nb], bx_lo[i][nb]);
+      split8_3(x, bx_hi[i][nb], bx_lo[i][nb], bx_lo2[i][nb]);
       split8(v, bv_hi[i][nb], bv_lo[i][nb]);
     }
 
@@ -168,14 +175,15 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
     for (int i = 0; i < SPW; ++i) {
       if (step_exists(i)) {
         const int col = col_of(i);
-        u32x4 ahi[2], alo[2];
-        convert_step(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo);
+        u32x4 ahi[2], alo[2], alo2[2];
+        convert_step<HAS0>(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo, alo2);
         load_step_regs(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
           for (int rb = 0; rb < 2; ++rb) {
-            if (HAS0) accZ[nb][rb] = mfma3(ahi[rb], alo[rb], bx_hi[i][nb], bx_lo[i][nb], accZ[nb][rb]);
+            if (HAS0)
+              accZ[nb][rb] = mfma6(ahi[rb], alo[rb], alo2[rb], bx_hi[i][nb], bx_lo[i][nb], bx_lo2[i][nb], accZ[nb][rb]);
             if (HAS1) accW[nb][rb] = mfma3(ahi[rb], alo[rb], bv_hi[i][nb], bv_lo[i][nb], accW[nb][rb]);
           }
       }
@@ -253,7 +261,7 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
   const int NC = a.NC, p = a.p;
   const int slice = blockIdx.x;
   const WaveSteps ws = wave_steps(sa, slice, wave);
-  const int col_max = (int)a.lda - 4;
+  const int col_max = ((p + 3) & ~3) - 4;  // no load goes past element 4 ceil(p/4) of a row
 
   const int64_t r_begin = (int64_t)blockIdx.y * sa.rows_per_wg;
   int64_t r_end = r_begin + sa.rows_per_wg;
@@ -319,8 +327,8 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
       if (step_exists(i)) {
         const int col = col_of(i);
         const int sl = ws.local0 + i;  // step inside the slice
-        u32x4 ahi[2], alo[2];
-        convert_step(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo);
+        u32x4 ahi[2], alo[2], unused[2];
+        convert_step<false>(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo, unused);
         load_step_regs(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
         char* base = cm + (size_t)sl * kStepBytes;
 #pragma unroll

@@ -12,6 +12,9 @@ from parity_utils import TOL_ITERATE, TOL_PRIMITIVE, rel_l2
 
 pytestmark = pytest.mark.gpu
 
+# measured bound of the one known parity miss (see test_admm_sparse_shards_with_unconverged_cg_known_miss)
+KNOWN_MISS_TOL = 2e-2
+
 
 def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -140,6 +143,7 @@ def test_admm_residual_balancing(case):
     X0 = np.zeros_like(w.X0)
     # the sparse shards with a penalty of 1e-3 are ill-conditioned: 8 CG iterations leave the Newton directions far from
     # converged and float32 rounding then shows at several 1e-3 in the iterates, with fixed penalties as well; 30 do not
+    # (the 8-iteration run is kept below, at the tolerance it meets)
     T, Kcg, mu, tau = 2, (30 if w.sparse else 8), 4.0, 2.0
     params = nadmm.make_admm_params(K, nadmm.make_params(T, Kcg, w.max_ls, 0.0, 0.0, w.beta, w.gamma),
                                     penalty_rule=1, rb_mu=mu, rb_tau=tau)
@@ -161,3 +165,31 @@ def test_admm_residual_balancing(case):
     assert st["r_trace"] == pytest.approx([h["r_norm"] for h in hist], rel=5e-3)
     assert st["d_trace"] == pytest.approx([h["d_norm"] for h in hist], rel=5e-3)
     np.testing.assert_allclose(host(u).sum(0), lam * host(z), atol=1e-5 * max(1.0, float(np.abs(host(u)).max())))
+
+
+def test_admm_sparse_shards_with_unconverged_cg_known_miss():
+    """KNOWN PARITY MISS, kept at the tolerance it meets: the sparse shards of the balancing test with a penalty of 1e-3 and
+    only 8 CG iterations per Newton iteration.  The local Hessians are ill-conditioned (condition number about
+    ||A_i||^2 s / rho), 8 iterations leave CG far from converged, and the float32 rounding of the Hessian-vector products
+    is then amplified into the iterates: they agree with the float64 oracle to several 1e-3, not to the 1e-3 of the
+    north star.  The penalty history and the residuals still agree."""
+    w, N, rhos, lam, K = workloads.sparse_generic(1500, 600, 4, 30, seed=43), 3, [1e-3, 1e-3, 1e-3], 1e-3, 8
+    s = 1.0 / w.n
+    bounds = np.linspace(0, w.n, N + 1).astype(int)
+    gps, ops = [], []
+    for i in range(N):
+        A, b = w.A[bounds[i]:bounds[i + 1]], w.b[bounds[i]:bounds[i + 1]]
+        gps.append(nadmm.Problem(nadmm.SparseA.from_scipy(A, A.tocsc()), dev(b), w.C, s, 0.0, float(rhos[i]), None, None))
+        ops.append(orc.Problem(A, b, w.C, s=s))
+    X0 = np.zeros_like(w.X0)
+    T, Kcg, mu, tau = 2, 8, 4.0, 2.0
+    params = nadmm.make_admm_params(K, nadmm.make_params(T, Kcg, w.max_ls, 0.0, 0.0, w.beta, w.gamma),
+                                    penalty_rule=1, rb_mu=mu, rb_tau=tau)
+    x = dev(np.stack([X0] * N))
+    z, u, st = nadmm.nadmm_admm_solve(gps, lam, x, params)
+    z_ref, xs_ref, ys_ref, hist = adm.admm(ops, lam, rhos, X0, K, T, Kcg, 0.0, 0.0, w.beta, w.gamma, w.max_ls,
+                                           penalty_rule=1, rb_mu=mu, rb_tau=tau)
+    errs = [rel_l2(host(z), z_ref)] + [rel_l2(host(x)[i], xs_ref[i]) for i in range(N)]
+    print(f"admm sparse shards, 8 CG iterations: relative L2 errors of z and the x_i: {[f'{e:.2e}' for e in errs]}", flush=True)
+    assert st["rho_scale_trace"] == [h["rho_scale"] for h in hist]
+    assert max(errs) <= KNOWN_MISS_TOL
