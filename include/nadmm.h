@@ -60,7 +60,8 @@ typedef enum nadmm_status {
                               beta or gamma outside (0,1), negative iteration limits, nnz<0 */
   NADMM_EWORKSPACE = -2,   /* workspace missing, misaligned or too small */
   NADMM_EUNSUPPORTED = -3, /* shape outside the compiled range (C-1 > 32, max_ls > 62, n > 2^36 (sparse: 2^31 - 1), p (C-1) > 2^28) */
-  NADMM_EHIP = -4          /* a HIP call or kernel launch failed */
+  NADMM_EHIP = -4,         /* a HIP call or kernel launch failed */
+  NADMM_ESCRATCH = -5      /* nadmm_hessvec_static: the problem needs more scratch than the built-in buffer holds */
 } nadmm_status;
 
 #define NADMM_MAX_FREE_CLASSES 32   /* largest supported C-1 */
@@ -133,7 +134,8 @@ typedef struct nadmm_stats {
   double  grad_norm[NADMM_TRACE_LEN]; /* ||g|| at the start of each iteration */
 } nadmm_stats;
 
-/* 100 * major + minor; 102: sparse storage of A, residual balancing (struct layouts changed since 100) */
+/* 100 * major + minor; 102: sparse storage of A, residual balancing (struct layouts changed since 100);
+ * 103: nadmm_hessvec_static */
 int         nadmm_version(void);
 const char* nadmm_status_string(int code);
 
@@ -163,6 +165,27 @@ int nadmm_loss_grad(const nadmm_problem* prob, const float* d_X, double* d_loss,
  */
 int nadmm_hessvec(const nadmm_problem* prob, const float* d_X, const float* d_V, float* d_HV,
                   void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * nadmm_hessvec for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels and
+ * same results as nadmm_hessvec, but the scratch memory (rows of D, per-workgroup partial sums, partial
+ * logits of the column-sliced path, the sparse path's packed operand and windows) is a buffer built into
+ * the library: NADMM_STATIC_SCRATCH_BYTES = 32 MiB of device memory that every GPU the library runs on
+ * holds until the process ends.  The call allocates and frees nothing and does not synchronise.
+ *   - A problem that needs more (nadmm_hessvec_static_bytes(prob) > nadmm_static_scratch_bytes(); e.g.
+ *     n (C-1) beyond about 2 M with dense A) is rejected with NADMM_ESCRATCH before anything is enqueued.
+ *     The headline shape 60000 x 784, C = 10 needs 18 MB (the size covers every kernel path that
+ *     nadmm_set_kernel_path could select for the shape), 50000 x 3072, C = 10 needs 24 MB.
+ *   - Every call on one GPU shares that GPU's buffer, whatever the stream or thread: calls that overlap
+ *     in time on one GPU race.  Order them on one stream (or with events).  Nothing in the buffer has to
+ *     survive between calls and nothing has to start at zero.
+ *   - The device that is current at the call is the one whose buffer is used; d_* pointers must belong to it.
+ */
+#define NADMM_STATIC_SCRATCH_BYTES (32u << 20)
+size_t nadmm_static_scratch_bytes(void);                          /* size of the built-in buffer (host-only) */
+size_t nadmm_hessvec_static_bytes(const nadmm_problem* prob);     /* what this problem would need; 0 if invalid */
+int nadmm_hessvec_static(const nadmm_problem* prob, const float* d_X, const float* d_V, float* d_HV, void* stream);
 
 /*
  * Conjugate gradients on H(X) p = -g with early stopping (eq. inexact):

@@ -4,9 +4,15 @@
 // the device except the final copy of the statistics.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <string>
 
 #include "nadmm_internal.h"
+
+// Built-in workspace of nadmm_hessvec_static: every device that loads the library holds its own copy until the
+// process ends.  Host code never passes this name to a kernel; it asks the runtime for the copy's address on the
+// current device (scratch_on_current_device) and uses that pointer.
+static __device__ __align__(256) unsigned char scratch[NADMM_STATIC_SCRATCH_BYTES];
 
 namespace nadmm {
 namespace {
@@ -53,7 +59,9 @@ int validate_problem(const nadmm_problem* p, bool need_labels) {
   return NADMM_OK;
 }
 
-void make_layout(const nadmm_problem* p, Layout* L) {
+// hv_only: only the regions that a stand-alone Hessian-vector product touches (rows of D, partial sums, partial
+// logits, the sparse path's packed operand and windows); the other offsets are then not to be used.
+void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false) {
   Shape s;
   s.n = p->n;
   s.p = p->p;
@@ -69,19 +77,20 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   L->fused_parts = L->fused_ok ? fused_num_partials(s) : 0;
   L->thin_ok = !L->sparse && thin_supported(s, p->lda, p->d_A);
   L->thin_parts = L->thin_ok ? thin_num_partials(s) : 0;
-  const size_t vec = align256((size_t)s.d * sizeof(float));
+  const size_t vec = hv_only ? 0 : align256((size_t)s.d * sizeof(float));
   const size_t rows = align256((size_t)s.n * s.NC * sizeof(float));
+  const size_t rows_solver = hv_only ? 0 : rows;
   size_t off = 0;
-  L->state = off; off += align256(sizeof(DevState));
+  L->state = off; off += hv_only ? 0 : align256(sizeof(DevState));
   L->g = off; off += vec;
   L->pdir = off; off += vec;
   L->r = off; off += vec;
   L->dvec = off; off += vec;
   L->q = off; off += vec;
   L->drows = off; off += rows;
-  L->pcache = off; off += rows;
-  L->zx = off; off += rows;
-  L->zp = off; off += rows;
+  L->pcache = off; off += rows_solver;
+  L->zx = off; off += rows_solver;
+  L->zp = off; off += rows_solver;
   L->sliced_ok = !L->sparse && sliced_supported(s, p->lda, p->d_A);
   L->sliced_parts = 0;
   if (L->sliced_ok) {
@@ -94,10 +103,10 @@ void make_layout(const nadmm_problem* p, Layout* L) {
   L->partial = off; off += align256((size_t)parts * s.d * sizeof(float));
   int lblocks = L->gen_row_blocks > L->fused_parts ? L->gen_row_blocks : L->fused_parts;
   if (L->thin_parts > lblocks) lblocks = L->thin_parts;
-  L->loss_part = off; off += align256((size_t)lblocks * sizeof(double));
-  L->lpart = off; off += align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
-  L->dotpart = off; off += align256((size_t)2 * reduce_out_blocks(s.d) * sizeof(double));  // two sums per workgroup
-  L->rrpart = off; off += align256((size_t)cg_update_blocks(s.d) * sizeof(double));
+  L->loss_part = off; off += hv_only ? 0 : align256((size_t)lblocks * sizeof(double));
+  L->lpart = off; off += hv_only ? 0 : align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
+  L->dotpart = off; off += hv_only ? 0 : align256((size_t)2 * reduce_out_blocks(s.d) * sizeof(double));  // two sums per workgroup
+  L->rrpart = off; off += hv_only ? 0 : align256((size_t)cg_update_blocks(s.d) * sizeof(double));
   // per-slice partial logits of the column-sliced path; the logits [Z | W] of the sparse path
   L->zw = off; off += align256(L->sliced_ok ? sliced_zw_bytes(s) : (L->sparse ? (size_t)s.n * 2 * s.NC * sizeof(float) : 0));
   L->pack = off;
@@ -134,6 +143,26 @@ int hip_fail(hipError_t e) {
     hipError_t e_ = (expr);                      \
     if (e_ != hipSuccess) return hip_fail(e_);   \
   } while (0)
+
+// Address of the built-in scratch array on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+int scratch_on_current_device(void** out) {
+  int dev = -1;
+  NADMM_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return NADMM_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    NADMM_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (ptr == nullptr || ((uintptr_t)ptr & 255) != 0) return NADMM_EWORKSPACE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return NADMM_OK;
+}
 
 // 1 = two-pass vector kernels, 2 = fused single pass (matrix cores), 3 = thin-data single pass,
 // 4 = column-sliced two-sweep matrix-core path, 5 = sparse storage
@@ -532,7 +561,7 @@ static int admm_layout(const nadmm_problem* w, int32_t N, AdmmLayout* AL, int64_
 
 extern "C" {
 
-int nadmm_version(void) { return 102; }
+int nadmm_version(void) { return 103; }
 
 const char* nadmm_status_string(int code) {
   switch (code) {
@@ -541,6 +570,7 @@ const char* nadmm_status_string(int code) {
     case NADMM_EWORKSPACE: return "workspace missing, misaligned or too small";
     case NADMM_EUNSUPPORTED: return "shape or parameter outside the supported range";
     case NADMM_EHIP: return "HIP runtime error";
+    case NADMM_ESCRATCH: return "problem needs more scratch memory than the library's built-in buffer holds";
     default: return "unknown status";
   }
 }
@@ -629,6 +659,30 @@ int nadmm_hessvec(const nadmm_problem* prob, const float* d_X, const float* d_V,
   if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
   if (path == 5 && (rc = sparse_plan(prob, L, d_ws, (hipStream_t)stream)) != NADMM_OK) return rc;
   return hv_apply(prob, L, path, d_ws, d_X, false, d_V, d_HV, nullptr, nullptr, nullptr, (hipStream_t)stream);
+}
+
+size_t nadmm_static_scratch_bytes(void) { return NADMM_STATIC_SCRATCH_BYTES; }
+
+size_t nadmm_hessvec_static_bytes(const nadmm_problem* prob) {
+  if (validate_problem(prob, false) != NADMM_OK) return 0;
+  Layout L;
+  make_layout(prob, &L, true);
+  return L.total;
+}
+
+int nadmm_hessvec_static(const nadmm_problem* prob, const float* d_X, const float* d_V, float* d_HV, void* stream) {
+  int rc = validate_problem(prob, false);
+  if (rc != NADMM_OK) return rc;
+  if (d_X == nullptr || d_V == nullptr || d_HV == nullptr) return NADMM_EINVAL;
+  Layout L;
+  make_layout(prob, &L, true);
+  if (L.total > (size_t)NADMM_STATIC_SCRATCH_BYTES) return NADMM_ESCRATCH;  // before any device call: host-testable
+  int path = 0;
+  if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
+  void* ws = nullptr;
+  if ((rc = scratch_on_current_device(&ws)) != NADMM_OK) return rc;
+  if (path == 5 && (rc = sparse_plan(prob, L, ws, (hipStream_t)stream)) != NADMM_OK) return rc;
+  return hv_apply(prob, L, path, ws, d_X, false, d_V, d_HV, nullptr, nullptr, nullptr, (hipStream_t)stream);
 }
 
 int nadmm_cg_solve(const nadmm_problem* prob, const float* d_X, const float* d_g, float* d_p, int max_iter,

@@ -17,7 +17,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("NADMM_LIB", os.path.join(_HERE, "libnadmm.so"))  # NADMM_LIB: alternative build of the same library
 
-NADMM_OK, NADMM_EINVAL, NADMM_EWORKSPACE, NADMM_EUNSUPPORTED, NADMM_EHIP = 0, -1, -2, -3, -4
+NADMM_OK, NADMM_EINVAL, NADMM_EWORKSPACE, NADMM_EUNSUPPORTED, NADMM_EHIP, NADMM_ESCRATCH = 0, -1, -2, -3, -4, -5
 NADMM_TRACE_LEN = 64
 NADMM_MAX_LS = 62
 NADMM_MAX_FREE_CLASSES = 32
@@ -124,6 +124,11 @@ def lib():
     L.nadmm_workspace_bytes.argtypes = [PP, PR]
     L.nadmm_loss_grad.argtypes = [PP, vp, vp, vp, vp, sz, vp]
     L.nadmm_hessvec.argtypes = [PP, vp, vp, vp, vp, sz, vp]
+    L.nadmm_static_scratch_bytes.restype = sz
+    L.nadmm_static_scratch_bytes.argtypes = []
+    L.nadmm_hessvec_static_bytes.restype = sz
+    L.nadmm_hessvec_static_bytes.argtypes = [PP]
+    L.nadmm_hessvec_static.argtypes = [PP, vp, vp, vp, vp]
     L.nadmm_cg_solve.argtypes = [PP, vp, vp, vp, C.c_int, C.c_float, vp, vp, vp, sz, vp]
     L.nadmm_line_search.argtypes = [PP, vp, vp, vp, C.c_double, C.c_float, C.c_float, C.c_int, vp, vp, vp, vp, sz, vp]
     L.nadmm_local_newton.argtypes = [PP, vp, PR, PS, vp, sz, vp]
@@ -135,7 +140,7 @@ def lib():
     L.nadmm_admm_solve.argtypes = [PP, C.c_int32, C.c_float, vp, vp, vp, PA, PAS, vp, sz, vp]
     L.nadmm_set_kernel_path.argtypes = [C.c_int]
     L.nadmm_query_kernel_path.argtypes = [PP]
-    for f in (L.nadmm_loss_grad, L.nadmm_hessvec, L.nadmm_cg_solve, L.nadmm_line_search, L.nadmm_local_newton,
+    for f in (L.nadmm_loss_grad, L.nadmm_hessvec, L.nadmm_hessvec_static, L.nadmm_cg_solve, L.nadmm_line_search, L.nadmm_local_newton,
               L.nadmm_set_kernel_path, L.nadmm_query_kernel_path, L.nadmm_admm_consensus, L.nadmm_admm_solve):
         f.restype = C.c_int
     _lib = L
@@ -258,6 +263,20 @@ def nadmm_hessvec(prob: Problem, X: torch.Tensor, V: torch.Tensor, out=None, ws=
     out = prob.vec() if out is None else out
     _check(lib().nadmm_hessvec(C.byref(prob.c), _ptr(X), _ptr(V), _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
     return out
+
+
+def nadmm_hessvec_static(prob: Problem, X: torch.Tensor, V: torch.Tensor, out: torch.Tensor, stream=None):
+    """nadmm_hessvec on the library's built-in scratch buffer; `out` is the caller's (nothing is allocated here)."""
+    _check(lib().nadmm_hessvec_static(C.byref(prob.c), _ptr(X), _ptr(V), _ptr(out), _stream(stream)))
+    return out
+
+
+def nadmm_static_scratch_bytes() -> int:
+    return int(lib().nadmm_static_scratch_bytes())
+
+
+def nadmm_hessvec_static_bytes(prob: Problem) -> int:
+    return int(lib().nadmm_hessvec_static_bytes(C.byref(prob.c)))
 
 
 def nadmm_cg_solve(prob: Problem, X: torch.Tensor, g: torch.Tensor, max_iter: int, tol: float, out=None, ws=None,

@@ -197,6 +197,25 @@ def test_kernel_path_switch(lib):
     lib.nadmm_set_kernel_path(prev)
 
 
+def test_static_scratch_entry_point_validates_on_the_host(lib):
+    """nadmm_hessvec_static rejects invalid arguments and problems beyond its built-in buffer before any device call."""
+    fake = C.c_void_p(0x3000)
+    cap = lib.nadmm_static_scratch_bytes()
+    assert cap == 32 << 20
+    head = fake_problem(n=60000, p=784, Cc=10)
+    assert 0 < lib.nadmm_hessvec_static_bytes(C.byref(head)) < 20 << 20           # the headline shape fits
+    assert lib.nadmm_hessvec_static_bytes(C.byref(head)) < lib.nadmm_workspace_bytes(C.byref(head), None)
+    assert lib.nadmm_hessvec_static(C.byref(head), None, fake, fake, None) == nadmm.NADMM_EINVAL
+    assert lib.nadmm_hessvec_static(C.byref(head), fake, fake, None, None) == nadmm.NADMM_EINVAL
+    big = fake_problem(n=250000, p=2000, Cc=20)                                     # 146 MB of scratch
+    assert lib.nadmm_hessvec_static_bytes(C.byref(big)) > cap
+    assert lib.nadmm_hessvec_static(C.byref(big), fake, fake, fake, None) == nadmm.NADMM_ESCRATCH
+    assert b"built-in" in lib.nadmm_status_string(nadmm.NADMM_ESCRATCH)
+    bad = fake_problem(n=0, p=784, Cc=10)
+    assert lib.nadmm_hessvec_static_bytes(C.byref(bad)) == 0
+    assert lib.nadmm_hessvec_static(C.byref(bad), fake, fake, fake, None) == nadmm.NADMM_EINVAL
+
+
 def test_product_path_does_not_import_the_oracle():
     code = ("import sys; sys.path.insert(0, %r); import paper_1807_07132_amd.nadmm, paper_1807_07132_amd.workloads;"
             "assert not any(m == 'oracle' or m.startswith('oracle.') for m in sys.modules)" % ROOT)

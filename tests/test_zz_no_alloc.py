@@ -1,0 +1,71 @@
+"""nadmm_hessvec_static: the Hessian-vector product on the library's built-in scratch buffer (for callers that cannot
+allocate) against nadmm_hessvec with a caller-allocated workspace and against the float64 oracle.  Two calls in a row,
+the second on a smaller problem, on every kernel path; this file is collected last so that the rest of the suite has
+already run in the same process when it does, and it passes in a fresh process too."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import nadmm_oracle as orc
+from paper_1807_07132_amd import nadmm, workloads
+from parity_utils import TOL_PRIMITIVE, oracle_problem, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+PAIRS = {
+    # kernel path: (larger problem, smaller problem run right after it on the same buffer)
+    "fused": (lambda: workloads.image_like(0, n=9000), lambda: workloads.generic(700, 100, 7, seed=12), 2),
+    "thin": (lambda: workloads.tall_binary(0, n=60011), lambda: workloads.generic(300, 12, 4, seed=19), 3),
+    "sliced": (lambda: workloads.wide(0, n=2100), lambda: workloads.generic(300, 1100, 4, seed=25, x_std=0.05), 4),
+    "vector": (lambda: workloads.generic(1237, 45, 5, seed=3), lambda: workloads.generic(65, 33, 3, seed=10), 1),
+    "sparse": (lambda: workloads.sparse_generic(800, 1500, 6, 25, seed=1), lambda: workloads.sparse_generic(200, 300, 4, 10, seed=2), 5),
+}
+
+
+@pytest.mark.parametrize("name", list(PAIRS))
+def test_static_scratch_matches_the_workspace_call(name):
+    big, small, path = PAIRS[name]
+    nadmm.nadmm_set_kernel_path(0)
+    outs = []
+    for make in (big, small, big):         # larger, smaller, larger again: stale contents of the buffer must not matter
+        w = make()
+        gp = nadmm.Problem.from_workload(w)
+        assert nadmm.nadmm_query_kernel_path(gp) == path
+        assert 0 < nadmm.nadmm_hessvec_static_bytes(gp) <= nadmm.nadmm_static_scratch_bytes()
+        X, V = dev(w.X0), dev(w.V)
+        want = nadmm.nadmm_hessvec(gp, X, V)
+        got = torch.full_like(want, float("nan"))
+        nadmm.nadmm_hessvec_static(gp, X, V, got)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want)       # same kernels in the same order: bit for bit
+        assert rel_l2(got.cpu().numpy(), orc.hessvec(oracle_problem(w), w.X0, w.V)) <= TOL_PRIMITIVE
+        outs.append(got)
+    assert torch.equal(outs[0], outs[2])
+
+
+def test_static_scratch_at_the_headline_shape_and_rejection_beyond_the_buffer():
+    w = workloads.image_like(0)
+    gp = nadmm.Problem.from_workload(w)
+    nadmm.nadmm_set_kernel_path(0)
+    assert nadmm.nadmm_hessvec_static_bytes(gp) < 20 << 20
+    X, V = dev(w.X0), dev(w.V)
+    want = nadmm.nadmm_hessvec(gp, X, V)
+    got = torch.empty_like(want)
+    before = torch.cuda.memory_allocated()
+    for _ in range(3):
+        nadmm.nadmm_hessvec_static(gp, X, V, got)
+    torch.cuda.synchronize()
+    assert torch.cuda.memory_allocated() == before
+    assert torch.equal(got, want)
+    # a share whose rows of D alone exceed the buffer: rejected on the host, nothing enqueued
+    n_big = nadmm.nadmm_static_scratch_bytes() // (4 * 9) + 1
+    fake = nadmm.Problem(gp.A, gp.labels, w.C, w.s, w.lam, w.rho, gp.z, gp.y)
+    fake.c.n = n_big
+    with pytest.raises(nadmm.NadmmError) as ei:
+        nadmm.nadmm_hessvec_static(fake, X, V, got)
+    assert ei.value.code == nadmm.NADMM_ESCRATCH
