@@ -114,9 +114,13 @@ __global__ __launch_bounds__(kRowsPerBlock) void rows_kernel(const RowArgs a) {
   const bool has0 = a.B0 != nullptr;
   const bool has1 = a.B1 != nullptr;
 
+  // The logits Z are summed in float32 over one column tile (32 terms) and the tile sums in float64: exp()
+  // turns the absolute error of a logit into a relative error of the probabilities (Section 2.2), and a
+  // float32 sum over thousands of columns would carry 1e-4 at logits of a few hundred.
   float z[NCP], w[NCP];
+  double zd[NCP];
 #pragma unroll
-  for (int c = 0; c < NCP; ++c) { z[c] = 0.f; w[c] = 0.f; }
+  for (int c = 0; c < NCP; ++c) { z[c] = 0.f; w[c] = 0.f; zd[c] = 0.0; }
 
   const int lr = lane >> 5, lc = lane & 31;
   for (int j0 = 0; j0 < a.p; j0 += kTileCols) {
@@ -148,6 +152,14 @@ __global__ __launch_bounds__(kRowsPerBlock) void rows_kernel(const RowArgs a) {
           if (c < NC) w[c] = fmaf(av, v[c], w[c]);
       }
     }
+    if (has0) {
+#pragma unroll
+      for (int c = 0; c < NCP; ++c) { zd[c] += (double)z[c]; z[c] = 0.f; }
+    }
+  }
+  if (has0) {
+#pragma unroll
+    for (int c = 0; c < NCP; ++c) z[c] = (float)zd[c];
   }
 
   const bool valid = row < a.n;
