@@ -50,12 +50,15 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   if (a.flag != nullptr && *a.flag == 0) return;
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int steps = fa.steps;
-  char* cm = lds;                                                  // steps x 4 KB, step s owned by wave s % 8
+  char* cm = lds;                                                  // steps x 4 KB, every step slot private to the wave that owns the step
   float* part = reinterpret_cast<float*>(lds + (size_t)steps * kStepBytes);  // [wave][quad][comp][lane]
   float* dbuf = part + kPartBytes / 4;                             // [e][lane]
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // The slots of one wave's steps (s = wave, wave + 8, ...) lie back to back, so that the slot of step slot i is a
+  // compile-time offset from one per-wave base and needs no address arithmetic per tile.
+  char* cmw = cm + (size_t)(wave * (steps >> 3) + (wave < (steps & 7) ? wave : (steps & 7))) * kStepBytes;
   const int m = lane & 15;   // phase 1: row within the row block; rows stage / phase 2: class or column
   const int kg = lane >> 4;  // k-group of the MFMA operands
   const int NC = a.NC;
@@ -132,6 +135,17 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     split8(v, bv_hi[i], bv_lo[i]);
   }
 
+  u32x4 dhi, dlo;  // D of the current tile as MFMA operand
+  auto phase2_step = [&](int i) {  // out^T[:, step] += D^T (tile held in this step's LDS slot)
+    const char* base = cmw + i * kStepBytes;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int off = cm_offset(16 * h + m, kg);
+      const u32x4 thi = *reinterpret_cast<const u32x4*>(base + off);
+      const u32x4 tlo = *reinterpret_cast<const u32x4*>(base + 2048 + off);
+      acc2[i][h] = mfma3(dhi, dlo, thi, tlo, acc2[i][h]);
+    }
+  };
   for (int64_t row0 = r_begin; row0 < r_end; row0 += kTileRows) {
     // the row this wave handles in the rows stage: e = wave, row = row0 + 4 kg + (e & 3) + 16 (e >> 2)
     const int64_t my_row = row0 + 4 * kg + (wave & 3) + ((wave >> 2) << 4);
@@ -169,23 +183,36 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
             }
           }
         }
-        u32x4 ahi[2], alo[2];
+        // Both row blocks are converted first and the products are issued term by term across the (up to four)
+        // accumulators, so that consecutive MFMAs never depend on each other.
+        u32x4 ahi[2], alo[2], alo2[2];
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
-          if (has0) {
-            u32x4 alo2;
-            split8_3(av[rb], ahi[rb], alo[rb], alo2);
-            accZ[rb] = mfma6(ahi[rb], alo[rb], alo2, bx_hi[i], bx_lo[i], bx_lo2[i], accZ[rb]);
-          } else {
-            split8(av[rb], ahi[rb], alo[rb]);
+          if (has0) split8_3(av[rb], ahi[rb], alo[rb], alo2[rb]);
+          else split8(av[rb], ahi[rb], alo[rb]);
+        }
+        if (has0) {  // the three smallest of the six terms of Z (see mfma6)
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb) accZ[rb] = mfma(alo2[rb], bx_hi[i], accZ[rb]);
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb) accZ[rb] = mfma(ahi[rb], bx_lo2[i], accZ[rb]);
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb) accZ[rb] = mfma(alo[rb], bx_lo[i], accZ[rb]);
+        }
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {  // lo * hi, hi * lo, hi * hi of Z and W
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb) {
+            const u32x4 aa = t == 0 ? alo[rb] : ahi[rb];
+            if (has0) accZ[rb] = mfma(aa, t == 1 ? bx_lo[i] : bx_hi[i], accZ[rb]);
+            if (has1) accW[rb] = mfma(aa, t == 1 ? bv_lo[i] : bv_hi[i], accW[rb]);
           }
-          if (has1) accW[rb] = mfma3(ahi[rb], alo[rb], bv_hi[i], bv_lo[i], accW[rb]);
         }
         // the registers are free again: prefetch the next tile (past the range the rows clamp to the last row)
         load_step(i, row0 + kTileRows);
         if (with_cols) {
           // transposed copy for phase 2: pair (row m, row m+16) of one column per 32-bit word
-          char* base = cm + (size_t)s * kStepBytes;
+          char* base = cmw + i * kStepBytes;
 #pragma unroll
           for (int c = 0; c < 8; ++c) {
             const unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
@@ -259,7 +286,6 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     tile_barrier();
 
     // ---------------- phase 2 ----------------
-    u32x4 dhi, dlo;
     {
       unsigned h[4], l[4];
 #pragma unroll
@@ -272,38 +298,47 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
       dlo = u32x4{l[0], l[1], l[2], l[3]};
     }
 #pragma unroll
-    for (int i = 0; i < SPW; ++i) {
-      const int s = wave + kWaves * i;
-      if (step_exists(i)) {
-        const char* base = cm + (size_t)s * kStepBytes;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const int off = cm_offset(16 * h + m, kg);
-          const u32x4 thi = *reinterpret_cast<const u32x4*>(base + off);
-          const u32x4 tlo = *reinterpret_cast<const u32x4*>(base + 2048 + off);
-          acc2[i][h] = mfma3(dhi, dlo, thi, tlo, acc2[i][h]);
-        }
-      }
-    }
+    for (int i = 0; i < SPW; ++i)
+      if (step_exists(i)) phase2_step(i);
   }
 
   // ---- epilogue: per-workgroup partial of A^T rows, and the partial loss ----
+  // The 32 columns of a step are one contiguous run of 32 (C-1) floats of the partial: each wave lays its steps
+  // out in that order in its own (now idle) LDS step slots and writes them with 16-byte stores, a whole run per
+  // instruction, instead of 4-byte stores scattered at a stride of C-1 floats.
   if (with_cols) {
     float* out = fa.partial + (size_t)blockIdx.x * ((size_t)p * NC);
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
       const int s = wave + kWaves * i;
       if (s < steps) {
+        float* stage = reinterpret_cast<float*>(cmw + i * kStepBytes);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const int j = kStepCols * s + 16 * h + m;
-          if (j < p) {
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int c = 4 * kg + e;
-              if (c < NC) out[(size_t)j * NC + c] = acc2[i][h][e];
-            }
+          for (int e = 0; e < 4; ++e) {
+            const int c = 4 * kg + e;
+            if (c < NC) stage[(16 * h + m) * NC + c] = acc2[i][h][e];
           }
+      }
+    }
+    // LDS operations of one wave execute in order; the slots are private to the wave
+#pragma unroll
+    for (int i = 0; i < SPW; ++i) {
+      const int s = wave + kWaves * i;
+      if (s < steps) {
+        const float* stage = reinterpret_cast<const float*>(cmw + i * kStepBytes);
+        const int cols = p - kStepCols * s < kStepCols ? p - kStepCols * s : kStepCols;
+        const int total = cols * NC;                       // floats of this step's run
+        float* dst = out + (size_t)kStepCols * s * NC;     // 128 (C-1) s bytes into the partial
+        if (((p * NC) & 3) == 0) {                         // every partial starts on a 16-byte boundary
+          const int quads = total >> 2;
+          for (int q = lane; q < quads; q += 64)
+            *reinterpret_cast<float4*>(dst + 4 * q) = *reinterpret_cast<const float4*>(stage + 4 * q);
+          const int tail = total & 3;
+          if (lane < tail) dst[4 * quads + lane] = stage[4 * quads + lane];
+        } else {
+          for (int q = lane; q < total; q += 64) dst[q] = stage[q];
         }
       }
     }
