@@ -25,6 +25,7 @@ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 struct Layout {
   Shape s;
   size_t state, g, pdir, r, dvec, q;
+  size_t pdir2, r2, dvec2, pfinal;  // second vector set and final iterate of the deferred CG update (fused path)
   size_t drows, pcache, zx, zp;
   size_t partial, loss_part, lpart, dotpart, rrpart, zw;
   size_t pack, win_rows, win_cols;  // sparse storage: packed dense operand, windows of the two views
@@ -87,6 +88,10 @@ void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false) {
   L->r = off; off += vec;
   L->dvec = off; off += vec;
   L->q = off; off += vec;
+  L->pdir2 = off; off += L->fused_ok ? vec : 0;
+  L->r2 = off; off += L->fused_ok ? vec : 0;
+  L->dvec2 = off; off += L->fused_ok ? vec : 0;
+  L->pfinal = off; off += L->fused_ok ? vec : 0;
   L->drows = off; off += rows;
   L->pcache = off; off += rows_solver;
   L->zx = off; off += rows_solver;
@@ -216,7 +221,8 @@ int sparse_plan(const nadmm_problem* prob, const Layout& L, void* ws, hipStream_
 
 // One sweep over A: rows pass, and (if with_cols) partial sums of A^T rows_out.
 int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArgs ra, bool with_cols,
-          int* nparts, hipStream_t st) {
+          int* nparts, hipStream_t st, const CgPend* cg = nullptr) {
+  if (cg != nullptr && path != 2) return NADMM_EINVAL;  // the deferred CG update lives in the fused kernel only
   ra.A = prob->d_A;
   ra.n = prob->n;
   ra.p = prob->p;
@@ -268,7 +274,7 @@ int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArg
     return NADMM_OK;
   }
   if (path == 2) {
-    NADMM_HIP(launch_fused(ra, with_cols ? at<float>(ws, L.partial) : nullptr, L.fused_parts, st));
+    NADMM_HIP(launch_fused(ra, with_cols ? at<float>(ws, L.partial) : nullptr, L.fused_parts, st, cg));
     *nparts = L.fused_parts;
     return NADMM_OK;
   }
@@ -342,7 +348,9 @@ int reduce(const nadmm_problem* prob, const Layout& L, void* ws, int nparts, int
 // q = H(X) v.  With X == NULL the probabilities cached in the workspace are used.  With out == NULL only
 // the partial sums of A^T D are formed (*nparts_out of them) and the caller finishes q.
 int hv_apply(const nadmm_problem* prob, const Layout& L, int path, void* ws, const float* X, bool write_pcache,
-             const float* v, float* out, double* dot_part, const int32_t* flag, int* nparts_out, hipStream_t st) {
+             const float* v, float* out, double* dot_part, const int32_t* flag, int* nparts_out, hipStream_t st,
+             const CgPend* cg = nullptr, const int32_t* red_flag = nullptr, const int32_t* cur = nullptr,
+             const float* v_alt = nullptr) {
   RowArgs ra = blank_rows();
   ra.kind = kRowsHv;
   ra.B0 = X;
@@ -352,18 +360,55 @@ int hv_apply(const nadmm_problem* prob, const Layout& L, int path, void* ws, con
   ra.rows_out = at<float>(ws, L.drows);
   ra.flag = flag;
   int nparts = 0;
-  int rc = sweep(prob, L, path, ws, ra, true, &nparts, st);
+  int rc = sweep(prob, L, path, ws, ra, true, &nparts, st, cg);
   if (rc != NADMM_OK) return rc;
   if (nparts_out) *nparts_out = nparts;
   if (out == nullptr) return NADMM_OK;
-  return reduce(prob, L, ws, nparts, 0, v, out, dot_part, flag, st);
+  // deferred CG update: the reduction reads the activity flag and the current vector set that the sweep's
+  // workgroup 0 has just written
+  ReduceArgs r = reduce_args(prob, L, ws, nparts, 0, v, out, dot_part, red_flag != nullptr ? red_flag : flag);
+  r.cur = cur;
+  r.V_alt = v_alt;
+  NADMM_HIP(launch_reduce_out(r, st));
+  return NADMM_OK;
 }
 
-// One CG iteration after the initialisation: q = H d, then the update of p, r, d (Section 2.4).
+// The deferred form of the CG update (fused single-pass path): see CgPend.
+bool cg_deferred(int path) { return path == 2; }
+
+CgPend cg_pend(const Layout& L, void* ws, DevState* ds, int slot_in, bool final_p, float tol) {
+  CgPend c;
+  std::memset(&c, 0, sizeof(c));
+  c.st = ds;
+  c.slot_in = slot_in;
+  c.final_p = final_p ? 1 : 0;
+  c.r[0] = at<float>(ws, L.r); c.r[1] = at<float>(ws, L.r2);
+  c.d[0] = at<float>(ws, L.dvec); c.d[1] = at<float>(ws, L.dvec2);
+  c.p[0] = at<float>(ws, L.pdir); c.p[1] = at<float>(ws, L.pdir2);
+  c.q = at<float>(ws, L.q);
+  c.dot_part = at<double>(ws, L.dotpart);
+  c.ndot = reduce_out_blocks(L.s.d);
+  c.tol = tol;
+  c.p_final = at<float>(ws, L.pfinal);
+  c.dlen = L.s.d;
+  return c;
+}
+
+// CG iteration k after the initialisation: q = H d, then the update of p, r, d (Section 2.4).  On the fused path
+// the update is deferred: iteration k's sweep first applies the update of iteration k - 1 (every workgroup for
+// itself), and the update of the last iteration is applied by whatever consumes the iterate (cg_pend(final_p)).
 int cg_iteration(const nadmm_problem* prob, const Layout& L, int path, void* ws, DevState* ds, const float* X,
-                 bool write_pcache, float tol, hipStream_t st) {
+                 bool write_pcache, float tol, int k, hipStream_t st) {
   float* dvec = at<float>(ws, L.dvec);
   float* q = at<float>(ws, L.q);
+  if (cg_deferred(path)) {
+    double* dot = at<double>(ws, L.dotpart);
+    if (k == 0)  // nothing pending: d is the first direction, state slot 0 as the initialisation left it
+      return hv_apply(prob, L, path, ws, X, write_pcache, dvec, q, dot, &ds->cgs[0].active, nullptr, st);
+    const CgPend c = cg_pend(L, ws, ds, (k - 1) & 1, false, tol);
+    return hv_apply(prob, L, path, ws, nullptr, false, dvec, q, dot, nullptr, nullptr, st, &c, &ds->cgs[k & 1].active,
+                    &ds->cgs[k & 1].cur, at<float>(ws, L.dvec2));
+  }
   CgUpdateArgs cu;
   cu.st = ds;
   cu.pdir = at<float>(ws, L.pdir);
@@ -480,16 +525,24 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
 
     // CG on H p = -g with the probabilities of this iterate
     for (int k = 0; k < params->max_cg; ++k) {
-      if ((rc = cg_iteration(prob, L, path, d_ws, ds, nullptr, false, params->cg_tol, st)) != NADMM_OK) return rc;
+      if ((rc = cg_iteration(prob, L, path, d_ws, ds, nullptr, false, params->cg_tol, k, st)) != NADMM_OK) return rc;
     }
 
-    // Armijo backtracking on Z(alpha) = A X + alpha A p, then X += alpha p
+    // Armijo backtracking on Z(alpha) = A X + alpha A p, then X += alpha p.  With the deferred CG update the sweep
+    // that forms A p applies the last update first and leaves p in its own buffer.
+    const bool pend = cg_deferred(path) && params->max_cg > 0;
+    float* pstep = pend ? at<float>(d_ws, L.pfinal) : pdir;
     RowArgs rz = blank_rows();
     rz.kind = kRowsLogits;
-    rz.B1 = pdir;
+    rz.B1 = pstep;
     rz.Z1out = at<float>(d_ws, L.zp);
     rz.flag = &ds->newton_active;
-    if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st)) != NADMM_OK) return rc;
+    if (pend) {
+      const CgPend c = cg_pend(L, d_ws, ds, (params->max_cg - 1) & 1, true, params->cg_tol);
+      if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st, &c)) != NADMM_OK) return rc;
+    } else if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st)) != NADMM_OK) {
+      return rc;
+    }
 
     LsEvalArgs le;
     std::memset(&le, 0, sizeof(le));
@@ -520,7 +573,7 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     lt.X = d_X;
     lt.z = prob->d_z;
     lt.y = prob->d_y;
-    lt.pdir = pdir;
+    lt.pdir = pstep;
     lt.g = g;
     lt.d = L.s.d;
     lt.X_apply = d_X;
@@ -712,11 +765,13 @@ int nadmm_cg_solve(const nadmm_problem* prob, const float* d_X, const float* d_g
   NADMM_HIP(launch_newton_head(nh, st));
 
   for (int k = 0; k < max_iter; ++k) {
-    if ((rc = cg_iteration(prob, L, path, d_ws, ds, k == 0 ? d_X : nullptr, true, tol, st)) != NADMM_OK) return rc;
+    if ((rc = cg_iteration(prob, L, path, d_ws, ds, k == 0 ? d_X : nullptr, true, tol, k, st)) != NADMM_OK) return rc;
   }
+  const bool pend = cg_deferred(path) && max_iter > 0;
+  if (pend) NADMM_HIP(launch_cg_pending_finish(cg_pend(L, d_ws, ds, (max_iter - 1) & 1, true, tol), st));
   CgFinishArgs cf;
   cf.st = ds;
-  cf.pdir = at<float>(d_ws, L.pdir);
+  cf.pdir = pend ? at<float>(d_ws, L.pfinal) : at<float>(d_ws, L.pdir);
   cf.p_out = d_p;
   cf.d = L.s.d;
   cf.iters_out = d_iters;

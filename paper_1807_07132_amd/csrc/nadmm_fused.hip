@@ -19,6 +19,7 @@
 // (x = hi + lo + O(2^-18 |x|)), and each product uses the three MFMA terms
 // hi*hi + hi*lo + lo*hi with fp32 accumulation (v_mfma_f32_16x16x32_bf16).
 #include "nadmm_internal.h"
+#include "nadmm_cgstep.h"
 #include "nadmm_mfma.h"
 
 namespace nadmm {
@@ -42,9 +43,12 @@ struct FusedArgs {
   float* partial;     // gridDim.x x (p*NC) or NULL (no transpose product)
   int32_t steps;      // ceil(p / 32)
   int32_t rows_per_wg;
+  CgPend cg;          // cg.st != NULL: the operand B1 is the result of a pending CG update (kernels without B0 only)
 };
 
-template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES>
+// HALFQ: the vectors of a pending CG update fit SPW quads per thread (half the capacity): the update then carries
+// no surplus work (a wave issues one instruction per four cycles or so, and every workgroup repeats the update).
+template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES, bool HALFQ = false>
 __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   const RowArgs& a = fa.r;
   if (a.flag != nullptr && *a.flag == 0) return;
@@ -104,15 +108,53 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     }
   };
 
-  if (r_begin < r_end) {
+  auto load_first_tile = [&]() {
+    if (r_begin < r_end) {
 #pragma unroll
-    for (int i = 0; i < SPW; ++i)
-      if (step_exists(i)) load_step(i, r_begin);
-  }
+      for (int i = 0; i < SPW; ++i)
+        if (step_exists(i)) load_step(i, r_begin);
+    }
+  };
+  bool deferred = false;
+  if constexpr (!HAS0 && HAS1) deferred = fa.cg.st != nullptr;
+  if (!deferred) load_first_tile();
 
   // ---- [X|V] operands of this wave's steps, split and packed once (branch-free loads,
   //      issued while the first tile is already on its way) ----
   //      X in three bf16 parts: the logit product is taken to full fp32 accuracy (mfma6)
+  // Deferred CG update: the operand is the new direction (or the final iterate), which every workgroup forms
+  // for itself in LDS (the step slots are idle until the first tile is converted); its loads go out first, the
+  // first tile right behind them.  If CG has stopped there is no product to form.
+  float xop[SPW][8], vop[SPW][8];  // this lane's entries of X and V: rows 32 s + 8 kg + e, class m
+  auto operand_index = [&](int i, int e) {
+    const int j = kStepCols * (wave + kWaves * i) + 8 * kg + e;
+    return (size_t)(j < p ? j : p - 1) * NC + mc;
+  };
+  bool from_lds = false;
+  if constexpr (!HAS0 && HAS1) {
+    if (deferred) {
+      float* vec = reinterpret_cast<float*>(cm);  // p (C-1) floats; 4 p (C-1) <= 128 p bytes of step slots
+      if (!cg_pending_update<kThreads, HALFQ ? SPW : 2 * SPW>(fa.cg, blockIdx.x == 0, vec, reinterpret_cast<double*>(part), load_first_tile))
+        return;
+      // LDS reads proper (a generic pointer would make these flat loads, whose results the compiler can only wait for
+      // together with every outstanding global load, i.e. with the whole first tile)
+#pragma unroll
+      for (int i = 0; i < SPW; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vop[i][e] = vec[operand_index(i, e)];
+      from_lds = true;
+    }
+  }
+  if (!from_lds) {
+#pragma unroll
+    for (int i = 0; i < SPW; ++i)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vop[i][e] = has1 ? a.B1[operand_index(i, e)] : 0.f;
+  }
+#pragma unroll
+  for (int i = 0; i < SPW; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) xop[i][e] = has0 ? a.B0[operand_index(i, e)] : 0.f;
   u32x4 bx_hi[SPW], bx_lo[SPW], bx_lo2[SPW], bv_hi[SPW], bv_lo[SPW];
 #pragma unroll
   for (int i = 0; i < SPW; ++i) {
@@ -120,20 +162,14 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     float x[8], v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const int j = kStepCols * s + 8 * kg + e;
-      const size_t idx = (size_t)(j < p ? j : p - 1) * NC + mc;
-      x[e] = has0 ? a.B0[idx] : 0.f;
-      v[e] = has1 ? a.B1[idx] : 0.f;
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
       const bool ok = cv && (kStepCols * s + 8 * kg + e) < p;
-      x[e] = ok ? x[e] : 0.f;
-      v[e] = ok ? v[e] : 0.f;
+      x[e] = ok ? xop[i][e] : 0.f;
+      v[e] = ok ? vop[i][e] : 0.f;
     }
     split8_3(x, bx_hi[i], bx_lo[i], bx_lo2[i]);
     split8(v, bv_hi[i], bv_lo[i]);
   }
+  if (deferred) lds_barrier();  // every wave has picked its operands from LDS: the step slots may be overwritten
 
   u32x4 dhi, dlo;  // D of the current tile as MFMA operand
   auto phase2_step = [&](int i) {  // out^T[:, step] += D^T (tile held in this step's LDS slot)
@@ -373,12 +409,12 @@ int num_cus() {
 
 int steps_of(int p) { return (p + kStepCols - 1) / kStepCols; }
 
-template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES>
+template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES, bool HALFQ = false>
 hipError_t launch_k(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t st) {
   static uint64_t lds_set = 0;  // per device
-  hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&fused_kernel<SPW, KIND, HAS0, HAS1, STORES>), &lds_set);
+  hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&fused_kernel<SPW, KIND, HAS0, HAS1, STORES, HALFQ>), &lds_set);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((fused_kernel<SPW, KIND, HAS0, HAS1, STORES>), dim3(grid), dim3(kThreads), lds_bytes, st, fa);
+  hipLaunchKernelGGL((fused_kernel<SPW, KIND, HAS0, HAS1, STORES, HALFQ>), dim3(grid), dim3(kThreads), lds_bytes, st, fa);
   return hipGetLastError();
 }
 
@@ -387,8 +423,14 @@ hipError_t launch_k(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t
 template <int SPW, int KIND, bool HAS0, bool HAS1>
 hipError_t launch_one(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t st) {
   const RowArgs& a = fa.r;
-  if (KIND == kRowsLogits || a.Pout != nullptr || a.Z0out != nullptr)
-    return launch_k<SPW, KIND, HAS0, HAS1, true>(fa, grid, lds_bytes, st);
+  const bool stores = KIND == kRowsLogits || a.Pout != nullptr || a.Z0out != nullptr;
+  if constexpr (!HAS0 && HAS1 && (KIND == kRowsHv || KIND == kRowsLogits)) {
+    if (fa.cg.st != nullptr && (fa.cg.dlen >> 2) <= (int64_t)kThreads * SPW) {  // pending CG update on short vectors
+      if (stores) return launch_k<SPW, KIND, HAS0, HAS1, true, true>(fa, grid, lds_bytes, st);
+      return launch_k<SPW, KIND, HAS0, HAS1, false, true>(fa, grid, lds_bytes, st);
+    }
+  }
+  if (stores) return launch_k<SPW, KIND, HAS0, HAS1, true>(fa, grid, lds_bytes, st);
   return launch_k<SPW, KIND, HAS0, HAS1, false>(fa, grid, lds_bytes, st);
 }
 
@@ -434,9 +476,16 @@ int fused_num_partials(const Shape& s) {
   return (int)(g < 1 ? 1 : g);
 }
 
-hipError_t launch_fused(const RowArgs& a, float* partial, int nparts, hipStream_t st) {
+hipError_t launch_fused(const RowArgs& a, float* partial, int nparts, hipStream_t st, const CgPend* cg) {
   FusedArgs fa;
   fa.r = a;
+  if (cg != nullptr) {
+    if (a.B0 != nullptr || a.B1 == nullptr || (a.kind != kRowsHv && a.kind != kRowsLogits)) return hipErrorInvalidValue;
+    if (cg->ndot < 1 || cg->ndot > kThreads || cg->dlen != (int64_t)a.p * a.NC) return hipErrorInvalidValue;
+    fa.cg = *cg;
+  } else {
+    fa.cg = CgPend{};
+  }
   fa.partial = partial;
   fa.steps = steps_of(a.p);
   const int grid = nparts;

@@ -28,6 +28,16 @@ constexpr int kWave = 64;
 constexpr int kMaxCand = NADMM_MAX_LS + 2;  // candidate step sizes 1, gamma, ..., gamma^(max_ls+1)
 constexpr int kCandSlots = kMaxCand + 1;    // + one slot for alpha = 0 (objective at X itself)
 
+// CG state after some number of updates, kept twice: a kernel that applies a pending update reads one copy and
+// its workgroup 0 writes the other, so that no workgroup reads what another one of the same kernel writes.
+struct CgSlot {
+  double rr;        // ||r||^2 of the current residual
+  int32_t active;   // 0 once CG has stopped (tolerance met, no positive curvature, or nothing to solve)
+  int32_t iters;    // updates applied
+  int32_t cur;      // which of the two sets of the vectors r, d, p is current
+  int32_t pad_;
+};
+
 // Device-resident scalars of the Newton / CG / line-search drivers.  Lives at
 // the start of the workspace; written only by single-workgroup tail kernels.
 struct DevState {
@@ -48,6 +58,7 @@ struct DevState {
   float cg_alpha;   //   step length of this CG iteration
   int32_t pad_[3];
   double rr_prev;   //   ||r||^2 before this CG iteration
+  CgSlot cgs[2];    // deferred CG update (fused single-pass path): see CgPend
   nadmm_stats stats;  // copied to the host at the end of nadmm_local_newton
 };
 
@@ -75,6 +86,26 @@ struct RowArgs {
   double* loss_part;   // per-workgroup partial sums of row losses (kinds 1, 2)
   int32_t kind;
   const int32_t* flag; // if non-NULL and *flag == 0 the kernel does nothing
+};
+
+// A CG update (Section 2.4) that has not been applied yet, handed to the kernel that needs its result: the
+// next Hessian-vector sweep needs the new direction d, the sweep after the last CG iteration the iterate p.
+// Every workgroup of that kernel applies the update for itself from q = H d and the partial sums of <d, q>
+// (identical arithmetic in every workgroup, so all of them agree bit for bit, also on whether CG stops);
+// workgroup 0 writes the new vectors to the other set and the new state to the other CgSlot.
+struct CgPend {
+  DevState* st;          // NULL: no deferred update (operands come from RowArgs as usual)
+  int32_t slot_in;       // st->cgs[slot_in] is read, st->cgs[slot_in ^ 1] written
+  int32_t final_p;       // 0: the kernel wants d (Hessian-vector product), 1: it wants p (end of CG)
+  float* r[2];
+  float* d[2];
+  float* p[2];
+  const float* q;        // H d of the update
+  const double* dot_part;
+  int32_t ndot;
+  float tol;
+  float* p_final;        // final_p: workgroup 0 leaves the iterate here and copies the state to the scalars of DevState
+  int64_t dlen;
 };
 
 // Column-pass (transpose product) description: partial[k] = (rows of chunk k of A)^T rows_in
@@ -120,6 +151,8 @@ struct ReduceArgs {
   float lambda, rho;
   const float* rho_scale; // optional device scalar: the penalty is rho * *rho_scale (adaptive penalty of the outer solver)
   float* out;
+  const float* V_alt;     // kind 0, optional with cur: V is V_alt if *cur != 0 (the two vector sets of a deferred CG update)
+  const int32_t* cur;
   double* dot_part;       // kind 0, optional: per-workgroup sums of out[e] * V[e], reduce_out_blocks(d) entries
   double* pen_part;       // kind 1, optional: per-workgroup sums of the penalty terms lambda/2 x^2 + rho/2 (x - z + y/rho)^2
   double* gg_part;        // kind 1, optional: per-workgroup sums of out[e]^2
@@ -276,7 +309,9 @@ int fused_num_partials(const Shape& s);
 // over A; leaves per-workgroup partial sums of A^T rows in `partial`
 // (nparts = fused_num_partials() blocks of d floats) and per-workgroup partial
 // losses in a.loss_part[0 .. nparts).
-hipError_t launch_fused(const RowArgs& a, float* partial, int nparts, hipStream_t st);
+hipError_t launch_fused(const RowArgs& a, float* partial, int nparts, hipStream_t st, const CgPend* cg = nullptr);
+// the pending update alone (one workgroup): end of a stand-alone CG solve
+hipError_t launch_cg_pending_finish(const CgPend& c, hipStream_t st);
 
 // ---- thin-data single-pass path (nadmm_thin.hip): p <= 32, p % 4 == 0, C-1 <= 3, lda == p ----
 bool thin_supported(const Shape& s, int64_t lda, const void* A);

@@ -5,6 +5,7 @@
 // single-workgroup "tail" kernels sum in a fixed order, so results are
 // reproducible bit for bit.
 #include "nadmm_internal.h"
+#include "nadmm_cgstep.h"
 
 namespace nadmm {
 namespace {
@@ -62,7 +63,8 @@ __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
   double prod = 0.0, pen = 0.0;
   if (ok) {
     if (a.kind == 0) {
-      const float v = a.V[e];
+      const float* __restrict__ V = (a.cur != nullptr && *a.cur != 0) ? a.V_alt : a.V;
+      const float v = V[e];
       out = fmaf(a.lambda + rho_, v, out);
       prod = (double)out * (double)v;
     } else {
@@ -239,7 +241,10 @@ __global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs
   const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;  // outer solver: common factor on the penalty
   __shared__ double sm[17];
   DevState* st = a.st;
-  if (a.newton_mode && st->newton_active == 0) return;
+  if (a.newton_mode && st->newton_active == 0) {
+    if (threadIdx.x == 0) st->cgs[0] = CgSlot{0.0, 0, 0, 0, 0};  // a stopped Newton iteration leaves CG inactive
+    return;
+  }
 
   double gg = 0.0;
   if (a.gg_part != nullptr) {
@@ -279,6 +284,9 @@ __global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs
     st->gg_cg = gg;
     st->cg_iters = 0;
     st->cg_active = gg > 0.0 ? 1 : 0;
+    int32_t cg_on = st->cg_active;
+    if (a.newton_mode && (sqrt(gg) < (double)a.grad_tol || !(gg > 0.0))) cg_on = 0;
+    st->cgs[0] = CgSlot{gg, cg_on, 0, 0, 0};
     if (a.newton_mode) {
       const double gn = sqrt(gg);
       st->loss = loss;
@@ -513,6 +521,14 @@ __global__ __launch_bounds__(kTail) void cg_reduce_update_kernel(const ReduceArg
     st->cg_iters += 1;
     if (stop) st->cg_active = 0;
   }
+}
+
+// The pending update of a deferred CG iteration alone (end of a stand-alone CG solve); the iterate is formed in p_final.
+constexpr int kPendThreads = 512;
+constexpr int kPendPer = 8;   // quads per thread: the fused single-pass path has p (C-1) <= 960 * 16 <= 4 * 512 * 8
+__global__ __launch_bounds__(kPendThreads) void cg_pending_finish_kernel(const CgPend c) {
+  __shared__ double sm[kPendThreads / 64 + 1];
+  cg_pending_update<kPendThreads, kPendPer>(c, true, c.p_final, sm, [] {});
 }
 
 __global__ __launch_bounds__(256) void cg_finish_kernel(const CgFinishArgs a) {
@@ -827,6 +843,13 @@ bool cg_fused_tail_supported(int64_t d, int nparts) {
 
 hipError_t launch_cg_reduce_update(const ReduceArgs& r, const CgUpdateArgs& a, hipStream_t st) {
   hipLaunchKernelGGL(cg_reduce_update_kernel, dim3(1), dim3(kTail), 0, st, r, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_cg_pending_finish(const CgPend& c, hipStream_t st) {
+  if (c.st == nullptr || c.final_p == 0 || c.dlen > (int64_t)4 * kPendThreads * kPendPer || c.ndot > kPendThreads || c.ndot < 1)
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(cg_pending_finish_kernel, dim3(1), dim3(kPendThreads), 0, st, c);
   return hipGetLastError();
 }
 
