@@ -222,7 +222,9 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
 /* ------------------------------------------------------------------------------------------------
  * ADMM outer solver with N workers simulated on one GPU (Algorithm 1 with fixed or residual-balanced penalty parameters;
  * Section 2.3: x-, z-, y-updates, closed-form z-update for g(z) = lambda/2 ||z||^2; Section 2.3.1:
- * residuals and stopping).  The workers' local solves run one after the other on the one device.
+ * residuals and stopping).  The workers' local solves of one outer iteration are independent; they are spread over a few
+ * library-owned streams (forked from and joined to the caller's stream with events, created on the first call of a host
+ * thread and kept), every worker on its own part of the workspace, so that they overlap on the one device.
  *
  * Multipliers are kept in the sign convention of nadmm_problem.d_y: u_i = -y_i of the paper, so
  *   z   = sum_i (rho_i x_i + u_i) / (lambda + sum_i rho_i)
@@ -262,7 +264,7 @@ typedef struct nadmm_admm_stats {
 } nadmm_admm_stats;
 
 /*
- * Workspace for nadmm_admm_solve / nadmm_admm_consensus: the largest local workspace of the N
+ * Workspace for nadmm_admm_solve / nadmm_admm_consensus: the local workspaces of the N
  * workers plus the consensus state.  h_workers: host array of N problem descriptions (shards of the
  * rows of A; same p and C).  Returns 0 on invalid arguments.
  */
@@ -282,8 +284,10 @@ int nadmm_admm_consensus(int32_t N, int64_t d, const float* d_x, float* d_u, flo
  * Algorithm 1.  h_workers[i]: shard i (d_A, n, p, lda, d_labels, C, loss_scale, rho = rho_i; its lambda,
  * d_z, d_y are ignored: the local subproblems have no regulariser and use d_z, d_u below).
  * d_x: N x d, x_i^0 on entry, x_i on return.  d_u: N x d (out; zero-initialised by the call), d_z: d (out;
- * zero-initialised).  Everything is enqueued on `stream`; after the residual test has stopped the
- * iteration the remaining kernels are no-ops.  h_stats (host) may be NULL; if not, the stream is
+ * zero-initialised).  Everything is ordered after the work already on `stream` and before work enqueued on it later.
+ * With both tolerances 0 nothing synchronises.  With a residual test the call waits for the stream after every fourth
+ * outer iteration and stops enqueueing once the test has fired (under stream capture it cannot wait: all max_outer
+ * iterations are enqueued and those after the stop are no-ops).  h_stats (host) may be NULL; if not, the stream is
  * synchronised before return.
  */
 int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, float* d_x, float* d_u, float* d_z,

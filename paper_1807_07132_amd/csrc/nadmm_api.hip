@@ -62,7 +62,9 @@ int validate_problem(const nadmm_problem* p, bool need_labels) {
 
 // hv_only: only the regions that a stand-alone Hessian-vector product touches (rows of D, partial sums, partial
 // logits, the sparse path's packed operand and windows); the other offsets are then not to be used.
-void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false) {
+// wg_cap > 0: at most that many workgroups for the fused single-pass kernels (several workers' solves running side by
+// side share the compute units; each then keeps the long row ranges per workgroup that amortise a launch).
+void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg_cap = 0) {
   Shape s;
   s.n = p->n;
   s.p = p->p;
@@ -76,6 +78,7 @@ void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false) {
   if (L->sparse) L->gen_chunks = 1;  // the column view gives every element of A^T D whole
   L->fused_ok = !L->sparse && fused_supported(s, p->lda, p->d_A);
   L->fused_parts = L->fused_ok ? fused_num_partials(s) : 0;
+  if (wg_cap > 0 && L->fused_parts > wg_cap) L->fused_parts = wg_cap;
   L->thin_ok = !L->sparse && thin_supported(s, p->lda, p->d_A);
   L->thin_parts = L->thin_ok ? thin_num_partials(s) : 0;
   const size_t vec = hv_only ? 0 : align256((size_t)s.d * sizeof(float));
@@ -588,27 +591,65 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
 }
 
 struct AdmmLayout {
-  size_t state, part, local, total;
+  size_t state, part, total;
+  size_t local[NADMM_MAX_WORKERS];  // one local workspace per worker: their solves run side by side
+  int wg_cap;
 };
+
+constexpr int kAdmmStreams = 4;  // streams the workers' solves are spread over: the caller's and three internal ones
+                                 // (a process has four hardware queues by default; a fifth stream would share one)
+
+static int admm_wg_cap(int32_t N) {
+  const int lanes = N < kAdmmStreams ? N : kAdmmStreams;
+  return lanes > 1 ? 256 / lanes : 0;
+}
 
 static int admm_layout(const nadmm_problem* w, int32_t N, AdmmLayout* AL, int64_t* d_out) {
   if (w == nullptr || N < 1 || N > NADMM_MAX_WORKERS) return NADMM_EINVAL;
-  size_t local = 0;
+  AL->wg_cap = admm_wg_cap(N);
+  const int64_t d0 = (int64_t)w[0].p * (w[0].C - 1);
+  size_t off = 0;
+  AL->state = off; off += align256(sizeof(AdmmState));
   for (int i = 0; i < N; ++i) {
     int rc = validate_problem(&w[i], true);
     if (rc != NADMM_OK) return rc;
     if (w[i].p != w[0].p || w[i].C != w[0].C) return NADMM_EINVAL;
-    Layout L;
-    make_layout(&w[i], &L);
-    if (L.total > local) local = L.total;
   }
-  const int64_t d = (int64_t)w[0].p * (w[0].C - 1);
-  size_t off = 0;
-  AL->state = off; off += align256(sizeof(AdmmState));
-  AL->part = off; off += align256((size_t)admm_blocks(d) * 5 * sizeof(double));
-  AL->local = off; off += local;
+  AL->part = off; off += align256((size_t)admm_blocks(d0) * 5 * sizeof(double));
+  for (int i = 0; i < N; ++i) {
+    Layout L;
+    make_layout(&w[i], &L, false, AL->wg_cap);
+    AL->local[i] = off;
+    off += align256(L.total);
+  }
   AL->total = off;
-  if (d_out) *d_out = d;
+  if (d_out) *d_out = d0;
+  return NADMM_OK;
+}
+
+// Streams and events of the outer solver, per host thread and device, created on first use and kept.
+struct AdmmLanes {
+  hipStream_t stream[kAdmmStreams];
+  hipEvent_t fork;
+  hipEvent_t join[kAdmmStreams];
+  bool ready;
+};
+
+static int admm_lanes(AdmmLanes** out) {
+  thread_local AdmmLanes lanes[kMaxDevices] = {};
+  int dev = -1;
+  NADMM_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return NADMM_EUNSUPPORTED;
+  AdmmLanes* l = &lanes[dev];
+  if (!l->ready) {
+    for (int i = 1; i < kAdmmStreams; ++i) {  // lane 0 is the caller's stream
+      NADMM_HIP(hipStreamCreateWithFlags(&l->stream[i], hipStreamNonBlocking));  // default priority
+      NADMM_HIP(hipEventCreateWithFlags(&l->join[i], hipEventDisableTiming));
+    }
+    NADMM_HIP(hipEventCreateWithFlags(&l->fork, hipEventDisableTiming));
+    l->ready = true;
+  }
+  *out = l;
   return NADMM_OK;
 }
 
@@ -921,7 +962,6 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
   if (d_ws == nullptr || ((uintptr_t)d_ws & 255) != 0 || ws_bytes < AL.total) return NADMM_EWORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   AdmmState* as = at<AdmmState>(d_ws, AL.state);
-  void* local_ws = at<char>(d_ws, AL.local);
 
   // per-worker subproblems: no local regulariser, consensus variable and multipliers of this call
   nadmm_problem wk[NADMM_MAX_WORKERS];
@@ -934,7 +974,7 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
     wk[i].lambda = 0.f;
     wk[i].d_z = d_z;
     wk[i].d_y = d_u + (size_t)i * d;
-    make_layout(&wk[i], &Ls[i]);
+    make_layout(&wk[i], &Ls[i], false, AL.wg_cap);
     Ls[i].rho_scale = &as->rho_scale;
     if ((rc = choose_path(Ls[i], &paths[i])) != NADMM_OK) return rc;
     ca.rho[i] = wk[i].rho;
@@ -944,14 +984,45 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
   ca.penalty_rule = params->penalty_rule; ca.rb_mu = params->rb_mu; ca.rb_tau = params->rb_tau;
   ca.part = at<double>(d_ws, AL.part);
 
+  // The workers' local solves of one outer iteration are independent: they are spread over a few internal streams
+  // (forked from and joined to the caller's stream with events, each worker on its own workspace), so that their
+  // launch latencies and tails overlap; the consensus step runs on the caller's stream after the join.
+  AdmmLanes* lanes = nullptr;
+  const int nlanes = N < kAdmmStreams ? N : kAdmmStreams;
+  if (nlanes > 1 && (rc = admm_lanes(&lanes)) != NADMM_OK) return rc;
+  // With a residual test the host looks at the stopping flag every few iterations instead of enqueueing max_outer
+  // iterations of no-ops (not while the stream is being captured into a graph, where it cannot wait).
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  NADMM_HIP(hipStreamIsCapturing(st, &cap));
+  const bool poll = (params->eps_abs > 0.f || params->eps_rel > 0.f) && cap == hipStreamCaptureStatusNone;
+  constexpr int kPollEvery = 4;
+
   NADMM_HIP(launch_admm_init(as, d_u, d_z, N, d, st));
   for (int k = 0; k < params->max_outer; ++k) {
+    if (nlanes > 1) {
+      NADMM_HIP(hipEventRecord(lanes->fork, st));
+      for (int l = 1; l < nlanes; ++l) NADMM_HIP(hipStreamWaitEvent(lanes->stream[l], lanes->fork, 0));
+    }
     for (int i = 0; i < N; ++i) {
-      rc = local_newton_enqueue(&wk[i], d_x + (size_t)i * d, &params->local, Ls[i], paths[i], local_ws, &as->active, st);
+      hipStream_t si = (nlanes > 1 && i % nlanes != 0) ? lanes->stream[i % nlanes] : st;
+      rc = local_newton_enqueue(&wk[i], d_x + (size_t)i * d, &params->local, Ls[i], paths[i], at<char>(d_ws, AL.local[i]),
+                                &as->active, si);
       if (rc != NADMM_OK) return rc;
+    }
+    if (nlanes > 1) {
+      for (int l = 1; l < nlanes; ++l) {
+        NADMM_HIP(hipEventRecord(lanes->join[l], lanes->stream[l]));
+        NADMM_HIP(hipStreamWaitEvent(st, lanes->join[l], 0));
+      }
     }
     ca.iter = k;
     NADMM_HIP(launch_admm_consensus(ca, st));
+    if (poll && (k + 1) % kPollEvery == 0 && k + 1 < params->max_outer) {
+      int32_t active = 1;
+      NADMM_HIP(hipMemcpyAsync(&active, &as->active, sizeof(active), hipMemcpyDeviceToHost, st));
+      NADMM_HIP(hipStreamSynchronize(st));
+      if (active == 0) break;
+    }
   }
   if (h_stats != nullptr) {
     NADMM_HIP(hipMemcpyAsync(h_stats, &as->stats, sizeof(nadmm_admm_stats), hipMemcpyDeviceToHost, st));
