@@ -21,15 +21,42 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak, GB/s
 HV_PER_STEP = 100
 LG_PER_STEP = 100
 # HBM bytes per nadmm_hessvec call from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
-# profiles/ (scaled by a plain copy of known size); counters cannot be read inside a timing run.
+# profiles/ (scaled by a plain copy of known size); counters cannot be read inside a timing run.  Every entry
+# names the summary it comes from and the digest of the kernel sources it was measured with: if the sources of
+# that kernel path have changed since, the line reports traffic = null instead of a stale figure.
 MEASURED_HV_TRAFFIC = {
-    ("image_like_60000x784_C10", 2): 207.0e6,
-    ("tall_binary_1375000x28_C2", 3): 154.4e6,
-    ("wide_50000x3072_C10", 4): 1286.5e6,
-    ("large_multiclass_250000x2000_C20", 4): 4435.8e6,
+    ("image_like_60000x784_C10", 2): (207.0e6, "profiles/hessvec_fused_image_like_60000x784_C10.md", ""),
+    ("tall_binary_1375000x28_C2", 3): (154.4e6, "profiles/hessvec_thin_tall_binary_1375000x28_C2.md", ""),
+    ("wide_50000x3072_C10", 4): (1286.5e6, "profiles/hessvec_sliced_wide_50000x3072_C10.md", ""),
+    ("large_multiclass_250000x2000_C20", 4): (4435.8e6, "profiles/hessvec_sliced_large_multiclass_250000x2000_C20.md", ""),
     # sparse storage: bytes between the L2 caches and the memory side, most of them operand rows served by the Infinity Cache
-    ("e18_like_40628x279998_C20_sparse", 5): 12480.0e6,
+    ("e18_like_40628x279998_C20_sparse", 5): (12480.0e6, "profiles/hessvec_sparse_e18_like_40628x279998_C20.md", ""),
 }
+PATH_SOURCES = {1: ["nadmm_generic.hip"], 2: ["nadmm_fused.hip", "nadmm_cgstep.h"], 3: ["nadmm_thin.hip"], 4: ["nadmm_sliced.hip", "nadmm_generic.hip"],
+                5: ["nadmm_sparse.hip", "nadmm_generic.hip"]}
+DTYPE = "f32 data and results; products on bf16 MFMA with split operands (3 terms, 6 for the logits A X), f32 accumulate; f64 scalar sums"
+
+
+def source_digest(path):
+    """Digest of the kernel sources of one kernel path (plus the shared helpers and the reduction)."""
+    import hashlib
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_1807_07132_amd", "csrc")
+    h = hashlib.sha256()
+    for name in PATH_SOURCES[path] + ["nadmm_mfma.h", "nadmm_vec.hip"]:
+        with open(os.path.join(here, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:12]
+
+
+def measured_traffic(name, path):
+    ent = MEASURED_HV_TRAFFIC.get((name, path))
+    if ent is None:
+        return None, None
+    nbytes, profile, digest = ent
+    cur = source_digest(path)
+    if digest != cur:
+        return None, f"{profile} was measured with kernel sources {digest or '(unrecorded)'}; they are {cur} now"
+    return nbytes, f"{profile} (kernel sources {digest})"
 
 
 def parse():
@@ -51,6 +78,8 @@ def parse():
     ap.add_argument("--only", default="", help="comma list of hv,lg,solve: restrict the step (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run 3 plain device copies of A (known size) so that HBM counters can be scaled")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the Hessian-vector timing of the other dense benchmark configurations in extra")
     ap.add_argument("--hv-per-step", type=int, default=HV_PER_STEP)
     ap.add_argument("--lg-per-step", type=int, default=LG_PER_STEP)
     return ap.parse_args()
@@ -79,6 +108,37 @@ def cpu_baseline(w, seconds):
     return {"value": reps / el, "unit": "Hv/s", "cores": min(threads, avail), "kind": "oracle",
             "sample": f"{reps} float64 numpy{'/scipy.sparse' if w.sparse else ''} Hessian-vector products at the "
                       f"full workload shape ({w.n}x{w.p}, C={w.C}) in {el:.1f} s"}
+
+
+def other_configs(nadmm, workloads, torch, np, skip):
+    """Hessian-vector time and HBM fraction of the other dense benchmark configurations (outside the timed steps)."""
+    out = {}
+    for name in ("wide", "tall_binary", "large_multiclass"):
+        if name == skip:
+            continue
+        try:
+            w = workloads.make(name, 0)
+            gp = nadmm.Problem.from_workload(w)
+            ws = gp.workspace()
+            X, V, hv = torch.from_numpy(w.X0).cuda(), torch.from_numpy(w.V).cuda(), gp.vec()
+            reps = 20
+            for _ in range(3):
+                nadmm.nadmm_hessvec(gp, X, V, out=hv, ws=ws)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                nadmm.nadmm_hessvec(gp, X, V, out=hv, ws=ws)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            nbytes = 4.0 * w.n * w.p + 12.0 * w.p * (w.C - 1)
+            out[w.name] = {"hv_us": us, "hv_hbm_frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                           "kernel_path": nadmm.nadmm_query_kernel_path(gp)}
+            del gp, ws, w
+            torch.cuda.empty_cache()
+        except Exception as e:  # never lose the headline line over an extra
+            out[name] = {"error": repr(e)[:200]}
+    return out
 
 
 def main():
@@ -221,7 +281,7 @@ def main():
                 e1.record()
                 torch.cuda.synchronize()
                 runs[name] = {"outer_iterations": st["outer_iters"], "stopped_by_residual_test": st["converged"],
-                              "seconds_with_the_no_op_remainder_of_max_outer": e0.elapsed_time(e1) / 1e3,
+                              "seconds": e0.elapsed_time(e1) / 1e3,
                               "final_penalty_factor": st["rho_scale"]}
             admm["to_tolerance"] = {"eps_abs": eps_abs, "eps_rel": eps_rel, "max_outer": cap, **runs}
         del shards, aws, xw, uw, zw
@@ -245,8 +305,9 @@ def main():
         per_hv_s = tot["hv"] / 1e3 / (args.hv_per_step * args.steps)
         value = 1.0 / per_hv_s
         ach = bytes_hv / per_hv_s / 1e9
+        traffic, traffic_source = measured_traffic(w.name, path)
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                "traffic": MEASURED_HV_TRAFFIC.get((w.name, path)),
+                "traffic": traffic, "traffic_source": traffic_source,
                 "kernel": "Hessian-vector product (all kernels of one nadmm_hessvec call)",
                 "us_per_launch": per_hv_s * 1e6, "algorithmic_bytes": bytes_hv}
         extra["hv_us"] = per_hv_s * 1e6
@@ -254,6 +315,9 @@ def main():
         extra["hv_tflops_useful"] = flops / per_hv_s / 1e12
         extra["hv_frac_fp32_vector_peak"] = flops / per_hv_s / 1e12 / 157.3
         if cold_hv_us is not None:
+            # A fits the Infinity Cache; with two copies used in turn every call has to read its A from HBM
+            roof["us_per_launch_two_copies_of_A"] = cold_hv_us
+            roof["frac_two_copies_of_A"] = bytes_hv / (cold_hv_us * 1e-6) / 1e9 / HBM_PEAK_GBS
             extra["hv_us_two_copies_of_A"] = cold_hv_us
             extra["hv_hbm_frac_two_copies_of_A"] = bytes_hv / (cold_hv_us * 1e-6) / 1e9 / HBM_PEAK_GBS
     if "lg" in tot:
@@ -270,11 +334,15 @@ def main():
 
     if admm is not None:
         extra["admm"] = admm
+    if not only and not args.no_extras and not args.no_other_configs and not w.sparse and args.n is None:
+        del gp, ws
+        torch.cuda.empty_cache()
+        extra["other_configs"] = other_configs(nadmm, workloads, torch, np, args.workload)
     out = {
-        "metric": "Hv products/s (n=60k,p=784,C=10); loss+grad/s and local Newton-CG solve seconds in extra",
+        "metric": f"Hv products/s ({w.name}: n={n}, p={p}, C={w.C}); loss+grad/s and local Newton-CG solve seconds in extra",
         "value": value, "unit": "Hv/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3 / max(args.steps, 1), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": w.name, "n": n, "p": p, "C": w.C, "hv_per_step": args.hv_per_step,
                    "loss_grad_per_step": args.lg_per_step, "newton_iters": w.max_newton, "cg_iters": w.max_cg,
                    "loss_scale": "1/n", "lambda": w.lam, "rho": w.rho},

@@ -239,7 +239,7 @@ struct LsEvalArgs {
   int32_t NC;
   int32_t ncand;           // number of step sizes in alphas[] that are evaluated
   float alphas[kCandSlots];
-  double* lpart;           // nblocks x kCandSlots
+  double* lpart;           // [candidate slot][workgroup], ls_eval_blocks(n) workgroups
   const int32_t* flag;
 };
 int ls_eval_blocks(int64_t n);

@@ -540,59 +540,49 @@ __global__ __launch_bounds__(256) void cg_finish_kernel(const CgFinishArgs a) {
   }
 }
 
-// Row losses at Z = Zx + alpha Zp for all candidate step sizes (Sections 2.1, 2.2); the cached logits are
-// read once per 16 candidates.
+// Row losses at Z = Zx + alpha Zp for all candidate step sizes (Sections 2.1, 2.2).  One thread per (row, candidate):
+// a workgroup is 16 rows x 16 candidate slots, the 16 threads of a row read the same cached logits (one broadcast
+// load per wave and address), and a row costs a thread one log-sum-exp instead of one per candidate, so that a compute
+// unit holds many short threads instead of a few long ones.  More than 16 candidates take further passes.
 template <int NCP>
 __global__ __launch_bounds__(256) void ls_eval_kernel(const LsEvalArgs a) {
   if (a.flag != nullptr && *a.flag == 0) return;
-  __shared__ double sm[17];
+  __shared__ double sm[4][16];
   const int NC = a.NC;
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  constexpr int G = 16;  // candidates per pass over the cached logits (the usual 12 take one pass)
-  for (int k0 = 0; k0 < a.ncand; k0 += G) {
-    float al[G];
-#pragma unroll
-    for (int kk = 0; kk < G; ++kk) al[kk] = (k0 + kk < a.ncand) ? a.alphas[k0 + kk] : 0.f;
-    double acc[G];
-#pragma unroll
-    for (int kk = 0; kk < G; ++kk) acc[kk] = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < a.n; i += stride) {
-      float zx[NCP], zp[NCP];
+  const int slot = threadIdx.x & 15, rloc = threadIdx.x >> 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int k0 = 0; k0 < a.ncand; k0 += 16) {
+    const bool live = k0 + slot < a.ncand;
+    const float al = live ? a.alphas[k0 + slot] : 0.f;
+    double acc = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 16 + rloc; i < a.n; i += (int64_t)gridDim.x * 16) {
       const size_t ro = (size_t)i * NC;
+      const int b = a.labels[i];
+      float zz[NCP];
+      float M = 0.f, zb = 0.f;
 #pragma unroll
       for (int c = 0; c < NCP; ++c) {
-        zx[c] = (c < NC) ? a.Zx[ro + c] : 0.f;
-        zp[c] = (c < NC) ? a.Zp[ro + c] : 0.f;
-      }
-      const int b = a.labels[i];
-#pragma unroll
-      for (int kk = 0; kk < G; ++kk) {
-        if (k0 + kk < a.ncand) {  // uniform
-          float M = 0.f, zb = 0.f;
-          float zz[NCP];
-#pragma unroll
-          for (int c = 0; c < NCP; ++c) {
-            zz[c] = fmaf(al[kk], zp[c], zx[c]);
-            if (c < NC) {
-              M = fmaxf(M, zz[c]);
-              if (c == b) zb = zz[c];
-            }
-          }
-          float alpha = expf(-M);
-#pragma unroll
-          for (int c = 0; c < NCP; ++c)
-            if (c < NC) alpha += expf(zz[c] - M);
-          acc[kk] += (double)M + (double)logf(alpha) - (double)zb;
+        zz[c] = 0.f;
+        if (c < NC) {
+          zz[c] = fmaf(al, a.Zp[ro + c], a.Zx[ro + c]);
+          M = fmaxf(M, zz[c]);
+          if (c == b) zb = zz[c];
         }
       }
-    }
+      float alpha = expf(-M);
 #pragma unroll
-    for (int kk = 0; kk < G; ++kk) {
-      if (k0 + kk < a.ncand) {  // uniform
-        const double t = block_sum(acc[kk], sm);
-        if (threadIdx.x == 0) a.lpart[(size_t)blockIdx.x * kCandSlots + k0 + kk] = t;
-      }
+      for (int c = 0; c < NCP; ++c)
+        if (c < NC) alpha += expf(zz[c] - M);
+      acc += (double)M + (double)logf(alpha) - (double)zb;
     }
+    // rows of this workgroup, in a fixed order: the 4 row lanes of a wave, then the 4 waves
+    acc += __shfl_xor(acc, 16, 64);
+    acc += __shfl_xor(acc, 32, 64);
+    __syncthreads();  // the previous pass has read sm
+    if (lane < 16) sm[wave][lane] = acc;
+    __syncthreads();
+    if (threadIdx.x < 16 && live)
+      a.lpart[(size_t)(k0 + slot) * gridDim.x + blockIdx.x] = (sm[0][slot] + sm[1][slot]) + (sm[2][slot] + sm[3][slot]);
   }
 }
 
@@ -679,7 +669,7 @@ __global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a, int 
 #pragma unroll
       for (int u = 0; u < kBlk; ++u) {
         const int b = b0 + 64 * u;
-        v[u] = b < a.nblocks ? a.lpart[(size_t)b * kCandSlots + k] : 0.0;
+        v[u] = b < a.nblocks ? a.lpart[(size_t)k * a.nblocks + b] : 0.0;
       }
 #pragma unroll
       for (int u = 0; u < kBlk; ++u) acc += v[u];
@@ -778,6 +768,122 @@ __global__ __launch_bounds__(kTail) void ls_tail_kernel(const LsTailArgs a, int 
   }
 }
 
+// The same for short vectors (d <= PER * 1024, at most 1024 partial sums per candidate): every load of the kernel is
+// issued before anything is used, so that it costs one memory round trip instead of one per stage, and the four sums
+// over d share their barriers.  X_apply, if given, is X itself.
+template <int PER>
+__global__ __launch_bounds__(kTail) void ls_tail_fast_kernel(const LsTailArgs a) {
+  const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;  // outer solver: common factor on the penalty
+  __shared__ double sm4[4][kTail / 64];
+  __shared__ double cand[kCandSlots];
+  __shared__ float s_alpha;
+  DevState* st = a.st;
+  if (a.flag != nullptr && *a.flag == 0) return;
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int nslots = a.ncand + (a.zero_slot >= 0 ? 1 : 0);
+  const int d = (int)a.d;
+  // ---- loads ----
+  const float* zsrc = a.z ? a.z : a.X;  // a missing z or y reads X instead and is then set to zero (no branch around loads)
+  const float* ysrc = a.y ? a.y : a.X;
+  float xv[PER], zv[PER], yv[PER], pv[PER], gv[PER];
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    const int e = t + u * kTail;
+    const int ec = e < d ? e : d - 1;
+    xv[u] = a.X[ec];
+    zv[u] = zsrc[ec];
+    yv[u] = ysrc[ec];
+    pv[u] = a.pdir[ec];
+    gv[u] = a.g[ec];
+  }
+  constexpr int kLp = 1024 / 64;  // partial sums per lane and candidate
+  double lp[kLp];
+  {
+    const int k = wave < nslots ? wave : nslots - 1;
+#pragma unroll
+    for (int j = 0; j < kLp; ++j) {
+      const int b = lane + 64 * j;
+      lp[j] = a.lpart[(size_t)k * a.nblocks + (b < a.nblocks ? b : a.nblocks - 1)];
+    }
+  }
+  // ---- candidate sums: wave w takes candidates w, w + 16, ... ----
+  for (int k = wave; k < nslots; k += kTail / 64) {
+    double acc = 0.0;
+#pragma unroll
+    for (int j = 0; j < kLp; ++j) {
+      const int b = lane + 64 * j;
+      double v = lp[j];
+      if (k != wave) v = a.lpart[(size_t)k * a.nblocks + (b < a.nblocks ? b : a.nblocks - 1)];  // uniform: beyond 16 candidates
+      acc += b < a.nblocks ? v : 0.0;
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) cand[k] = acc;
+  }
+  // ---- penalty along the line: q0 + alpha q1 + alpha^2 q2, and the slope <p, g> ----
+  double q0 = 0.0, q1 = 0.0, q2 = 0.0, sl = 0.0;
+  const double inv_rho = 1.0 / (double)rho_;
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    if (t + u * kTail < d) {
+      const double x = xv[u];
+      const double uu = x - (a.z ? (double)zv[u] : 0.0) + (a.y ? (double)yv[u] : 0.0) * inv_rho;
+      const double pvd = pv[u];
+      q0 += 0.5 * (double)a.lambda * x * x + 0.5 * (double)rho_ * uu * uu;
+      q1 += (double)a.lambda * x * pvd + (double)rho_ * uu * pvd;
+      q2 += 0.5 * ((double)a.lambda + (double)rho_) * pvd * pvd;
+      sl += pvd * (double)gv[u];
+    }
+  }
+  q0 = wave_sum(q0); q1 = wave_sum(q1); q2 = wave_sum(q2); sl = wave_sum(sl);
+  if (lane == 0) { sm4[0][wave] = q0; sm4[1][wave] = q1; sm4[2][wave] = q2; sm4[3][wave] = sl; }
+  __syncthreads();  // also publishes cand[]
+  if (t == 0) {
+    q0 = q1 = q2 = sl = 0.0;
+    for (int w = 0; w < kTail / 64; ++w) { q0 += sm4[0][w]; q1 += sm4[1][w]; q2 += sm4[2][w]; sl += sm4[3][w]; }
+    double f0;
+    if (a.zero_slot >= 0) f0 = (double)a.scale * cand[a.zero_slot] + q0;
+    else if (a.use_state_loss) f0 = st->loss;
+    else f0 = a.loss_at_X;
+    int k = 0, ok = 1;
+    double fk = 0.0;
+    for (;;) {
+      const double al = (double)a.alphas[k];
+      fk = (double)a.scale * cand[k] + q0 + al * q1 + al * al * q2;
+      if (!(fk > f0 + al * (double)a.beta * sl)) break;       // Armijo holds (eq. armijo)
+      if (k + 1 >= a.ncand) { ok = 0; break; }                 // the i > i_max break of Algorithm 2
+      ++k;
+    }
+    const float alpha = a.alphas[k];
+    s_alpha = alpha;
+    st->alpha = alpha;
+    st->loss_new = fk;
+    st->armijo_ok = ok;
+    st->ls_evals = k + 1;
+    if (a.alpha_out) *a.alpha_out = alpha;
+    if (a.loss_new_out) *a.loss_new_out = fk;
+    if (a.ok_out) *a.ok_out = ok;
+    if (a.iter >= 0) {
+      nadmm_stats* s = &st->stats;
+      s->newton_iters += 1;
+      s->cg_iters_total += st->cg_iters;
+      s->ls_evals_total += k + 1;
+      s->armijo_failed += ok ? 0 : 1;
+      s->loss_final = fk;
+      if (a.iter < NADMM_TRACE_LEN) { s->alpha[a.iter] = alpha; s->cg_iters[a.iter] = st->cg_iters; }
+    }
+  }
+  __syncthreads();
+  if (a.X_apply != nullptr) {
+    const float alpha = s_alpha;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int e = t + u * kTail;
+      if (e < d) a.X_apply[e] = fmaf(alpha, pv[u], xv[u]);
+    }
+  }
+}
+
 template <typename F>
 hipError_t dispatch_ncp(int NC, F&& f) {
   if (NC <= 1) return f(std::integral_constant<int, 1>());
@@ -861,7 +967,7 @@ hipError_t launch_cg_finish(const CgFinishArgs& a, hipStream_t st) {
 }
 
 int ls_eval_blocks(int64_t n) {
-  int64_t b = (n + 255) / 256;
+  int64_t b = (n + 15) / 16;  // 16 rows per workgroup and pass over the rows
   if (b > 1024) b = 1024;
   if (b < 1) b = 1;
   return (int)b;
@@ -884,6 +990,10 @@ int ls_tail_parts(int64_t d) {
 
 hipError_t launch_ls_tail(const LsTailArgs& a, hipStream_t st) {
   const int nq = a.qpart != nullptr ? ls_tail_parts(a.d) : 0;
+  if (nq == 0 && a.d <= 8 * kTail && a.nblocks >= 1 && a.nblocks <= 1024 && (a.X_apply == nullptr || a.X_apply == a.X)) {
+    hipLaunchKernelGGL(ls_tail_fast_kernel<8>, dim3(1), dim3(kTail), 0, st, a);
+    return hipGetLastError();
+  }
   if (nq > 0) hipLaunchKernelGGL(ls_vec_part_kernel, dim3(nq), dim3(256), 0, st, a, nq);
   hipLaunchKernelGGL(ls_tail_kernel, dim3(1), dim3(kTail), 0, st, a, nq);
   if (nq > 0 && a.X_apply != nullptr)
