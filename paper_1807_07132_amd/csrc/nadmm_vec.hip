@@ -586,6 +586,62 @@ __global__ __launch_bounds__(256) void ls_eval_kernel(const LsEvalArgs a) {
   }
 }
 
+// The same with one thread per row and all candidates in a loop (the cached logits are read once per 16 candidates):
+// for many rows (n > kLsRowsPerThreadFrom) there are threads enough, and a thread per row reads the logits coalesced.
+template <int NCP>
+__global__ __launch_bounds__(256) void ls_eval_rows_kernel(const LsEvalArgs a) {
+  if (a.flag != nullptr && *a.flag == 0) return;
+  __shared__ double sm[17];
+  const int NC = a.NC;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  constexpr int G = 16;  // candidates per pass over the cached logits (the usual 12 take one pass)
+  for (int k0 = 0; k0 < a.ncand; k0 += G) {
+    float al[G];
+#pragma unroll
+    for (int kk = 0; kk < G; ++kk) al[kk] = (k0 + kk < a.ncand) ? a.alphas[k0 + kk] : 0.f;
+    double acc[G];
+#pragma unroll
+    for (int kk = 0; kk < G; ++kk) acc[kk] = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < a.n; i += stride) {
+      float zx[NCP], zp[NCP];
+      const size_t ro = (size_t)i * NC;
+#pragma unroll
+      for (int c = 0; c < NCP; ++c) {
+        zx[c] = (c < NC) ? a.Zx[ro + c] : 0.f;
+        zp[c] = (c < NC) ? a.Zp[ro + c] : 0.f;
+      }
+      const int b = a.labels[i];
+#pragma unroll
+      for (int kk = 0; kk < G; ++kk) {
+        if (k0 + kk < a.ncand) {  // uniform
+          float M = 0.f, zb = 0.f;
+          float zz[NCP];
+#pragma unroll
+          for (int c = 0; c < NCP; ++c) {
+            zz[c] = fmaf(al[kk], zp[c], zx[c]);
+            if (c < NC) {
+              M = fmaxf(M, zz[c]);
+              if (c == b) zb = zz[c];
+            }
+          }
+          float alpha = expf(-M);
+#pragma unroll
+          for (int c = 0; c < NCP; ++c)
+            if (c < NC) alpha += expf(zz[c] - M);
+          acc[kk] += (double)M + (double)logf(alpha) - (double)zb;
+        }
+      }
+    }
+#pragma unroll
+    for (int kk = 0; kk < G; ++kk) {
+      if (k0 + kk < a.ncand) {  // uniform
+        const double t = block_sum(acc[kk], sm);
+        if (threadIdx.x == 0) a.lpart[(size_t)(k0 + kk) * gridDim.x + blockIdx.x] = t;
+      }
+    }
+  }
+}
+
 // Long vectors (d > kWideFrom): the sums over d that the line search needs, per workgroup, and the update
 // X += alpha p as kernels of their own around the single-workgroup decision kernel below.
 // qpart: [4][nq] partial sums of the penalty coefficients q0, q1, q2 and of the slope <p, g>.
@@ -966,8 +1022,11 @@ hipError_t launch_cg_finish(const CgFinishArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+constexpr int64_t kLsRowsPerThreadFrom = (int64_t)1 << 17;
+
 int ls_eval_blocks(int64_t n) {
-  int64_t b = (n + 15) / 16;  // 16 rows per workgroup and pass over the rows
+  // up to 2^17 rows: 16 rows x 16 candidate slots per workgroup and pass; beyond: 256 rows per workgroup and pass
+  int64_t b = n <= kLsRowsPerThreadFrom ? (n + 15) / 16 : (n + 255) / 256;
   if (b > 1024) b = 1024;
   if (b < 1) b = 1;
   return (int)b;
@@ -977,15 +1036,20 @@ hipError_t launch_ls_eval(const LsEvalArgs& a, hipStream_t st) {
   const int blocks = ls_eval_blocks(a.n);
   return dispatch_ncp(a.NC, [&](auto ncp) {
     constexpr int NCP = decltype(ncp)::value;
-    hipLaunchKernelGGL(ls_eval_kernel<NCP>, dim3(blocks), dim3(256), 0, st, a);
+    if (a.n <= kLsRowsPerThreadFrom) hipLaunchKernelGGL(ls_eval_kernel<NCP>, dim3(blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(ls_eval_rows_kernel<NCP>, dim3(blocks), dim3(256), 0, st, a);
     return hipGetLastError();
   });
 }
 
+// Workgroups that form the sums over d of the line-search tail: none up to 8192 elements (one workgroup does everything,
+// ls_tail_fast_kernel), else one per 2048 elements, at most 256.  4 sums per workgroup fit the 2 reduce_out_blocks(d)
+// doubles of the dot-product partials in every case.
 int ls_tail_parts(int64_t d) {
-  if (d <= kWideFrom) return 0;
-  const int b = reduce_out_blocks(d) / 2;  // 4 sums per part fit the 2 reduce_out_blocks(d) doubles of the dot-product partials
-  return b < 256 ? b : 256;
+  if (d <= 8 * kTail) return 0;
+  int64_t b = d > kWideFrom ? reduce_out_blocks(d) / 2 : (d + kWideChunk - 1) / kWideChunk;
+  if (b > 256) b = 256;
+  return (int)(b < 1 ? 1 : b);
 }
 
 hipError_t launch_ls_tail(const LsTailArgs& a, hipStream_t st) {
