@@ -125,10 +125,24 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   // Deferred CG update: the operand is the new direction (or the final iterate), which every workgroup forms
   // for itself in LDS (the step slots are idle until the first tile is converted); its loads go out first, the
   // first tile right behind them.  If CG has stopped there is no product to form.
-  float xop[SPW][8], vop[SPW][8];  // this lane's entries of X and V: rows 32 s + 8 kg + e, class m
-  auto operand_index = [&](int i, int e) {
-    const int j = kStepCols * (wave + kWaves * i) + 8 * kg + e;
-    return (size_t)(j < p ? j : p - 1) * NC + mc;
+  // This lane's entries of X and V: rows 32 s + 8 kg + e (e < 8), class m.  The index is a uniform part (step and e)
+  // plus a lane part, so that a load needs no address arithmetic of its own.  Nothing is masked here: padded class
+  // lanes read class C-2 again and columns past p (last step only, index clamped into the operand) read some other
+  // entry; both only ever meet zeros of the other operand (the rows stage ignores padded classes and gives them D = 0,
+  // the tile's columns past p are zeroed when it is converted).
+  float xop[SPW][8], vop[SPW][8];
+  const unsigned lane_part = 8 * kg * NC + mc;
+  const int last_index = p * NC - 1;
+  // uniform element offset of (step slot i, e) and the lane's offset from it; only the last step slot can leave the
+  // operand, there both parts are clamped so that their sum stays inside it
+  auto operand_base = [&](int i, int e) {
+    const int u = (kStepCols * (wave + kWaves * i) + e) * NC;
+    return i < SPW - 1 ? u : (u < last_index ? u : last_index);
+  };
+  auto operand_lane = [&](int i, int e) {
+    if (i < SPW - 1) return lane_part;
+    const unsigned room = (unsigned)(last_index - operand_base(i, e));
+    return lane_part < room ? lane_part : room;
   };
   bool from_lds = false;
   if constexpr (!HAS0 && HAS1) {
@@ -141,7 +155,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
 #pragma unroll
       for (int i = 0; i < SPW; ++i)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vop[i][e] = vec[operand_index(i, e)];
+        for (int e = 0; e < 8; ++e) vop[i][e] = vec[operand_base(i, e) + operand_lane(i, e)];
       from_lds = true;
     }
   }
@@ -149,25 +163,17 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
 #pragma unroll
     for (int i = 0; i < SPW; ++i)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) vop[i][e] = has1 ? a.B1[operand_index(i, e)] : 0.f;
+      for (int e = 0; e < 8; ++e) vop[i][e] = has1 ? (a.B1 + operand_base(i, e))[operand_lane(i, e)] : 0.f;
   }
 #pragma unroll
   for (int i = 0; i < SPW; ++i)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) xop[i][e] = has0 ? a.B0[operand_index(i, e)] : 0.f;
+    for (int e = 0; e < 8; ++e) xop[i][e] = has0 ? (a.B0 + operand_base(i, e))[operand_lane(i, e)] : 0.f;
   u32x4 bx_hi[SPW], bx_lo[SPW], bx_lo2[SPW], bv_hi[SPW], bv_lo[SPW];
 #pragma unroll
   for (int i = 0; i < SPW; ++i) {
-    const int s = wave + kWaves * i;
-    float x[8], v[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const bool ok = cv && (kStepCols * s + 8 * kg + e) < p;
-      x[e] = ok ? xop[i][e] : 0.f;
-      v[e] = ok ? vop[i][e] : 0.f;
-    }
-    split8_3(x, bx_hi[i], bx_lo[i], bx_lo2[i]);
-    split8(v, bv_hi[i], bv_lo[i]);
+    split8_3(xop[i], bx_hi[i], bx_lo[i], bx_lo2[i]);
+    split8(vop[i], bv_hi[i], bv_lo[i]);
   }
   if (deferred) lds_barrier();  // every wave has picked its operands from LDS: the step slots may be overwritten
 
@@ -425,7 +431,9 @@ hipError_t launch_one(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream
   const RowArgs& a = fa.r;
   const bool stores = KIND == kRowsLogits || a.Pout != nullptr || a.Z0out != nullptr;
   if constexpr (!HAS0 && HAS1 && (KIND == kRowsHv || KIND == kRowsLogits)) {
-    if (fa.cg.st != nullptr && (fa.cg.dlen >> 2) <= (int64_t)kThreads * SPW) {  // pending CG update on short vectors
+    // the instantiation with the larger update capacity needs more registers in its prologue: it is taken only for a
+    // pending CG update on vectors that do not fit the smaller one
+    if (fa.cg.st == nullptr || (fa.cg.dlen >> 2) <= (int64_t)kThreads * SPW) {
       if (stores) return launch_k<SPW, KIND, HAS0, HAS1, true, true>(fa, grid, lds_bytes, st);
       return launch_k<SPW, KIND, HAS0, HAS1, false, true>(fa, grid, lds_bytes, st);
     }
