@@ -158,7 +158,6 @@ def main():
     gp = nadmm.Problem.from_workload(w)
     nadmm.nadmm_set_kernel_path(args.path)
     path = nadmm.nadmm_query_kernel_path(gp)
-    ws = gp.workspace()
     rng = np.random.default_rng(1234)
     Vs = [torch.from_numpy(rng.standard_normal(w.V.shape).astype(np.float32)).cuda() for _ in range(4)]
     X = torch.from_numpy(w.X0).cuda()
@@ -166,6 +165,7 @@ def main():
     g_out = gp.vec()
     loss_out = torch.empty((), dtype=torch.float64, device="cuda")
     params = nadmm.make_params(w.max_newton, w.max_cg, w.max_ls, 0.0, 0.0, w.beta, w.gamma)
+    ws = gp.workspace(params)   # sized for the local solve: every entry point accepts it
     Xs = gp.vec()
     only = set(x for x in args.only.split(",") if x)
     do = lambda k: not only or k in only
@@ -331,6 +331,13 @@ def main():
         extra["local_solve_seconds"] = per_solve_s
         extra["local_solve_passes_over_A"] = passes
         extra["local_solve_hbm_frac"] = passes * bytes_A / per_solve_s / 1e9 / HBM_PEAK_GBS
+        # the method's passes (gradient, max_cg Hessian-vector products, A p per Newton iteration) against the ones the
+        # library makes: with a workspace sized for the parameters the fused path keeps the A d_k of its CG sweeps and
+        # puts A p together from them
+        kept = nadmm.nadmm_workspace_bytes(gp, params) > nadmm.nadmm_workspace_bytes(gp)
+        made = w.max_newton * (w.max_cg + (1 if kept else 2))
+        extra["local_solve_passes_over_A_made"] = made
+        extra["local_solve_hbm_frac_of_passes_made"] = made * bytes_A / per_solve_s / 1e9 / HBM_PEAK_GBS
 
     if admm is not None:
         extra["admm"] = admm

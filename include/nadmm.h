@@ -146,6 +146,9 @@ const char* nadmm_last_hip_error(void);
  * Bytes of device workspace that every entry point below accepts for this
  * problem and these parameters (params may be NULL: defaults for the
  * stand-alone calls).  Host-only; returns 0 if the problem is invalid.
+ * With params the size can include room for max_cg (<= 32) arrays of n (C-1) floats (dense A on the
+ * single-pass matrix-core path, 3 max_cg (C-1) <= p): see nadmm_local_newton.  The size without
+ * params is a prefix of it and is accepted by every entry point as well.
  */
 size_t nadmm_workspace_bytes(const nadmm_problem* prob, const nadmm_params* params);
 
@@ -215,6 +218,12 @@ int nadmm_line_search(const nadmm_problem* prob, const float* d_X, const float* 
  * Algorithm 3: inexact Newton iteration on the local subproblem.  d_X holds the
  * warm start on entry (Algorithm 1 passes x_i^k) and x_i^{k+1} on return.
  * h_stats (host) may be NULL; if not, the stream is synchronised before return.
+ * Passes over A per Newton iteration: one for the gradient, one per CG iteration, one for the logits A p of
+ * the step that the line search (Algorithm 2) evaluates all its candidates from.  If ws_bytes is at least
+ * nadmm_workspace_bytes(prob, params) for these params and that includes the arrays named there, the last
+ * pass is left out: the CG iterate is p = sum_k alpha_k d_k, every CG pass has A d_k in hand and stores
+ * it, and A p is put together from those.  A smaller (but sufficient) workspace takes the pass; the results
+ * agree to rounding.
  */
 int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params* params,
                        nadmm_stats* h_stats, void* d_ws, size_t ws_bytes, void* stream);
@@ -265,7 +274,8 @@ typedef struct nadmm_admm_stats {
 
 /*
  * Workspace for nadmm_admm_solve / nadmm_admm_consensus: the local workspaces of the N
- * workers plus the consensus state.  h_workers: host array of N problem descriptions (shards of the
+ * workers (sized for params->local as nadmm_workspace_bytes sizes them; params may be NULL) plus the
+ * consensus state.  h_workers: host array of N problem descriptions (shards of the
  * rows of A; same p and C).  Returns 0 on invalid arguments.
  */
 size_t nadmm_admm_workspace_bytes(const nadmm_problem* h_workers, int32_t N, const nadmm_admm_params* params);

@@ -29,7 +29,10 @@ struct Layout {
   size_t drows, pcache, zx, zp;
   size_t partial, loss_part, lpart, dotpart, rrpart, zw;
   size_t pack, win_rows, win_cols;  // sparse storage: packed dense operand, windows of the two views
-  size_t total;
+  size_t total;       // with the history of directional logits (hist_bufs of them), which comes last
+  size_t total_base;  // without it
+  size_t hist;
+  int hist_bufs;
   int gen_row_blocks, gen_slabs, gen_chunks, gen_rpc;
   int fused_parts, thin_parts, sliced_parts;
   bool fused_ok, thin_ok, sliced_ok;
@@ -64,7 +67,9 @@ int validate_problem(const nadmm_problem* p, bool need_labels) {
 // logits, the sparse path's packed operand and windows); the other offsets are then not to be used.
 // wg_cap > 0: at most that many workgroups for the fused single-pass kernels (several workers' solves running side by
 // side share the compute units; each then keeps the long row ranges per workgroup that amortise a launch).
-void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg_cap = 0) {
+// max_cg > 0: room for the directional logits A d_k of that many CG iterations, if the fused single-pass path is the
+// one a solve would take and keeping them is cheaper than the pass over A they replace (see local_newton_enqueue).
+void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg_cap = 0, int max_cg = 0) {
   Shape s;
   s.n = p->n;
   s.p = p->p;
@@ -130,6 +135,11 @@ void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg
     L->win_rows = off; off += align256((size_t)(L->nwin_rows + 1) * sizeof(int32_t));
     L->win_cols = off; off += align256((size_t)(L->nwin_cols + 1) * sizeof(int32_t));
   }
+  L->total_base = off;
+  // 2 max_cg n (C-1) floats written and read instead of n p floats read: taken with a margin
+  const bool fused_default = L->fused_ok && (g_path == 2 || (g_path == 0 && !L->thin_ok));
+  L->hist_bufs = (!hv_only && fused_default && max_cg >= 1 && max_cg <= kCgHist && (int64_t)3 * max_cg * s.NC <= s.p) ? max_cg : 0;
+  L->hist = off; off += (size_t)L->hist_bufs * rows;
   L->total = off;
 }
 
@@ -353,9 +363,10 @@ int reduce(const nadmm_problem* prob, const Layout& L, void* ws, int nparts, int
 int hv_apply(const nadmm_problem* prob, const Layout& L, int path, void* ws, const float* X, bool write_pcache,
              const float* v, float* out, double* dot_part, const int32_t* flag, int* nparts_out, hipStream_t st,
              const CgPend* cg = nullptr, const int32_t* red_flag = nullptr, const int32_t* cur = nullptr,
-             const float* v_alt = nullptr) {
+             const float* v_alt = nullptr, float* w_rows = nullptr) {
   RowArgs ra = blank_rows();
   ra.kind = kRowsHv;
+  ra.Z1out = w_rows;  // fused single-pass path only: the directional logits A v, n x (C-1)
   ra.B0 = X;
   ra.B1 = v;
   ra.Pin = X ? nullptr : at<float>(ws, L.pcache);
@@ -400,17 +411,19 @@ CgPend cg_pend(const Layout& L, void* ws, DevState* ds, int slot_in, bool final_
 // CG iteration k after the initialisation: q = H d, then the update of p, r, d (Section 2.4).  On the fused path
 // the update is deferred: iteration k's sweep first applies the update of iteration k - 1 (every workgroup for
 // itself), and the update of the last iteration is applied by whatever consumes the iterate (cg_pend(final_p)).
+// w_rows (deferred form only): where the sweep leaves A d_k, or NULL.
 int cg_iteration(const nadmm_problem* prob, const Layout& L, int path, void* ws, DevState* ds, const float* X,
-                 bool write_pcache, float tol, int k, hipStream_t st) {
+                 bool write_pcache, float tol, int k, hipStream_t st, float* w_rows = nullptr) {
   float* dvec = at<float>(ws, L.dvec);
   float* q = at<float>(ws, L.q);
   if (cg_deferred(path)) {
     double* dot = at<double>(ws, L.dotpart);
     if (k == 0)  // nothing pending: d is the first direction, state slot 0 as the initialisation left it
-      return hv_apply(prob, L, path, ws, X, write_pcache, dvec, q, dot, &ds->cgs[0].active, nullptr, st);
+      return hv_apply(prob, L, path, ws, X, write_pcache, dvec, q, dot, &ds->cgs[0].active, nullptr, st, nullptr, nullptr,
+                      nullptr, nullptr, w_rows);
     const CgPend c = cg_pend(L, ws, ds, (k - 1) & 1, false, tol);
     return hv_apply(prob, L, path, ws, nullptr, false, dvec, q, dot, nullptr, nullptr, st, &c, &ds->cgs[k & 1].active,
-                    &ds->cgs[k & 1].cur, at<float>(ws, L.dvec2));
+                    &ds->cgs[k & 1].cur, at<float>(ws, L.dvec2), w_rows);
   }
   CgUpdateArgs cu;
   cu.st = ds;
@@ -464,8 +477,11 @@ static int validate_params(const nadmm_params* params) {
 }
 
 // Enqueues Algorithm 3 (arguments already validated).  outer_flag: see launch_state_init.
+// use_hist: the workspace holds L.hist_bufs >= max_cg buffers for the directional logits of the CG sweeps.  The step p is
+// sum_k alpha_k d_k over the iterations taken, so A p = sum_k alpha_k (A d_k), and every sweep has A d_k in hand: it
+// stores it (n (C-1) floats), and the line search puts A p together from them instead of a further pass over A.
 static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nadmm_params* params, const Layout& L,
-                                int path, void* d_ws, const int32_t* outer_flag, hipStream_t st) {
+                                int path, void* d_ws, const int32_t* outer_flag, hipStream_t st, bool use_hist = false) {
   int rc = NADMM_OK;
   DevState* ds = at<DevState>(d_ws, L.state);
   float* g = at<float>(d_ws, L.g);
@@ -527,8 +543,11 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     NADMM_HIP(launch_newton_head(nh, st));
 
     // CG on H p = -g with the probabilities of this iterate
+    const bool hist = use_hist && cg_deferred(path) && params->max_cg >= 1 && params->max_cg <= L.hist_bufs;
+    const size_t hist_stride = align256((size_t)L.s.n * L.s.NC * sizeof(float)) / sizeof(float);
     for (int k = 0; k < params->max_cg; ++k) {
-      if ((rc = cg_iteration(prob, L, path, d_ws, ds, nullptr, false, params->cg_tol, k, st)) != NADMM_OK) return rc;
+      float* w_rows = hist ? at<float>(d_ws, L.hist) + (size_t)k * hist_stride : nullptr;
+      if ((rc = cg_iteration(prob, L, path, d_ws, ds, nullptr, false, params->cg_tol, k, st, w_rows)) != NADMM_OK) return rc;
     }
 
     // Armijo backtracking on Z(alpha) = A X + alpha A p, then X += alpha p.  With the deferred CG update the sweep
@@ -540,7 +559,9 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     rz.B1 = pstep;
     rz.Z1out = at<float>(d_ws, L.zp);
     rz.flag = &ds->newton_active;
-    if (pend) {
+    if (hist) {  // the last update alone; A p comes from the history
+      NADMM_HIP(launch_cg_pending_finish(cg_pend(L, d_ws, ds, (params->max_cg - 1) & 1, true, params->cg_tol), st));
+    } else if (pend) {
       const CgPend c = cg_pend(L, d_ws, ds, (params->max_cg - 1) & 1, true, params->cg_tol);
       if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st, &c)) != NADMM_OK) return rc;
     } else if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st)) != NADMM_OK) {
@@ -550,7 +571,11 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     LsEvalArgs le;
     std::memset(&le, 0, sizeof(le));
     le.Zx = at<float>(d_ws, L.zx);
-    le.Zp = at<float>(d_ws, L.zp);
+    le.Zp = hist ? nullptr : at<float>(d_ws, L.zp);
+    le.hist = hist ? at<float>(d_ws, L.hist) : nullptr;
+    le.hist_stride = (int64_t)hist_stride;
+    le.nbuf = hist ? params->max_cg : 0;
+    le.st = ds;
     le.labels = prob->d_labels;
     le.n = prob->n;
     le.NC = L.s.NC;
@@ -604,7 +629,7 @@ static int admm_wg_cap(int32_t N) {
   return lanes > 1 ? 256 / lanes : 0;
 }
 
-static int admm_layout(const nadmm_problem* w, int32_t N, AdmmLayout* AL, int64_t* d_out) {
+static int admm_layout(const nadmm_problem* w, int32_t N, AdmmLayout* AL, int64_t* d_out, int max_cg = 0) {
   if (w == nullptr || N < 1 || N > NADMM_MAX_WORKERS) return NADMM_EINVAL;
   AL->wg_cap = admm_wg_cap(N);
   const int64_t d0 = (int64_t)w[0].p * (w[0].C - 1);
@@ -618,7 +643,7 @@ static int admm_layout(const nadmm_problem* w, int32_t N, AdmmLayout* AL, int64_
   AL->part = off; off += align256((size_t)admm_blocks(d0) * 5 * sizeof(double));
   for (int i = 0; i < N; ++i) {
     Layout L;
-    make_layout(&w[i], &L, false, AL->wg_cap);
+    make_layout(&w[i], &L, false, AL->wg_cap, max_cg);
     AL->local[i] = off;
     off += align256(L.total);
   }
@@ -689,10 +714,9 @@ int nadmm_query_kernel_path(const nadmm_problem* prob) {
 }
 
 size_t nadmm_workspace_bytes(const nadmm_problem* prob, const nadmm_params* params) {
-  (void)params;
   if (validate_problem(prob, false) != NADMM_OK) return 0;
   Layout L;
-  make_layout(prob, &L);
+  make_layout(prob, &L, false, 0, params != nullptr ? params->max_cg : 0);
   return L.total;
 }
 
@@ -899,12 +923,16 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
   if (d_X == nullptr) return NADMM_EINVAL;
   if ((rc = validate_params(params)) != NADMM_OK) return rc;
   Layout L;
-  make_layout(prob, &L);
+  make_layout(prob, &L, false, 0, params->max_cg);
+  // the history of directional logits is used if the workspace has room for it (it has if it was sized for these
+  // parameters); a workspace sized without parameters still does, with one more pass over A per Newton iteration
+  const bool use_hist = L.hist_bufs > 0 && ws_bytes >= L.total;
+  if (!use_hist) L.total = L.total_base;
   if ((rc = check_ws(L, d_ws, ws_bytes)) != NADMM_OK) return rc;
   int path = 0;
   if ((rc = choose_path(L, &path)) != NADMM_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
-  if ((rc = local_newton_enqueue(prob, d_X, params, L, path, d_ws, nullptr, st)) != NADMM_OK) return rc;
+  if ((rc = local_newton_enqueue(prob, d_X, params, L, path, d_ws, nullptr, st, use_hist)) != NADMM_OK) return rc;
   DevState* ds = at<DevState>(d_ws, L.state);
   if (h_stats != nullptr) {
     NADMM_HIP(hipMemcpyAsync(h_stats, &ds->stats, sizeof(nadmm_stats), hipMemcpyDeviceToHost, st));
@@ -915,9 +943,9 @@ int nadmm_local_newton(const nadmm_problem* prob, float* d_X, const nadmm_params
 
 
 // ---- ADMM outer solver (Algorithm 1) ----
-size_t nadmm_admm_workspace_bytes(const nadmm_problem* h_workers, int32_t N, const nadmm_admm_params* /*params*/) {
+size_t nadmm_admm_workspace_bytes(const nadmm_problem* h_workers, int32_t N, const nadmm_admm_params* params) {
   AdmmLayout AL;
-  if (admm_layout(h_workers, N, &AL, nullptr) != NADMM_OK) return 0;
+  if (admm_layout(h_workers, N, &AL, nullptr, params != nullptr ? params->local.max_cg : 0) != NADMM_OK) return 0;
   return AL.total;
 }
 
@@ -948,9 +976,12 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
                      void* d_ws, size_t ws_bytes, void* stream) {
   AdmmLayout AL;
   int64_t d = 0;
-  int rc = admm_layout(h_workers, N, &AL, &d);
+  int rc = admm_layout(h_workers, N, &AL, &d, params != nullptr ? params->local.max_cg : 0);
   if (rc != NADMM_OK) return rc;
   if (d_x == nullptr || d_u == nullptr || d_z == nullptr || params == nullptr) return NADMM_EINVAL;
+  // room for the workers' histories of directional logits (see nadmm_local_newton), else the layout without them
+  bool use_hist = ws_bytes >= AL.total;
+  if (!use_hist && (rc = admm_layout(h_workers, N, &AL, &d, 0)) != NADMM_OK) return rc;
   if (params->max_outer < 0 || !(lambda >= 0.f) || !std::isfinite(lambda) || !(params->eps_abs >= 0.f) ||
       !(params->eps_rel >= 0.f))
     return NADMM_EINVAL;
@@ -974,7 +1005,7 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
     wk[i].lambda = 0.f;
     wk[i].d_z = d_z;
     wk[i].d_y = d_u + (size_t)i * d;
-    make_layout(&wk[i], &Ls[i], false, AL.wg_cap);
+    make_layout(&wk[i], &Ls[i], false, AL.wg_cap, use_hist ? params->local.max_cg : 0);
     Ls[i].rho_scale = &as->rho_scale;
     if ((rc = choose_path(Ls[i], &paths[i])) != NADMM_OK) return rc;
     ca.rho[i] = wk[i].rho;
@@ -1006,7 +1037,7 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
     for (int i = 0; i < N; ++i) {
       hipStream_t si = (nlanes > 1 && i % nlanes != 0) ? lanes->stream[i % nlanes] : st;
       rc = local_newton_enqueue(&wk[i], d_x + (size_t)i * d, &params->local, Ls[i], paths[i], at<char>(d_ws, AL.local[i]),
-                                &as->active, si);
+                                &as->active, si, use_hist && Ls[i].hist_bufs > 0);
       if (rc != NADMM_OK) return rc;
     }
     if (nlanes > 1) {

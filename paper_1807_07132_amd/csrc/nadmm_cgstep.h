@@ -150,6 +150,7 @@ __device__ __forceinline__ bool cg_pending_update(const CgPend& c, bool writer, 
   }
   if (writer && t == 0) {
     st->cgs[c.slot_in ^ 1] = out;
+    if (updated && in.iters < kCgHist) st->cg_alphas[in.iters] = al;
     if (want_p) {  // the scalars that the line search and the statistics read
       st->rr = out.rr;
       st->cg_iters = out.iters;

@@ -319,6 +319,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     if (STORES && cv && my_valid) {
       if (a.Pout) a.Pout[my_off] = P;
       if (has0 && a.Z0out) a.Z0out[my_off] = z;
+      if (KIND == kRowsHv && a.Z1out) a.Z1out[my_off] = w;  // directional logits A V, kept for the line search
     }
     if (!with_cols) {
       tile_barrier();  // the partials are rewritten by the next tile
@@ -429,7 +430,7 @@ hipError_t launch_k(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t
 template <int SPW, int KIND, bool HAS0, bool HAS1>
 hipError_t launch_one(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t st) {
   const RowArgs& a = fa.r;
-  const bool stores = KIND == kRowsLogits || a.Pout != nullptr || a.Z0out != nullptr;
+  const bool stores = KIND == kRowsLogits || a.Pout != nullptr || a.Z0out != nullptr || a.Z1out != nullptr;
   if constexpr (!HAS0 && HAS1 && (KIND == kRowsHv || KIND == kRowsLogits)) {
     // the instantiation with the larger update capacity needs more registers in its prologue: it is taken only for a
     // pending CG update on vectors that do not fit the smaller one

@@ -40,6 +40,10 @@ struct CgSlot {
 
 // Device-resident scalars of the Newton / CG / line-search drivers.  Lives at
 // the start of the workspace; written only by single-workgroup tail kernels.
+// Iterations of one CG solve whose directional logits A d_k the fused path may keep, so that the line search gets
+// A p = sum_k alpha_k A d_k without another pass over A.
+constexpr int kCgHist = 32;
+
 struct DevState {
   double loss;      // Fhat at the current X
   double gg;        // ||g||^2 at the current X
@@ -59,6 +63,7 @@ struct DevState {
   int32_t pad_[3];
   double rr_prev;   //   ||r||^2 before this CG iteration
   CgSlot cgs[2];    // deferred CG update (fused single-pass path): see CgPend
+  float cg_alphas[kCgHist];  // deferred CG update: step length of every iteration taken (p = sum_k alpha_k d_k)
   nadmm_stats stats;  // copied to the host at the end of nadmm_local_newton
 };
 
@@ -233,7 +238,11 @@ hipError_t launch_cg_finish(const CgFinishArgs& a, hipStream_t st);
 
 struct LsEvalArgs {
   const float* Zx;
-  const float* Zp;
+  const float* Zp;         // A p; or NULL: A p = sum_{k < st->cg_iters} st->cg_alphas[k] * hist[k * hist_stride + .]
+  const float* hist;       // the directional logits A d_k that the CG sweeps left, n x NC each
+  int64_t hist_stride;     // elements between two of them
+  int32_t nbuf;            // buffers there are (<= kCgHist): the most iterations a solve takes
+  const DevState* st;
   const int32_t* labels;
   int64_t n;
   int32_t NC;

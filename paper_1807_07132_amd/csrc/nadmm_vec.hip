@@ -6,6 +6,7 @@
 // reproducible bit for bit.
 #include "nadmm_internal.h"
 #include "nadmm_cgstep.h"
+#include "nadmm_mfma.h"
 
 namespace nadmm {
 namespace {
@@ -540,40 +541,80 @@ __global__ __launch_bounds__(256) void cg_finish_kernel(const CgFinishArgs a) {
   }
 }
 
+// A p of one element of the cached-logit arrays from the directional logits of the CG iterations taken (LsEvalArgs).
+__device__ __forceinline__ float zp_from_history(const LsEvalArgs& a, int nused, const float* al, size_t e) {
+  float v = 0.f;
+  for (int k = 0; k < nused; ++k) v = fmaf(al[k], a.hist[(size_t)k * a.hist_stride + e], v);
+  return v;
+}
+
 // Row losses at Z = Zx + alpha Zp for all candidate step sizes (Sections 2.1, 2.2).  One thread per (row, candidate):
 // a workgroup is 16 rows x 16 candidate slots, the 16 threads of a row read the same cached logits (one broadcast
 // load per wave and address), and a row costs a thread one log-sum-exp instead of one per candidate, so that a compute
 // unit holds many short threads instead of a few long ones.  More than 16 candidates take further passes.
-template <int NCP>
+// NK = 0: A p is given.  NK > 0: A p comes from up to NK history buffers (LsEvalArgs).  The 4 rows of a wave are 4 (C-1)
+// consecutive elements of every buffer: lane l takes element l through all buffers (NK coalesced loads, each a line or
+// two), and the threads of a row then fetch the C-1 sums of their row from those lanes.
+// No load sits under a condition (indices are clamped instead: padded classes read class C-2 again, rows past the end
+// the last row, buffers past the last one the last one), so that all of a row's loads are in flight together.
+template <int NCP, int NK>
 __global__ __launch_bounds__(256) void ls_eval_kernel(const LsEvalArgs a) {
   if (a.flag != nullptr && *a.flag == 0) return;
   __shared__ double sm[4][16];
   const int NC = a.NC;
   const int slot = threadIdx.x & 15, rloc = threadIdx.x >> 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float hal[NK > 0 ? NK : 1];
+  if (NK > 0) {
+    const int nused = a.st->cg_iters < a.nbuf ? a.st->cg_iters : a.nbuf;
+#pragma unroll
+    for (int k = 0; k < NK; ++k) hal[k] = k < nused ? a.st->cg_alphas[k < kCgHist ? k : kCgHist - 1] : 0.f;  // uniform
+  }
+  const int64_t last = a.n * NC - 1;
   for (int k0 = 0; k0 < a.ncand; k0 += 16) {
     const bool live = k0 + slot < a.ncand;
     const float al = live ? a.alphas[k0 + slot] : 0.f;
     double acc = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * 16 + rloc; i < a.n; i += (int64_t)gridDim.x * 16) {
-      const size_t ro = (size_t)i * NC;
-      const int b = a.labels[i];
+    for (int64_t g = (int64_t)blockIdx.x * 16; g < a.n; g += (int64_t)gridDim.x * 16) {  // the same trips for every thread
+      const int64_t i = g + rloc;
+      const bool valid = i < a.n;
+      const size_t ro = (size_t)(valid ? i : a.n - 1) * NC;
+      const int b = a.labels[valid ? i : a.n - 1];
+      float zx[NCP], zp[NCP], h[NK > 0 ? NK : 1];
+      if (NK > 0) {
+        const int64_t e = (g + 4 * wave) * NC + lane;  // lanes past the 4 rows read on into the next rows: never used
+        const float* src = a.hist + (e < last ? e : last);
+#pragma unroll
+        for (int k = 0; k < NK; ++k) h[k] = src[(size_t)(k < a.nbuf ? k : a.nbuf - 1) * a.hist_stride];
+      }
+#pragma unroll
+      for (int c = 0; c < NCP; ++c) {
+        const size_t e = ro + (c < NC ? c : NC - 1);
+        zx[c] = a.Zx[e];
+        if (NK == 0) zp[c] = a.Zp[e];
+      }
+      if (NK > 0) {
+        float sum = 0.f;
+#pragma unroll
+        for (int k = 0; k < NK; ++k) sum = hal[k] != 0.f ? fmaf(hal[k], h[k], sum) : sum;  // unused buffers hold anything
+#pragma unroll
+        for (int c = 0; c < NCP; ++c) {
+          const int from = (rloc & 3) * NC + (c < NC ? c : NC - 1);  // < 4 (C-1) <= 64
+          zp[c] = __int_as_float(__builtin_amdgcn_ds_bpermute(from << 2, __float_as_int(sum)));
+        }
+      }
       float zz[NCP];
       float M = 0.f, zb = 0.f;
 #pragma unroll
       for (int c = 0; c < NCP; ++c) {
-        zz[c] = 0.f;
-        if (c < NC) {
-          zz[c] = fmaf(al, a.Zp[ro + c], a.Zx[ro + c]);
-          M = fmaxf(M, zz[c]);
-          if (c == b) zb = zz[c];
-        }
+        zz[c] = fmaf(al, zp[c], zx[c]);
+        M = c < NC ? fmaxf(M, zz[c]) : M;
+        zb = (c < NC && c == b) ? zz[c] : zb;   // the reference class (label C-1) has logit 0
       }
       float alpha = expf(-M);
 #pragma unroll
-      for (int c = 0; c < NCP; ++c)
-        if (c < NC) alpha += expf(zz[c] - M);
-      acc += (double)M + (double)logf(alpha) - (double)zb;
+      for (int c = 0; c < NCP; ++c) alpha += c < NC ? expf(zz[c] - M) : 0.f;
+      if (valid) acc += (double)M + (double)logf(alpha) - (double)zb;
     }
     // rows of this workgroup, in a fixed order: the 4 row lanes of a wave, then the 4 waves
     acc += __shfl_xor(acc, 16, 64);
@@ -592,9 +633,17 @@ template <int NCP>
 __global__ __launch_bounds__(256) void ls_eval_rows_kernel(const LsEvalArgs a) {
   if (a.flag != nullptr && *a.flag == 0) return;
   __shared__ double sm[17];
+  __shared__ float cgal[kCgHist];
   const int NC = a.NC;
   const int64_t stride = (int64_t)gridDim.x * 256;
   constexpr int G = 16;  // candidates per pass over the cached logits (the usual 12 take one pass)
+  const bool from_hist = a.Zp == nullptr;
+  int nused = 0;
+  if (from_hist) {
+    nused = a.st->cg_iters < kCgHist ? a.st->cg_iters : kCgHist;
+    if (threadIdx.x < kCgHist) cgal[threadIdx.x] = threadIdx.x < nused ? a.st->cg_alphas[threadIdx.x] : 0.f;
+    __syncthreads();
+  }
   for (int k0 = 0; k0 < a.ncand; k0 += G) {
     float al[G];
 #pragma unroll
@@ -607,8 +656,9 @@ __global__ __launch_bounds__(256) void ls_eval_rows_kernel(const LsEvalArgs a) {
       const size_t ro = (size_t)i * NC;
 #pragma unroll
       for (int c = 0; c < NCP; ++c) {
-        zx[c] = (c < NC) ? a.Zx[ro + c] : 0.f;
-        zp[c] = (c < NC) ? a.Zp[ro + c] : 0.f;
+        const size_t e = ro + (c < NC ? c : NC - 1);  // no load under a condition: padded classes read class C-2 again
+        zx[c] = a.Zx[e];
+        zp[c] = from_hist ? zp_from_history(a, nused, cgal, e) : a.Zp[e];
       }
       const int b = a.labels[i];
 #pragma unroll
@@ -1036,8 +1086,19 @@ hipError_t launch_ls_eval(const LsEvalArgs& a, hipStream_t st) {
   const int blocks = ls_eval_blocks(a.n);
   return dispatch_ncp(a.NC, [&](auto ncp) {
     constexpr int NCP = decltype(ncp)::value;
-    if (a.n <= kLsRowsPerThreadFrom) hipLaunchKernelGGL(ls_eval_kernel<NCP>, dim3(blocks), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(ls_eval_rows_kernel<NCP>, dim3(blocks), dim3(256), 0, st, a);
+    if (a.Zp == nullptr && (a.hist == nullptr || a.st == nullptr || a.nbuf < 1 || a.nbuf > kCgHist)) return hipErrorInvalidValue;
+    if (a.n > kLsRowsPerThreadFrom) {
+      hipLaunchKernelGGL(ls_eval_rows_kernel<NCP>, dim3(blocks), dim3(256), 0, st, a);
+    } else if (a.Zp != nullptr) {
+      hipLaunchKernelGGL((ls_eval_kernel<NCP, 0>), dim3(blocks), dim3(256), 0, st, a);
+    } else if constexpr (NCP <= 16) {  // 4 rows of a wave are at most 64 elements
+      if (a.nbuf <= 8) hipLaunchKernelGGL((ls_eval_kernel<NCP, 8>), dim3(blocks), dim3(256), 0, st, a);
+      else if (a.nbuf <= 12) hipLaunchKernelGGL((ls_eval_kernel<NCP, 12>), dim3(blocks), dim3(256), 0, st, a);
+      else if (a.nbuf <= 16) hipLaunchKernelGGL((ls_eval_kernel<NCP, 16>), dim3(blocks), dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((ls_eval_kernel<NCP, kCgHist>), dim3(blocks), dim3(256), 0, st, a);
+    } else {
+      return hipErrorInvalidValue;
+    }
     return hipGetLastError();
   });
 }

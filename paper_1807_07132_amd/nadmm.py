@@ -204,9 +204,13 @@ class Problem:
         A = SparseA.from_scipy(w.A, w.extra["csc"], dev) if w.sparse else to(w.A)
         return cls(A, to(w.b), w.C, w.s, w.lam, w.rho, to(w.z), to(w.y))
 
-    def workspace(self) -> torch.Tensor:
-        if self._ws is None:
-            self._ws = alloc_workspace(self)
+    def workspace(self, params=None) -> torch.Tensor:
+        """Cached workspace for this problem, sized for `params` (nadmm_workspace_bytes) and regrown if a later call needs more."""
+        need = nadmm_workspace_bytes(self, params)
+        if need == 0:
+            raise NadmmError(NADMM_EINVAL)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.A.device)
         return self._ws
 
     def vec(self) -> torch.Tensor:
@@ -306,7 +310,7 @@ def nadmm_line_search(prob: Problem, X: torch.Tensor, p: torch.Tensor, g: torch.
 
 def nadmm_local_newton(prob: Problem, X: torch.Tensor, params: nadmm_params, want_stats=True, ws=None, stream=None):
     """Updates X in place.  Returns a dict of statistics (synchronises) or None."""
-    ws = prob.workspace() if ws is None else ws
+    ws = prob.workspace(params) if ws is None else ws
     st = nadmm_stats() if want_stats else None
     _check(lib().nadmm_local_newton(C.byref(prob.c), _ptr(X), C.byref(params), C.byref(st) if st is not None else None,
                                     _ptr(ws), ws.numel(), _stream(stream)))

@@ -224,6 +224,38 @@ def test_local_newton(cache, name, path):
         st, [(it["alpha"], it["armijo_ok"], it["loss"], it["grad_norm"]) for it in st_ref["iters"]])
 
 
+@pytest.mark.parametrize("cg_tol", [0.0, 3e-2])
+@pytest.mark.parametrize("name", ["image_like_3k", "fused_130x960_C4", "wide_700"])
+def test_local_newton_with_and_without_the_history_of_directional_logits(cache, name, cg_tol):
+    """A workspace sized for the solve's parameters lets the fused path put A p together from the A d_k its CG sweeps
+    leave behind (p = sum_k alpha_k d_k) instead of another pass over A; one sized without parameters takes that
+    pass.  Both must follow the oracle, also when CG stops early and leaves part of the history unused."""
+    w, gp, op = setup_case(cache, name)
+    force_path(gp, 2)
+    T, K = 3, 12
+    params = nadmm.make_params(T, K, w.max_ls, cg_tol, 0.0, w.beta, w.gamma)
+    small, large = nadmm.nadmm_workspace_bytes(gp), nadmm.nadmm_workspace_bytes(gp, params)
+    assert large >= small + K * w.n * (w.C - 1) * 4      # this shape qualifies for the history
+    w2 = dataclasses.replace(w, max_cg=K, cg_tol=cg_tol)
+    out = []
+    for nbytes in (small, large):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)                                   # NaN patterns: nothing may be read before it is written
+        X = dev(w.X0.copy())
+        st = nadmm.nadmm_local_newton(gp, X, params, ws=ws)
+        X_ref, st_ref, _ = oracle_newton_following(op, w.X0, w2, st["alpha"], max_newton=T)
+        assert st["newton_iters"] == T
+        assert st["cg_iters"] == [it["cg_iters"] for it in st_ref["iters"]]
+        if cg_tol > 0 and name == "image_like_3k":
+            assert min(st["cg_iters"]) < K               # the early stop is really exercised
+        assert st["alpha"] == pytest.approx([it["alpha"] for it in st_ref["iters"]], rel=1e-6)
+        assert rel_l2(host(X), X_ref) <= TOL_ITERATE
+        assert rel_abs(st["loss_final"], st_ref["loss_final"]) <= TOL_PRIMITIVE
+        out.append((host(X), st))
+    assert out[0][1]["alpha"] == out[1][1]["alpha"]
+    assert rel_l2(out[0][0], out[1][0]) <= 1e-4
+
+
 def test_local_newton_stops_on_gradient_tolerance(cache):
     w, gp, op = setup_case(cache, "ragged_1237x45_C5")
     params = nadmm.make_params(30, 50, 10, 1e-6, 1e-4, w.beta, w.gamma)
