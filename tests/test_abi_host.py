@@ -125,6 +125,27 @@ def test_workspace_bytes(lib):
     assert lib.nadmm_workspace_bytes(None, None) == 0
 
 
+def test_workspace_bytes_with_parameters(lib):
+    """With parameters the size may add the history of directional logits (max_cg arrays of n (C-1) floats) where the
+    single-pass matrix-core path applies and the history is cheaper than the pass over A it replaces."""
+    rows = 60000 * 9 * 4
+    head = fake_problem(n=60000, p=784, Cc=10)
+    base = lib.nadmm_workspace_bytes(C.byref(head), None)
+    for max_cg, kept in ((10, True), (29, True), (30, False), (0, False), (33, False)):   # 3 max_cg (C-1) <= p, max_cg <= 32
+        pr = nadmm.make_params(10, max_cg, 10, 0.0, 0.0, 1e-4, 0.5)
+        need = lib.nadmm_workspace_bytes(C.byref(head), C.byref(pr))
+        assert need % 256 == 0
+        if kept:
+            assert max_cg * rows <= need - base < max_cg * (rows + 256)
+        else:
+            assert need == base
+    pr = nadmm.make_params(10, 10, 10, 0.0, 0.0, 1e-4, 0.5)
+    for other in (fake_problem(n=1375000, p=28, Cc=2),            # thin-data path
+                  fake_problem(n=50000, p=3072, Cc=10),           # column-sliced path
+                  fake_problem(n=60000, p=784, Cc=10, lda=785)):  # rows not 16-byte aligned: vector path
+        assert lib.nadmm_workspace_bytes(C.byref(other), C.byref(pr)) == lib.nadmm_workspace_bytes(C.byref(other), None)
+
+
 @pytest.mark.parametrize("kw,code", [
     (dict(n=0), nadmm.NADMM_EINVAL),
     (dict(p=0), nadmm.NADMM_EINVAL),
