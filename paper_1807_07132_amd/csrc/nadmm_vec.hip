@@ -36,42 +36,59 @@ __device__ __forceinline__ double block_sum(double v, double* sm /* >= 17 double
 // thread groups each sum every 8th partial (independent loads in flight), then the 8 group sums
 // are added in a fixed order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
-  const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;  // outer solver: common factor on the penalty
-  if (a.flag != nullptr && *a.flag == 0) return;
   __shared__ float sm[8][32];
   const int el = threadIdx.x & 31, grp = threadIdx.x >> 5;
   const int64_t e = (int64_t)blockIdx.x * 32 + el;
-  float sum = 0.f;
-  if (e < a.d) {
-    const float* __restrict__ pp = a.partial + e;
-    int k = grp;
-    for (; k + 8 * 15 < a.nparts; k += 8 * 16) {  // 16 independent loads in flight, summed in order
-      float v[16];
-#pragma unroll
-      for (int t = 0; t < 16; ++t) v[t] = pp[(size_t)(k + 8 * t) * a.d];
-#pragma unroll
-      for (int t = 0; t < 16; ++t) sum += v[t];
-    }
-    for (; k < a.nparts; k += 8) sum += pp[(size_t)k * a.d];
+  const bool ok = e < a.d;
+  const int64_t ec = ok ? e : a.d - 1;
+  // Every load is requested before the first result is needed: the vectors of the linear terms (clamped index, all
+  // threads, so that no load sits under a condition), then the partials; only then the activity flag is looked at.
+  float lin0 = 0.f, lin1 = 0.f, lin2 = 0.f;
+  if (a.kind == 0) {
+    lin0 = a.V[ec];
+    lin1 = a.V_alt != nullptr ? a.V_alt[ec] : 0.f;
+  } else {
+    lin0 = a.X[ec];
+    lin1 = a.z != nullptr ? a.z[ec] : 0.f;
+    lin2 = a.y != nullptr ? a.y[ec] : 0.f;
   }
+  const float* __restrict__ pp = a.partial + ec;
+  float sum = 0.f;
+  int k = grp;
+  float v[16];
+  const bool first_batch = k + 8 * 15 < a.nparts;  // uniform: the same for all 8 thread groups
+  if (first_batch) {
+#pragma unroll
+    for (int t = 0; t < 16; ++t) v[t] = pp[(size_t)(k + 8 * t) * a.d];
+  }
+  if (a.flag != nullptr && *a.flag == 0) return;
+  const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;  // outer solver: common factor on the penalty
+  if (first_batch) {
+#pragma unroll
+    for (int t = 0; t < 16; ++t) sum += v[t];
+    k += 8 * 16;
+  }
+  for (; k + 8 * 15 < a.nparts; k += 8 * 16) {  // 16 independent loads in flight, summed in order
+#pragma unroll
+    for (int t = 0; t < 16; ++t) v[t] = pp[(size_t)(k + 8 * t) * a.d];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) sum += v[t];
+  }
+  for (; k < a.nparts; k += 8) sum += pp[(size_t)k * a.d];
   sm[grp][el] = sum;
   __syncthreads();
   if (grp != 0) return;
-  const bool ok = e < a.d;
 #pragma unroll
   for (int g = 1; g < 8; ++g) sum += sm[g][el];
   float out = a.scale * sum;
   double prod = 0.0, pen = 0.0;
   if (ok) {
     if (a.kind == 0) {
-      const float* __restrict__ V = (a.cur != nullptr && *a.cur != 0) ? a.V_alt : a.V;
-      const float v = V[e];
-      out = fmaf(a.lambda + rho_, v, out);
-      prod = (double)out * (double)v;
+      const float vv = (a.cur != nullptr && *a.cur != 0) ? lin1 : lin0;
+      out = fmaf(a.lambda + rho_, vv, out);
+      prod = (double)out * (double)vv;
     } else {
-      const float x = a.X[e];
-      const float zz = a.z ? a.z[e] : 0.f;
-      const float yy = a.y ? a.y[e] : 0.f;
+      const float x = lin0, zz = lin1, yy = lin2;
       out += a.lambda * x + rho_ * (x - zz) + yy;
       const double xd = x, u = xd - (double)zz + (double)yy / (double)rho_;
       pen = 0.5 * (double)a.lambda * xd * xd + 0.5 * (double)rho_ * u * u;
