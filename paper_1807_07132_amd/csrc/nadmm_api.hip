@@ -559,8 +559,10 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     rz.B1 = pstep;
     rz.Z1out = at<float>(d_ws, L.zp);
     rz.flag = &ds->newton_active;
-    if (hist) {  // the last update alone; A p comes from the history
-      NADMM_HIP(launch_cg_pending_finish(cg_pend(L, d_ws, ds, (params->max_cg - 1) & 1, true, params->cg_tol), st));
+    const bool eval_finishes = hist && ls_eval_takes_pending(prob->n);  // the row kernel of the line search applies the last update
+    if (hist) {  // A p comes from the history; the last update alone, unless the line search's row kernel takes it along
+      if (!eval_finishes)
+        NADMM_HIP(launch_cg_pending_finish(cg_pend(L, d_ws, ds, (params->max_cg - 1) & 1, true, params->cg_tol), st));
     } else if (pend) {
       const CgPend c = cg_pend(L, d_ws, ds, (params->max_cg - 1) & 1, true, params->cg_tol);
       if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st, &c)) != NADMM_OK) return rc;
@@ -575,6 +577,10 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     le.hist = hist ? at<float>(d_ws, L.hist) : nullptr;
     le.hist_stride = (int64_t)hist_stride;
     le.nbuf = hist ? params->max_cg : 0;
+    if (eval_finishes) {
+      le.has_pend = 1;
+      le.pend = cg_pend(L, d_ws, ds, (params->max_cg - 1) & 1, true, params->cg_tol);
+    }
     le.st = ds;
     le.labels = prob->d_labels;
     le.n = prob->n;

@@ -161,4 +161,92 @@ __device__ __forceinline__ bool cg_pending_update(const CgPend& c, bool writer, 
   return want_p || out.active != 0;
 }
 
+// The scalars of a pending update alone, for a kernel whose workgroups all need the step length of the last CG
+// iteration (identical arithmetic in every workgroup): <d, q> from its partial sums in a fixed order, a = rr / <d, q>.
+struct CgPendScalars {
+  CgSlot in;
+  double dq;
+  float al;
+  bool updated;   // the update takes place (CG active, positive curvature)
+};
+template <int THREADS>
+__device__ __forceinline__ CgPendScalars cg_pending_scalars(const CgPend& c, double* sm) {
+  CgPendScalars s;
+  s.in = c.st->cgs[c.slot_in];
+  double v = 0.0;
+  for (int k = threadIdx.x; k < c.ndot; k += THREADS) v += c.dot_part[k];
+  s.dq = cg_block_sum<THREADS>(v, sm);
+  s.updated = s.in.active != 0 && s.dq > 0.0 && isfinite(s.dq);
+  s.al = s.updated ? (float)(s.in.rr / s.dq) : 0.f;
+  return s;
+}
+
+// The last update of a CG solve (c.final_p) by one workgroup that walks over the vectors in pieces (few registers: it
+// runs beside other work in the same kernel): leaves the iterate in c.p_final and the final scalars in the state.
+// The vector sets themselves are not advanced: nothing reads them after the last update.
+template <int THREADS>
+__device__ __forceinline__ void cg_pending_final_walk(const CgPend& c, double* sm) {
+  const CgPendScalars s = cg_pending_scalars<THREADS>(c, sm);
+  DevState* st = c.st;
+  const int cur = s.in.cur & 1;
+  const float* __restrict__ r_in = cur ? c.r[1] : c.r[0];
+  const float* __restrict__ d_in = cur ? c.d[1] : c.d[0];
+  const float* __restrict__ p_in = cur ? c.p[1] : c.p[0];
+  const int n = (int)c.dlen, n4 = n >> 2;
+  const float al = s.al;
+  double acc = 0.0;
+  constexpr int U = 2;
+  for (int k0 = threadIdx.x; k0 < n4; k0 += U * THREADS) {
+    float4 qv[U], rv[U], dv[U], pv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = k0 + u * THREADS < n4 ? k0 + u * THREADS : n4 - 1;
+      qv[u] = reinterpret_cast<const float4*>(c.q)[k];
+      rv[u] = reinterpret_cast<const float4*>(r_in)[k];
+      dv[u] = reinterpret_cast<const float4*>(d_in)[k];
+      pv[u] = reinterpret_cast<const float4*>(p_in)[k];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (k0 + u * THREADS < n4) {
+        float4 pn = pv[u];
+        if (s.updated) {
+          const float r0 = fmaf(-al, qv[u].x, rv[u].x), r1 = fmaf(-al, qv[u].y, rv[u].y);
+          const float r2 = fmaf(-al, qv[u].z, rv[u].z), r3 = fmaf(-al, qv[u].w, rv[u].w);
+          acc += ((double)r0 * (double)r0 + (double)r1 * (double)r1) + ((double)r2 * (double)r2 + (double)r3 * (double)r3);
+          pn.x = fmaf(al, dv[u].x, pv[u].x); pn.y = fmaf(al, dv[u].y, pv[u].y);
+          pn.z = fmaf(al, dv[u].z, pv[u].z); pn.w = fmaf(al, dv[u].w, pv[u].w);
+        }
+        reinterpret_cast<float4*>(c.p_final)[k0 + u * THREADS] = pn;
+      }
+    }
+  }
+  if ((int)threadIdx.x < (n & 3)) {
+    const int e = 4 * n4 + threadIdx.x;
+    float pn = p_in[e];
+    if (s.updated) {
+      const float rn = fmaf(-al, c.q[e], r_in[e]);
+      acc += (double)rn * (double)rn;
+      pn = fmaf(al, d_in[e], pn);
+    }
+    c.p_final[e] = pn;
+  }
+  const double rr_new = cg_block_sum<THREADS>(acc, sm);
+  if (threadIdx.x == 0) {
+    CgSlot out = s.in;
+    if (s.updated) {
+      out.rr = rr_new;
+      out.iters = s.in.iters + 1;
+      if (sqrt(rr_new) <= (double)c.tol * sqrt(st->gg_cg)) out.active = 0;
+      if (s.in.iters < kCgHist) st->cg_alphas[s.in.iters] = al;
+    } else if (s.in.active != 0) {
+      out.active = 0;  // no positive curvature: the current iterate stays
+    }
+    st->cgs[c.slot_in ^ 1] = out;
+    st->rr = out.rr;
+    st->cg_iters = out.iters;
+    st->cg_active = out.active;
+  }
+}
+
 }  // namespace nadmm

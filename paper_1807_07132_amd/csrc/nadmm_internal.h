@@ -242,6 +242,9 @@ struct LsEvalArgs {
   const float* hist;       // the directional logits A d_k that the CG sweeps left, n x NC each
   int64_t hist_stride;     // elements between two of them
   int32_t nbuf;            // buffers there are (<= kCgHist): the most iterations a solve takes
+  int32_t has_pend;        // the last CG update is still pending (pend): workgroup 0 applies it, the others take its
+                           // step length from the same scalars; launched with one workgroup more
+  CgPend pend;
   const DevState* st;
   const int32_t* labels;
   int64_t n;
@@ -252,6 +255,7 @@ struct LsEvalArgs {
   const int32_t* flag;
 };
 int ls_eval_blocks(int64_t n);
+bool ls_eval_takes_pending(int64_t n);
 hipError_t launch_ls_eval(const LsEvalArgs& a, hipStream_t st);
 
 struct LsTailArgs {

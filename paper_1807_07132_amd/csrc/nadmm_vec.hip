@@ -581,18 +581,35 @@ __global__ __launch_bounds__(256) void ls_eval_kernel(const LsEvalArgs a) {
   const int NC = a.NC;
   const int slot = threadIdx.x & 15, rloc = threadIdx.x >> 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // With the last CG update still pending, workgroup 0 applies it (iterate, final scalars) while the others evaluate;
+  // they take its step length from the same partial sums by the same arithmetic.
+  const int role0 = (NK > 0 && a.has_pend != 0) ? 1 : 0;
+  const int wg = blockIdx.x - role0, nwg = gridDim.x - role0;
   float hal[NK > 0 ? NK : 1];
   if (NK > 0) {
-    const int nused = a.st->cg_iters < a.nbuf ? a.st->cg_iters : a.nbuf;
+    __shared__ double smd[256 / 64 + 1];
+    if (role0 != 0 && blockIdx.x == 0) {
+      cg_pending_final_walk<256>(a.pend, smd);
+      return;
+    }
+    int nprev = a.st->cg_iters;
+    float al_last = 0.f;
+    if (role0 != 0) {
+      const CgPendScalars ps = cg_pending_scalars<256>(a.pend, smd);
+      nprev = ps.in.iters;
+      al_last = ps.al;  // 0 if the update does not take place
+    }
+    nprev = nprev < a.nbuf ? nprev : a.nbuf;
 #pragma unroll
-    for (int k = 0; k < NK; ++k) hal[k] = k < nused ? a.st->cg_alphas[k < kCgHist ? k : kCgHist - 1] : 0.f;  // uniform
+    for (int k = 0; k < NK; ++k)  // uniform
+      hal[k] = k < nprev ? a.st->cg_alphas[k < kCgHist ? k : kCgHist - 1] : ((k == nprev && k < a.nbuf) ? al_last : 0.f);
   }
   const int64_t last = a.n * NC - 1;
   for (int k0 = 0; k0 < a.ncand; k0 += 16) {
     const bool live = k0 + slot < a.ncand;
     const float al = live ? a.alphas[k0 + slot] : 0.f;
     double acc = 0.0;
-    for (int64_t g = (int64_t)blockIdx.x * 16; g < a.n; g += (int64_t)gridDim.x * 16) {  // the same trips for every thread
+    for (int64_t g = (int64_t)wg * 16; g < a.n; g += (int64_t)nwg * 16) {  // the same trips for every thread
       const int64_t i = g + rloc;
       const bool valid = i < a.n;
       const size_t ro = (size_t)(valid ? i : a.n - 1) * NC;
@@ -640,7 +657,7 @@ __global__ __launch_bounds__(256) void ls_eval_kernel(const LsEvalArgs a) {
     if (lane < 16) sm[wave][lane] = acc;
     __syncthreads();
     if (threadIdx.x < 16 && live)
-      a.lpart[(size_t)(k0 + slot) * gridDim.x + blockIdx.x] = (sm[0][slot] + sm[1][slot]) + (sm[2][slot] + sm[3][slot]);
+      a.lpart[(size_t)(k0 + slot) * nwg + wg] = (sm[0][slot] + sm[1][slot]) + (sm[2][slot] + sm[3][slot]);
   }
 }
 
@@ -1091,6 +1108,9 @@ hipError_t launch_cg_finish(const CgFinishArgs& a, hipStream_t st) {
 
 constexpr int64_t kLsRowsPerThreadFrom = (int64_t)1 << 17;
 
+// Whether the line-search row kernel for n rows can apply a pending last CG update itself (LsEvalArgs.has_pend).
+bool ls_eval_takes_pending(int64_t n) { return n <= kLsRowsPerThreadFrom; }
+
 int ls_eval_blocks(int64_t n) {
   // up to 2^17 rows: 16 rows x 16 candidate slots per workgroup and pass; beyond: 256 rows per workgroup and pass
   int64_t b = n <= kLsRowsPerThreadFrom ? (n + 15) / 16 : (n + 255) / 256;
@@ -1104,15 +1124,19 @@ hipError_t launch_ls_eval(const LsEvalArgs& a, hipStream_t st) {
   return dispatch_ncp(a.NC, [&](auto ncp) {
     constexpr int NCP = decltype(ncp)::value;
     if (a.Zp == nullptr && (a.hist == nullptr || a.st == nullptr || a.nbuf < 1 || a.nbuf > kCgHist)) return hipErrorInvalidValue;
+    if (a.has_pend != 0 && (!ls_eval_takes_pending(a.n) || a.Zp != nullptr || a.pend.st == nullptr || a.pend.final_p == 0 ||
+                            a.pend.ndot < 1 || a.pend.dlen < 1))
+      return hipErrorInvalidValue;
     if (a.n > kLsRowsPerThreadFrom) {
       hipLaunchKernelGGL(ls_eval_rows_kernel<NCP>, dim3(blocks), dim3(256), 0, st, a);
     } else if (a.Zp != nullptr) {
       hipLaunchKernelGGL((ls_eval_kernel<NCP, 0>), dim3(blocks), dim3(256), 0, st, a);
     } else if constexpr (NCP <= 16) {  // 4 rows of a wave are at most 64 elements
-      if (a.nbuf <= 8) hipLaunchKernelGGL((ls_eval_kernel<NCP, 8>), dim3(blocks), dim3(256), 0, st, a);
-      else if (a.nbuf <= 12) hipLaunchKernelGGL((ls_eval_kernel<NCP, 12>), dim3(blocks), dim3(256), 0, st, a);
-      else if (a.nbuf <= 16) hipLaunchKernelGGL((ls_eval_kernel<NCP, 16>), dim3(blocks), dim3(256), 0, st, a);
-      else hipLaunchKernelGGL((ls_eval_kernel<NCP, kCgHist>), dim3(blocks), dim3(256), 0, st, a);
+      const dim3 grid(blocks + (a.has_pend != 0 ? 1 : 0));
+      if (a.nbuf <= 8) hipLaunchKernelGGL((ls_eval_kernel<NCP, 8>), grid, dim3(256), 0, st, a);
+      else if (a.nbuf <= 12) hipLaunchKernelGGL((ls_eval_kernel<NCP, 12>), grid, dim3(256), 0, st, a);
+      else if (a.nbuf <= 16) hipLaunchKernelGGL((ls_eval_kernel<NCP, 16>), grid, dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((ls_eval_kernel<NCP, kCgHist>), grid, dim3(256), 0, st, a);
     } else {
       return hipErrorInvalidValue;
     }
