@@ -385,12 +385,17 @@ def test_non_default_stream(cache):
     assert rel_l2(host(hv), orc.hessvec(op, w.X0, w.V)) <= TOL_PRIMITIVE
 
 
-def test_local_newton_replays_from_a_hip_graph(cache):
+@pytest.mark.parametrize("sized_for_params", [False, True])
+def test_local_newton_replays_from_a_hip_graph(cache, sized_for_params):
     """The whole local solve is enqueued without host synchronisation or allocation, so it can be captured
-    once and replayed; every replay (with eager work in between) must give the eager result bit for bit."""
+    once and replayed; every replay (with eager work in between) must give the eager result bit for bit.
+    With a workspace sized for the parameters the solve keeps the directional logits of its CG sweeps (another
+    set of kernels and launches)."""
     w, gp, op = setup_case(cache, "fused_2000x100_C7")
     params = nadmm.make_params(2, 5, w.max_ls, 0.0, 0.0, w.beta, w.gamma)
-    ws = gp.workspace()
+    nbytes = nadmm.nadmm_workspace_bytes(gp, params if sized_for_params else None)
+    assert (nbytes > nadmm.nadmm_workspace_bytes(gp)) == sized_for_params
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     X0 = dev(w.X0.copy())
     X_eager = X0.clone()
     nadmm.nadmm_local_newton(gp, X_eager, params, want_stats=False, ws=ws)   # also the warm-up (kernel attributes)
