@@ -749,6 +749,13 @@ int nadmm_loss_grad(const nadmm_problem* prob, const float* d_X, double* d_loss,
   if ((rc = sweep(prob, L, path, d_ws, ra, d_grad != nullptr, &nparts, st)) != NADMM_OK) return rc;
   if (d_grad) {
     ReduceArgs rg = reduce_args(prob, L, d_ws, nparts, 1, d_X, d_grad, nullptr, nullptr);
+    if (L.s.d <= kReduceFinishMax) {  // short vectors: the objective is finished by a workgroup of the same launch
+      rg.lf_loss_part = at<double>(d_ws, L.loss_part);
+      rg.lf_nblocks = loss_blocks(L, path);
+      rg.lf_loss_out = d_loss;
+      NADMM_HIP(launch_reduce_out(rg, st));
+      return NADMM_OK;
+    }
     rg.pen_part = at<double>(d_ws, L.dotpart);  // penalty terms, summed per workgroup on the way
     NADMM_HIP(launch_reduce_out(rg, st));
   }

@@ -165,7 +165,13 @@ struct ReduceArgs {
   float* cg_r;
   float* cg_d;
   const int32_t* flag;
+  // kind 1, optional (d <= kReduceFinishMax): one more workgroup finishes the objective beside the reduction,
+  // *lf_loss_out = s * sum(lf_loss_part[0 .. lf_nblocks)) + penalty terms of X (from X, z, y themselves)
+  const double* lf_loss_part;
+  int32_t lf_nblocks;
+  double* lf_loss_out;
 };
+constexpr int64_t kReduceFinishMax = 16384;
 int reduce_out_blocks(int64_t d);
 hipError_t launch_reduce_out(const ReduceArgs& a, hipStream_t st);
 

@@ -32,10 +32,78 @@ __device__ __forceinline__ double block_sum(double v, double* sm /* >= 17 double
   return t;
 }
 
+// The objective finished by one workgroup of 256 threads that runs beside the reduction of a gradient's partial sums
+// (ReduceArgs.lf_*): the row losses' partial sums are complete, the penalty terms come from X, z, y themselves.
+// All of a piece's loads (32 elements per vector and thread) are requested before the first is used.
+__device__ __forceinline__ void reduce_loss_finish_role(const ReduceArgs& a) {
+  __shared__ double smd[17];
+  const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;
+  constexpr int PER = 32;
+  const double inv_rho = 1.0 / (double)rho_;
+  // no load under a condition: a missing z or y reads X instead and counts with factor 0
+  const float* __restrict__ zp = a.z != nullptr ? a.z : a.X;
+  const float* __restrict__ yp = a.y != nullptr ? a.y : a.X;
+  const double zf = a.z != nullptr ? 1.0 : 0.0, yf = a.y != nullptr ? inv_rho : 0.0;
+  double acc = 0.0;
+  auto term = [&](float xf, float zv, float yv) {
+    const double x = xf;
+    const double uu = x - zf * (double)zv + yf * (double)yv;
+    return 0.5 * (double)a.lambda * x * x + 0.5 * (double)rho_ * uu * uu;
+  };
+  int64_t done = 0;  // elements handled by the 16-byte path
+  if ((((uintptr_t)a.X | (uintptr_t)zp | (uintptr_t)yp) & 15) == 0) {  // uniform
+    constexpr int PQ = PER / 4;
+    const int64_t n4 = a.d >> 2;
+    for (int64_t base = threadIdx.x; base < n4; base += (int64_t)PQ * 256) {
+      float4 xq[PQ], zq[PQ], yq[PQ];
+#pragma unroll
+      for (int u = 0; u < PQ; ++u) {
+        const int64_t k = base + (int64_t)u * 256;
+        const int64_t kc = k < n4 ? k : n4 - 1;
+        xq[u] = reinterpret_cast<const float4*>(a.X)[kc];
+        zq[u] = reinterpret_cast<const float4*>(zp)[kc];
+        yq[u] = reinterpret_cast<const float4*>(yp)[kc];
+      }
+#pragma unroll
+      for (int u = 0; u < PQ; ++u)
+        if (base + (int64_t)u * 256 < n4)
+          acc += (term(xq[u].x, zq[u].x, yq[u].x) + term(xq[u].y, zq[u].y, yq[u].y)) +
+                 (term(xq[u].z, zq[u].z, yq[u].z) + term(xq[u].w, zq[u].w, yq[u].w));
+    }
+    done = n4 << 2;
+  }
+  for (int64_t base = done + threadIdx.x; base < a.d; base += (int64_t)PER * 256) {
+    float xv[PER], zv[PER], yv[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int64_t e = base + (int64_t)u * 256;
+      const int64_t ec = e < a.d ? e : a.d - 1;
+      xv[u] = a.X[ec];
+      zv[u] = zp[ec];
+      yv[u] = yp[ec];
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u)
+      if (base + (int64_t)u * 256 < a.d) acc += term(xv[u], zv[u], yv[u]);
+  }
+  double data = 0.0;
+  for (int k = threadIdx.x; k < a.lf_nblocks; k += 256) data += a.lf_loss_part[k];
+  const double pen = block_sum(acc, smd);
+  data = block_sum(data, smd);
+  if (threadIdx.x == 0) *a.lf_loss_out = (double)a.scale * data + pen;
+}
+
 // out[e] = s * sum_k partial[k][e] + linear terms.  A workgroup covers 32 elements; its 8
 // thread groups each sum every 8th partial (independent loads in flight), then the 8 group sums
 // are added in a fixed order, so the result does not depend on scheduling.
+// FINISH: launched with one workgroup more, which finishes the objective (an instantiation of its own: that
+// workgroup's registers would cost the plain kernel its occupancy on long vectors).
+template <bool FINISH>
 __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
+  if (FINISH && blockIdx.x == gridDim.x - 1) {  // the workgroup beyond the last 32 elements
+    if (a.flag == nullptr || *a.flag != 0) reduce_loss_finish_role(a);
+    return;
+  }
   __shared__ float sm[8][32];
   const int el = threadIdx.x & 31, grp = threadIdx.x >> 5;
   const int64_t e = (int64_t)blockIdx.x * 32 + el;
@@ -1043,8 +1111,11 @@ int reduce_out_blocks(int64_t d) {
 
 hipError_t launch_reduce_out(const ReduceArgs& a, hipStream_t st) {
   const int blocks = reduce_out_blocks(a.d);
+  if (a.lf_loss_out != nullptr && (a.kind != 1 || a.d > kReduceFinishMax || a.lf_loss_part == nullptr || a.lf_nblocks < 1))
+    return hipErrorInvalidValue;
   if (a.d > kWideFrom) hipLaunchKernelGGL(reduce_out_wide_kernel, dim3(blocks), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL(reduce_out_kernel, dim3(blocks), dim3(256), 0, st, a);
+  else if (a.lf_loss_out != nullptr) hipLaunchKernelGGL(reduce_out_kernel<true>, dim3(blocks + 1), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL(reduce_out_kernel<false>, dim3(blocks), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 

@@ -284,6 +284,36 @@ def test_sum_scaling_and_missing_z_y(cache):
     assert rel_l2(host(nadmm.nadmm_hessvec(gp, dev(X), dev(w.V))), orc.hessvec(op, X, w.V)) <= TOL_PRIMITIVE
 
 
+@pytest.mark.parametrize("missing", ["", "z", "y", "zy"])
+def test_vectors_that_are_only_4_byte_aligned(cache, missing):
+    """X, z, y and the outputs may start at any multiple of 4 bytes; a missing z or y counts as zeros.  (The workgroup
+    that finishes the objective beside the gradient's reduction reads them 16 bytes at a time where it can.)"""
+    w = workloads.generic(700, 40, 6, seed=23)
+    z = None if "z" in missing else w.z
+    y = None if "y" in missing else w.y
+    op = orc.Problem(w.A, w.b, w.C, s=w.s, lam=w.lam, rho=w.rho, z=z, y=y)
+
+    def off(a, k):   # a device copy that starts k floats into a 256-byte aligned buffer
+        if a is None:
+            return None
+        buf = torch.zeros(a.size + 8, dtype=torch.float32, device="cuda")
+        view = buf[k:k + a.size].view(a.shape)
+        view.copy_(torch.from_numpy(np.ascontiguousarray(a)))
+        assert view.data_ptr() % 16 == (4 * k) % 16
+        return view
+
+    f_ref, g_ref = orc.loss_grad(op, w.X0)
+    for kx, kz, ky in ((1, 2, 3), (0, 1, 0), (0, 0, 0)):
+        gp = nadmm.Problem(dev(w.A), dev(w.b), w.C, w.s, w.lam, w.rho, off(z, kz), off(y, ky))
+        X = off(w.X0, kx)
+        grad_out = off(np.zeros_like(w.X0), 3)
+        loss, grad = nadmm.nadmm_loss_grad(gp, X, grad_out=grad_out)
+        assert rel_abs(loss.item(), f_ref) <= TOL_PRIMITIVE
+        assert rel_l2(host(grad), g_ref) <= TOL_PRIMITIVE
+        hv = nadmm.nadmm_hessvec(gp, X, off(w.V, 1))
+        assert rel_l2(host(hv), orc.hessvec(op, w.X0, w.V)) <= TOL_PRIMITIVE
+
+
 @pytest.mark.parametrize("stride", [64, 53])   # 64: every matrix-core path applies; 53: only the vector kernels do
 def test_row_stride_larger_than_p(cache, stride):
     w = workloads.generic(900, 50, 4, seed=22)
