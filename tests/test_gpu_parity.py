@@ -224,15 +224,23 @@ def test_local_newton(cache, name, path):
         st, [(it["alpha"], it["armijo_ok"], it["loss"], it["grad_norm"]) for it in st_ref["iters"]])
 
 
-@pytest.mark.parametrize("cg_tol", [0.0, 3e-2])
-@pytest.mark.parametrize("name", ["image_like_3k", "fused_130x960_C4", "wide_700"])
-def test_local_newton_with_and_without_the_history_of_directional_logits(cache, name, cg_tol):
+# (case, CG iterations, theta, bound on the iterates).  8, 12, 16 or 32 history buffers go into one launch.
+# fused_130x960_C4 has 130 rows for 2880 unknowns: float32 CG loses conjugacy there after some 16 iterations and the
+# iterates leave the float64 oracle's by 1.3e-2 (measured, the same with and without the history); the bound says so.
+HISTORY_CASES = [("image_like_3k", 12, 0.0, TOL_ITERATE), ("image_like_3k", 12, 3e-2, TOL_ITERATE), ("wide_700", 12, 0.0, TOL_ITERATE),
+                 ("image_like_3k", 20, 0.0, TOL_ITERATE), ("image_like_3k", 29, 0.0, TOL_ITERATE),
+                 ("fused_130x960_C4", 5, 0.0, TOL_ITERATE), ("fused_130x960_C4", 12, 3e-2, TOL_ITERATE),
+                 ("fused_130x960_C4", 16, 0.0, TOL_ITERATE), ("fused_130x960_C4", 32, 0.0, 3e-2)]
+
+
+@pytest.mark.parametrize("name,K,cg_tol,bound", HISTORY_CASES)
+def test_local_newton_with_and_without_the_history_of_directional_logits(cache, name, K, cg_tol, bound):
     """A workspace sized for the solve's parameters lets the fused path put A p together from the A d_k its CG sweeps
     leave behind (p = sum_k alpha_k d_k) instead of another pass over A; one sized without parameters takes that
     pass.  Both must follow the oracle, also when CG stops early and leaves part of the history unused."""
     w, gp, op = setup_case(cache, name)
     force_path(gp, 2)
-    T, K = 3, 12
+    T = 3
     params = nadmm.make_params(T, K, w.max_ls, cg_tol, 0.0, w.beta, w.gamma)
     small, large = nadmm.nadmm_workspace_bytes(gp), nadmm.nadmm_workspace_bytes(gp, params)
     assert large >= small + K * w.n * (w.C - 1) * 4      # this shape qualifies for the history
@@ -249,8 +257,9 @@ def test_local_newton_with_and_without_the_history_of_directional_logits(cache, 
         if cg_tol > 0 and name == "image_like_3k":
             assert min(st["cg_iters"]) < K               # the early stop is really exercised
         assert st["alpha"] == pytest.approx([it["alpha"] for it in st_ref["iters"]], rel=1e-6)
-        assert rel_l2(host(X), X_ref) <= TOL_ITERATE
-        assert rel_abs(st["loss_final"], st_ref["loss_final"]) <= TOL_PRIMITIVE
+        assert rel_l2(host(X), X_ref) <= bound
+        if bound == TOL_ITERATE:
+            assert rel_abs(st["loss_final"], st_ref["loss_final"]) <= TOL_PRIMITIVE
         out.append((host(X), st))
     assert out[0][1]["alpha"] == out[1][1]["alpha"]
     assert rel_l2(out[0][0], out[1][0]) <= 1e-4
