@@ -135,7 +135,7 @@ typedef struct nadmm_stats {
 } nadmm_stats;
 
 /* 100 * major + minor; 102: sparse storage of A, residual balancing (struct layouts changed since 100);
- * 103: nadmm_hessvec_static */
+ * 103: nadmm_hessvec_static; 104: nadmm_workspace_bytes / nadmm_admm_workspace_bytes take the parameters into account */
 int         nadmm_version(void);
 const char* nadmm_status_string(int code);
 

@@ -686,7 +686,7 @@ static int admm_lanes(AdmmLanes** out) {
 
 extern "C" {
 
-int nadmm_version(void) { return 103; }
+int nadmm_version(void) { return 104; }
 
 const char* nadmm_status_string(int code) {
   switch (code) {
