@@ -305,7 +305,8 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
                      void* d_ws, size_t ws_bytes, void* stream);
 
 /*
- * Kernel selection, for tests and benchmarks (process-wide, not thread-safe):
+ * Kernel selection, for tests and benchmarks; kept per host thread (it applies to the calls that the same
+ * thread makes afterwards, workspace sizes included), so the library has no state shared between threads:
  *   0 = automatic (default), 1 = two-pass fp32 vector kernels (any shape),
  *   2 = fused single-pass matrix-core kernel (row stride a multiple of 4, A 16-byte aligned,
  *       C-1 <= 16, p <= 960), 3 = thin-data single-pass kernel (p <= 32, p % 4 == 0,

@@ -17,7 +17,7 @@ static __device__ __align__(256) unsigned char scratch[NADMM_STATIC_SCRATCH_BYTE
 namespace nadmm {
 namespace {
 
-int g_path = 0;
+thread_local int g_path = 0;  // kernel path forced by the calling thread (0 = automatic)
 thread_local std::string g_last_hip_error;
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }

@@ -266,3 +266,18 @@ def test_admm_host_validation(lib):
     assert lib.nadmm_admm_consensus(2, 40, fake, fake, fake, rho, 0.1, 0.0, 0.0, None, fake, 1 << 16, None) == nadmm.NADMM_EINVAL
     rho = (C.c_float * 2)(1.0, 1.0)
     assert lib.nadmm_admm_consensus(2, 40, fake, fake, fake, rho, 0.1, 0.0, 0.0, None, fake, 16, None) == nadmm.NADMM_EWORKSPACE
+
+
+def test_kernel_path_switch_is_per_thread(lib):
+    """The forced kernel path belongs to the calling host thread: another thread still sees the automatic choice."""
+    import threading
+    assert lib.nadmm_set_kernel_path(2) == 0
+    try:
+        seen = []
+        t = threading.Thread(target=lambda: seen.append(lib.nadmm_set_kernel_path(1)))
+        t.start()
+        t.join()
+        assert seen == [0]                                # the other thread's previous value: untouched by this one
+        assert lib.nadmm_set_kernel_path(2) == 2          # and its own setting did not reach this thread
+    finally:
+        lib.nadmm_set_kernel_path(0)
