@@ -96,6 +96,30 @@ def test_admm_fixed_iterations(name):
     np.testing.assert_allclose(host(u).sum(0), lam * host(z), atol=1e-5 * max(1.0, float(np.abs(host(u)).max())))
 
 
+@pytest.mark.parametrize("sized_for_params", [True, False])
+def test_admm_workers_with_and_without_the_history_of_directional_logits(sized_for_params):
+    """Shards on the fused path whose shape qualifies for the history of directional logits (nadmm_local_newton): the
+    outer solver's workspace sized for its parameters holds the history of every worker, one sized without parameters
+    is accepted as well and makes the workers take the pass over A instead; both follow the oracle."""
+    w = workloads.generic(3001, 128, 5, seed=37)
+    N, rhos, lam, K, T, Kcg = 3, [0.3, 0.6, 1.2], 1e-2, 3, 2, 6
+    gps, ops = shards_of(w, N, rhos)
+    X0 = (0.05 * np.random.default_rng(7).standard_normal(w.X0.shape)).astype(np.float32)
+    params = nadmm.make_admm_params(K, nadmm.make_params(T, Kcg, w.max_ls, 0.0, 0.0, w.beta, w.gamma))
+    small, large = nadmm.nadmm_admm_workspace_bytes(gps), nadmm.nadmm_admm_workspace_bytes(gps, params)
+    assert large >= small + sum(Kcg * g.n * (w.C - 1) * 4 for g in gps)
+    ws = torch.empty(large if sized_for_params else small, dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    x = dev(np.stack([X0] * N))
+    z, u, st = nadmm.nadmm_admm_solve(gps, lam, x, params, ws=ws)
+    z_ref, xs_ref, ys_ref, hist = adm.admm(ops, lam, rhos, X0, K, T, Kcg, 0.0, 0.0, w.beta, w.gamma, w.max_ls)
+    assert st["outer_iters"] == K
+    assert rel_l2(host(z), z_ref) <= TOL_ITERATE
+    for i in range(N):
+        assert rel_l2(host(x)[i], xs_ref[i]) <= TOL_ITERATE
+    assert st["r_trace"] == pytest.approx([h["r_norm"] for h in hist], rel=5e-3)
+
+
 def test_admm_stops_on_the_residual_test_and_later_iterations_are_no_ops():
     w = workloads.generic(2400, 20, 3, seed=34)
     N, rhos, lam = 3, [0.1, 0.1, 0.1], 5e-2
