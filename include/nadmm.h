@@ -24,13 +24,19 @@
  *     h_stats synchronises the stream.
  *   - Layout of A: row-major n x p float32, row stride lda >= p elements, row i
  *     is sample a_i; or sparse storage, see nadmm_sparse.  The matrix-core kernels read rows in
- *     16-byte pieces, so d_A must be readable for (n-1) lda + 4 ceil(p/4) elements: up to three
- *     elements past the last sample when p is not a multiple of 4 (an n x lda allocation always
- *     is; what those elements hold does not matter).  Which kernels run depends on the stride:
- *     lda a multiple of 4 and d_A 16-byte aligned take the single-pass or two-sweep matrix-core
- *     kernels (50-60 % resp. about 30 % of the HBM roofline); any other stride or alignment
- *     falls to the two-pass float32 vector kernels, which are correct for every shape but 10 to
- *     20 times slower (2-4 % of the roofline): pad rows to a multiple of 4 elements.
+ *     16-byte pieces.  With lda a multiple of 4 and d_A 16-byte aligned the pieces are aligned ones and d_A must be
+ *     readable for (n-1) lda + 4 ceil(p/4) elements: up to three elements past the last sample when p is not a
+ *     multiple of 4 (an n x lda allocation always is; what those elements hold does not matter).  Which kernels run
+ *     depends on shape, stride and alignment:
+ *       p <= 960 and C-1 <= 16: the single-pass matrix-core kernel, 55-60 % of the HBM roofline with aligned rows;
+ *         any other row stride (lda >= p) and a d_A that is only 4-byte aligned take a variant of the same kernel
+ *         that reads nothing past column p-1 of a row and is 10-35 % slower (measured at 60000 x 785: 57 us per
+ *         Hessian-vector product against 42 us at 60000 x 784, a local solve 5.3 against 5.1 ms);
+ *       wider rows or up to 32 free classes: the two-sweep matrix-core kernels (about 30 %), which need lda a multiple
+ *         of 4 and d_A 16-byte aligned;
+ *       otherwise (wide or many-class data on unaligned rows, p < 4 on unaligned rows): the two-pass float32 vector
+ *         kernels, correct for every shape but 10 to 20 times slower (2-4 % of the roofline): pad such rows to a
+ *         multiple of 4 elements.
  *     nadmm_query_kernel_path() tells which path a problem takes.  Labels: int32 in 0..C-1; class C-1 is the reference
  *     class with logit 0 (the paper's class C).  Label values and finiteness
  *     of A are not checked (out-of-range labels are treated as the reference
@@ -312,8 +318,8 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
  * Kernel selection, for tests and benchmarks; kept per host thread (it applies to the calls that the same
  * thread makes afterwards, workspace sizes included), so the library has no state shared between threads:
  *   0 = automatic (default), 1 = two-pass fp32 vector kernels (any shape),
- *   2 = fused single-pass matrix-core kernel (row stride a multiple of 4, A 16-byte aligned,
- *       C-1 <= 16, p <= 960), 3 = thin-data single-pass kernel (p <= 32, p % 4 == 0,
+ *   2 = fused single-pass matrix-core kernel (C-1 <= 16, p <= 960; any row stride, A 4-byte aligned;
+ *       p >= 4 unless the rows are 16-byte aligned), 3 = thin-data single-pass kernel (p <= 32, p % 4 == 0,
  *       C-1 <= 3, lda == p), 4 = column-sliced two-sweep matrix-core kernels (the automatic
  *       choice where 2 and 3 do not apply: row stride a multiple of 4, A 16-byte aligned,
  *       C-1 <= 32), 5 = sparse-storage kernels (the only path for a problem with `sparse` set,

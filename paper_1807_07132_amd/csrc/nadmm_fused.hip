@@ -25,6 +25,11 @@
 namespace nadmm {
 namespace {
 
+// 16 bytes of a row of A that need only start on a 4-byte boundary (ANYSTRIDE kernels)
+struct __attribute__((packed, aligned(4))) Quad {
+  float x, y, z, w;
+};
+
 using namespace mfma_detail;
 
 __device__ __forceinline__ void tile_barrier() { __syncthreads(); }
@@ -48,7 +53,10 @@ struct FusedArgs {
 
 // HALFQ: the vectors of a pending CG update fit SPW quads per thread (half the capacity): the update then carries
 // no surplus work (a wave issues one instruction per four cycles or so, and every workgroup repeats the update).
-template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES, bool HALFQ = false>
+// ANYSTRIDE: rows of A need not start on 16-byte boundaries (any row stride, A 4-byte aligned): the 16-byte pieces are
+// loaded as such, and the last piece of a row is fetched from column p - 4 and shifted into place, so that no load goes
+// past a row's column p - 1.  (A variant of its own: the shifting costs the aligned kernel registers it does not have.)
+template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES, bool HALFQ = false, bool ANYSTRIDE = false>
 __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   const RowArgs& a = fa.r;
   if (a.flag != nullptr && *a.flag == 0) return;
@@ -84,8 +92,9 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   const int64_t r_begin = (int64_t)blockIdx.x * fa.rows_per_wg;
   int64_t r_end = r_begin + fa.rows_per_wg;
   if (r_end > a.n) r_end = a.n;
-  const int col_max = ((p + 3) & ~3) - 4;  // last 16-byte aligned column offset that holds a column of A: no load goes
-                                           // past element 4 ceil(p/4) of a row (<= lda, a multiple of 4)
+  // last column offset a 16-byte piece is fetched from.  Aligned rows: the last aligned piece that holds a column of A (no
+  // load goes past element 4 ceil(p/4) of a row, <= lda); ANYSTRIDE: the last piece that lies inside the row
+  const int col_max = ANYSTRIDE ? p - 4 : ((p + 3) & ~3) - 4;
 
   // ---- prefetch registers: [step][row block][half of the 8 columns] ----
   // Addresses are clamped into the matrix, so the loads need no branches; rows
@@ -103,7 +112,13 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int c0 = col + 4 * h;
-        pf[i][rb][h] = *reinterpret_cast<const float4*>(src + (c0 < col_max ? c0 : col_max));
+        const float* at = src + (c0 < col_max ? c0 : col_max);
+        if constexpr (ANYSTRIDE) {
+          const Quad q = *reinterpret_cast<const Quad*>(at);
+          pf[i][rb][h] = float4{q.x, q.y, q.z, q.w};
+        } else {
+          pf[i][rb][h] = *reinterpret_cast<const float4*>(at);
+        }
       }
     }
   };
@@ -217,11 +232,24 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
             const int c0 = col + 4 * h;
-            const int nv = c0 <= col_max ? p - c0 : 0;  // valid elements of this float4 (clamped loads hold other columns)
+            if constexpr (ANYSTRIDE) {
+              // a piece fetched from column p - 4 holds its columns `shift` places further up; what lies past p is zero
+              const int shift = c0 - (c0 < col_max ? c0 : col_max);  // 0: the piece is its own; >= 4: all of it is past p
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              av[0][4 * h + e] = e < nv ? av[0][4 * h + e] : 0.f;
-              av[1][4 * h + e] = e < nv ? av[1][4 * h + e] : 0.f;
+              for (int rb = 0; rb < 2; ++rb) {
+                const float q0 = av[rb][4 * h], q1 = av[rb][4 * h + 1], q2 = av[rb][4 * h + 2], q3 = av[rb][4 * h + 3];
+                av[rb][4 * h + 0] = shift == 0 ? q0 : (shift == 1 ? q1 : (shift == 2 ? q2 : (shift == 3 ? q3 : 0.f)));
+                av[rb][4 * h + 1] = shift == 0 ? q1 : (shift == 1 ? q2 : (shift == 2 ? q3 : 0.f));
+                av[rb][4 * h + 2] = shift == 0 ? q2 : (shift == 1 ? q3 : 0.f);
+                av[rb][4 * h + 3] = shift == 0 ? q3 : 0.f;
+              }
+            } else {
+              const int nv = c0 <= col_max ? p - c0 : 0;  // valid elements of this float4 (clamped loads hold other columns)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                av[0][4 * h + e] = e < nv ? av[0][4 * h + e] : 0.f;
+                av[1][4 * h + e] = e < nv ? av[1][4 * h + e] : 0.f;
+              }
             }
           }
         }
@@ -416,13 +444,21 @@ int num_cus() {
 
 int steps_of(int p) { return (p + kStepCols - 1) / kStepCols; }
 
+template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES, bool HALFQ, bool ANYSTRIDE>
+hipError_t launch_ks(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t st) {
+  static uint64_t lds_set = 0;  // per device
+  hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&fused_kernel<SPW, KIND, HAS0, HAS1, STORES, HALFQ, ANYSTRIDE>), &lds_set);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((fused_kernel<SPW, KIND, HAS0, HAS1, STORES, HALFQ, ANYSTRIDE>), dim3(grid), dim3(kThreads), lds_bytes, st, fa);
+  return hipGetLastError();
+}
+
+bool rows_16_byte_aligned(const RowArgs& a) { return (a.lda & 3) == 0 && (reinterpret_cast<uintptr_t>(a.A) & 15) == 0; }
+
 template <int SPW, int KIND, bool HAS0, bool HAS1, bool STORES, bool HALFQ = false>
 hipError_t launch_k(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t st) {
-  static uint64_t lds_set = 0;  // per device
-  hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&fused_kernel<SPW, KIND, HAS0, HAS1, STORES, HALFQ>), &lds_set);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((fused_kernel<SPW, KIND, HAS0, HAS1, STORES, HALFQ>), dim3(grid), dim3(kThreads), lds_bytes, st, fa);
-  return hipGetLastError();
+  if (rows_16_byte_aligned(fa.r)) return launch_ks<SPW, KIND, HAS0, HAS1, STORES, HALFQ, false>(fa, grid, lds_bytes, st);
+  return launch_ks<SPW, KIND, HAS0, HAS1, STORES, HALFQ, true>(fa, grid, lds_bytes, st);
 }
 
 // Kernels that may store rows of P / Z are separate instantiations: a store between the prefetch
@@ -474,7 +510,8 @@ hipError_t launch_spw(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream
 bool fused_supported(const Shape& s, int64_t lda, const void* A) {
   if (s.NC > 16) return false;
   if (steps_of(s.p) > kMaxSteps) return false;
-  if ((lda & 3) != 0 || (reinterpret_cast<uintptr_t>(A) & 15) != 0) return false;
+  if ((reinterpret_cast<uintptr_t>(A) & 3) != 0 || lda < s.p) return false;
+  if (((lda & 3) != 0 || (reinterpret_cast<uintptr_t>(A) & 15) != 0) && s.p < 4) return false;  // whole 16-byte pieces inside a row
   return true;
 }
 
