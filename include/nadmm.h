@@ -29,14 +29,13 @@
  *     multiple of 4 (an n x lda allocation always is; what those elements hold does not matter).  Which kernels run
  *     depends on shape, stride and alignment:
  *       p <= 960 and C-1 <= 16: the single-pass matrix-core kernel, 55-60 % of the HBM roofline with aligned rows;
- *         any other row stride (lda >= p) and a d_A that is only 4-byte aligned take a variant of the same kernel
- *         that reads nothing past column p-1 of a row and is 10-35 % slower (measured at 60000 x 785: 57 us per
- *         Hessian-vector product against 42 us at 60000 x 784, a local solve 5.3 against 5.1 ms);
- *       wider rows or up to 32 free classes: the two-sweep matrix-core kernels (about 30 %), which need lda a multiple
- *         of 4 and d_A 16-byte aligned;
- *       otherwise (wide or many-class data on unaligned rows, p < 4 on unaligned rows): the two-pass float32 vector
- *         kernels, correct for every shape but 10 to 20 times slower (2-4 % of the roofline): pad such rows to a
- *         multiple of 4 elements.
+ *       wider rows or up to 32 free classes: the two-sweep matrix-core kernels (about 30 %);
+ *       any other row stride (lda >= p) and a d_A that is only 4-byte aligned take variants of the same kernels that
+ *         read nothing past column p-1 of a row and are 15-35 % slower (measured: Hessian-vector product at
+ *         60000 x 785, C = 10: 57 us against 42 us at 60000 x 784, a local solve 5.3 against 5.1 ms; at 50000 x 3073:
+ *         301 against 245 us; at 250000 x 2001, C = 20: 1.02 against 0.89 ms);
+ *       rows shorter than 16 bytes (p < 4) that are not 16-byte aligned: the two-pass float32 vector kernels,
+ *         correct for every shape but 10 to 20 times slower (2-4 % of the roofline).
  *     nadmm_query_kernel_path() tells which path a problem takes.  Labels: int32 in 0..C-1; class C-1 is the reference
  *     class with logit 0 (the paper's class C).  Label values and finiteness
  *     of A are not checked (out-of-range labels are treated as the reference
@@ -321,8 +320,8 @@ int nadmm_admm_solve(const nadmm_problem* h_workers, int32_t N, float lambda, fl
  *   2 = fused single-pass matrix-core kernel (C-1 <= 16, p <= 960; any row stride, A 4-byte aligned;
  *       p >= 4 unless the rows are 16-byte aligned), 3 = thin-data single-pass kernel (p <= 32, p % 4 == 0,
  *       C-1 <= 3, lda == p), 4 = column-sliced two-sweep matrix-core kernels (the automatic
- *       choice where 2 and 3 do not apply: row stride a multiple of 4, A 16-byte aligned,
- *       C-1 <= 32), 5 = sparse-storage kernels (the only path for a problem with `sparse` set,
+ *       choice where 2 and 3 do not apply: C-1 <= 32; any row stride, A 4-byte aligned; p >= 4 unless
+ *       the rows are 16-byte aligned), 5 = sparse-storage kernels (the only path for a problem with `sparse` set,
  *       and only for those).  A forced path that does not support the problem makes the
  *       compute calls return NADMM_EUNSUPPORTED.
  * Returns the previous value, or NADMM_EINVAL.

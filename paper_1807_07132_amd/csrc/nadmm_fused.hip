@@ -25,11 +25,6 @@
 namespace nadmm {
 namespace {
 
-// 16 bytes of a row of A that need only start on a 4-byte boundary (ANYSTRIDE kernels)
-struct __attribute__((packed, aligned(4))) Quad {
-  float x, y, z, w;
-};
-
 using namespace mfma_detail;
 
 __device__ __forceinline__ void tile_barrier() { __syncthreads(); }

@@ -67,6 +67,12 @@ struct DevState {
   nadmm_stats stats;  // copied to the host at the end of nadmm_local_newton
 };
 
+// 16 bytes of a row of A that need only start on a 4-byte boundary: the load type of the matrix-core kernels' variants
+// for rows that are not 16-byte aligned (any row stride, A 4-byte aligned).
+struct __attribute__((packed, aligned(4))) Quad {
+  float x, y, z, w;
+};
+
 // Row-pass (forward) work description, shared by the two-pass and the fused kernels.
 //   kind 0  Hessian-vector rows:  D = P o W - P o rowsum(P o W)         (Section 2.6)
 //   kind 1  gradient rows:        R = P - Y, row losses                  (Sections 2.1, 2.2)

@@ -57,6 +57,8 @@ __device__ __forceinline__ WaveSteps wave_steps(const SlicedArgs& sa, int slice,
 }
 
 // Loads of one step (2 row blocks x 8 columns per lane), addresses clamped into the matrix.
+// ANY: rows need not start on 16-byte boundaries; col_max is then p - 4, the last piece that lies inside a row.
+template <bool ANY>
 __device__ __forceinline__ void load_step_regs(const RowArgs& a, float4 (&pf)[2][2], int64_t row0, int64_t r_end,
                                                int col, int col_max, int m) {
 #pragma unroll
@@ -67,14 +69,20 @@ __device__ __forceinline__ void load_step_regs(const RowArgs& a, float4 (&pf)[2]
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int c0 = col + 4 * h;
-      pf[rb][h] = *reinterpret_cast<const float4*>(src + (c0 < col_max ? c0 : col_max));
+      const float* at = src + (c0 < col_max ? c0 : col_max);
+      if constexpr (ANY) {
+        const Quad q = *reinterpret_cast<const Quad*>(at);
+        pf[rb][h] = float4{q.x, q.y, q.z, q.w};
+      } else {
+        pf[rb][h] = *reinterpret_cast<const float4*>(at);
+      }
     }
   }
 }
 
 // Registers of one step -> bf16 high/low operands of both row blocks (and, if THREE, the third parts
 // that the full-accuracy logit product needs); columns past p are zeroed.
-template <bool THREE>
+template <bool THREE, bool ANY>
 __device__ __forceinline__ void convert_step(const float4 (&pf)[2][2], int col, int col_max, int p, bool ragged,
                                              u32x4 (&ahi)[2], u32x4 (&alo)[2], u32x4 (&alo2)[2]) {
   float av[2][8];
@@ -87,11 +95,24 @@ __device__ __forceinline__ void convert_step(const float4 (&pf)[2][2], int col, 
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int c0 = col + 4 * h;
-      const int nv = c0 <= col_max ? p - c0 : 0;
+      if constexpr (ANY) {
+        // a piece fetched from column p - 4 holds its columns `shift` places further up; what lies past p is zero
+        const int shift = c0 - (c0 < col_max ? c0 : col_max);  // 0: the piece is its own; >= 4: all of it is past p
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        av[0][4 * h + e] = e < nv ? av[0][4 * h + e] : 0.f;
-        av[1][4 * h + e] = e < nv ? av[1][4 * h + e] : 0.f;
+        for (int rb = 0; rb < 2; ++rb) {
+          const float q0 = av[rb][4 * h], q1 = av[rb][4 * h + 1], q2 = av[rb][4 * h + 2], q3 = av[rb][4 * h + 3];
+          av[rb][4 * h + 0] = shift == 0 ? q0 : (shift == 1 ? q1 : (shift == 2 ? q2 : (shift == 3 ? q3 : 0.f)));
+          av[rb][4 * h + 1] = shift == 0 ? q1 : (shift == 1 ? q2 : (shift == 2 ? q3 : 0.f));
+          av[rb][4 * h + 2] = shift == 0 ? q2 : (shift == 1 ? q3 : 0.f);
+          av[rb][4 * h + 3] = shift == 0 ? q3 : 0.f;
+        }
+      } else {
+        const int nv = c0 <= col_max ? p - c0 : 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          av[0][4 * h + e] = e < nv ? av[0][4 * h + e] : 0.f;
+          av[1][4 * h + e] = e < nv ? av[1][4 * h + e] : 0.f;
+        }
       }
     }
   }
@@ -107,7 +128,7 @@ __device__ __forceinline__ void convert_step(const float4 (&pf)[2][2], int col, 
 // ------------------------------------------------------------------------------------------------
 // sweep 1: partial logits of one column slice
 // ------------------------------------------------------------------------------------------------
-template <int SPW, int NB, bool HAS0, bool HAS1>
+template <int SPW, int NB, bool HAS0, bool HAS1, bool ANY>
 __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs sa) {
   const RowArgs& a = sa.r;
   if (a.flag != nullptr && *a.flag == 0) return;
@@ -124,7 +145,7 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
   const int NC = a.NC, p = a.p;
   const int slice = blockIdx.x;
   const WaveSteps ws = wave_steps(sa, slice, wave);
-  const int col_max = ((p + 3) & ~3) - 4;  // no load goes past element 4 ceil(p/4) of a row
+  const int col_max = ANY ? p - 4 : ((p + 3) & ~3) - 4;  // no load goes past element 4 ceil(p/4) of a row (ANY: past column p - 1)
 
   const int64_t r_begin = (int64_t)blockIdx.y * sa.rows_per_wg;
   int64_t r_end = r_begin + sa.rows_per_wg;
@@ -137,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
   float4 pf[SPW][2][2];
 #pragma unroll
   for (int i = 0; i < SPW; ++i)
-    if (step_exists(i)) load_step_regs(a, pf[i], r_begin, r_end, col_of(i), col_max, m);
+    if (step_exists(i)) load_step_regs<ANY>(a, pf[i], r_begin, r_end, col_of(i), col_max, m);
 
   // operands [X|V] of this wave's steps: hi / lo, per class block; X in three parts (full-accuracy logits)
   u32x4 bx_hi[SPW][NB], bx_lo[SPW][NB], bx_lo2[SPW][NB], bv_hi[SPW][NB], bv_lo[SPW][NB];
@@ -176,8 +197,8 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
       if (step_exists(i)) {
         const int col = col_of(i);
         u32x4 ahi[2], alo[2], alo2[2];
-        convert_step<HAS0>(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo, alo2);
-        load_step_regs(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
+        convert_step<HAS0, ANY>(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo, alo2);
+        load_step_regs<ANY>(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -248,7 +269,7 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
 // ------------------------------------------------------------------------------------------------
 // sweep 2: out^T[:, slice] += D^T A[:, slice]
 // ------------------------------------------------------------------------------------------------
-template <int SPW, int NB>
+template <int SPW, int NB, bool ANY>
 __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs sa) {
   const RowArgs& a = sa.r;
   if (a.flag != nullptr && *a.flag == 0) return;
@@ -261,7 +282,7 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
   const int NC = a.NC, p = a.p;
   const int slice = blockIdx.x;
   const WaveSteps ws = wave_steps(sa, slice, wave);
-  const int col_max = ((p + 3) & ~3) - 4;  // no load goes past element 4 ceil(p/4) of a row
+  const int col_max = ANY ? p - 4 : ((p + 3) & ~3) - 4;  // no load goes past element 4 ceil(p/4) of a row (ANY: past column p - 1)
 
   const int64_t r_begin = (int64_t)blockIdx.y * sa.rows_per_wg;
   int64_t r_end = r_begin + sa.rows_per_wg;
@@ -298,7 +319,7 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
   if (r_begin < r_end) {
 #pragma unroll
     for (int i = 0; i < SPW; ++i)
-      if (step_exists(i)) load_step_regs(a, pf[i], r_begin, r_end, col_of(i), col_max, m);
+      if (step_exists(i)) load_step_regs<ANY>(a, pf[i], r_begin, r_end, col_of(i), col_max, m);
     load_d(r_begin);
   }
 
@@ -328,8 +349,8 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
         const int col = col_of(i);
         const int sl = ws.local0 + i;  // step inside the slice
         u32x4 ahi[2], alo[2], unused[2];
-        convert_step<false>(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo, unused);
-        load_step_regs(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
+        convert_step<false, ANY>(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo, unused);
+        load_step_regs<ANY>(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
         char* base = cm + (size_t)sl * kStepBytes;
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
@@ -377,14 +398,22 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
   }
 }
 
-template <int SPW, int NB, bool HAS0, bool HAS1>
-hipError_t launch_logits_t(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
+bool rows_16_byte_aligned(const RowArgs& a) { return (a.lda & 3) == 0 && (reinterpret_cast<uintptr_t>(a.A) & 15) == 0; }
+
+template <int SPW, int NB, bool HAS0, bool HAS1, bool ANY>
+hipError_t launch_logits_a(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
   const size_t lds = ((size_t)kWaves * (2 * NB * 2) * 4 * 64 + (size_t)kLogitBatchFloats) * sizeof(float);
   static uint64_t lds_set = 0;  // per device
-  hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&slice_logits_kernel<SPW, NB, HAS0, HAS1>), &lds_set);
+  hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&slice_logits_kernel<SPW, NB, HAS0, HAS1, ANY>), &lds_set);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((slice_logits_kernel<SPW, NB, HAS0, HAS1>), grid, dim3(kThreads), lds, st, sa);
+  hipLaunchKernelGGL((slice_logits_kernel<SPW, NB, HAS0, HAS1, ANY>), grid, dim3(kThreads), lds, st, sa);
   return hipGetLastError();
+}
+
+template <int SPW, int NB, bool HAS0, bool HAS1>
+hipError_t launch_logits_t(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
+  if (rows_16_byte_aligned(sa.r)) return launch_logits_a<SPW, NB, HAS0, HAS1, false>(sa, grid, st);
+  return launch_logits_a<SPW, NB, HAS0, HAS1, true>(sa, grid, st);
 }
 
 template <int SPW, int NB>
@@ -396,21 +425,28 @@ hipError_t launch_logits_nb(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
   return hipErrorInvalidValue;
 }
 
-template <int SPW, int NB>
-hipError_t launch_cols_t(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
+template <int SPW, int NB, bool ANY>
+hipError_t launch_cols_a(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
   const size_t lds = (size_t)sa.steps_max * kStepBytes;
   static uint64_t lds_set = 0;  // per device
-  hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&slice_cols_kernel<SPW, NB>), &lds_set);
+  hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&slice_cols_kernel<SPW, NB, ANY>), &lds_set);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((slice_cols_kernel<SPW, NB>), grid, dim3(kThreads), lds, st, sa);
+  hipLaunchKernelGGL((slice_cols_kernel<SPW, NB, ANY>), grid, dim3(kThreads), lds, st, sa);
   return hipGetLastError();
+}
+
+template <int SPW, int NB>
+hipError_t launch_cols_t(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
+  if (rows_16_byte_aligned(sa.r)) return launch_cols_a<SPW, NB, false>(sa, grid, st);
+  return launch_cols_a<SPW, NB, true>(sa, grid, st);
 }
 
 }  // namespace
 
 bool sliced_supported(const Shape& s, int64_t lda, const void* A) {
   if (s.NC > 32) return false;
-  if ((lda & 3) != 0 || (reinterpret_cast<uintptr_t>(A) & 15) != 0) return false;
+  if ((reinterpret_cast<uintptr_t>(A) & 3) != 0 || lda < s.p) return false;
+  if (((lda & 3) != 0 || (reinterpret_cast<uintptr_t>(A) & 15) != 0) && s.p < 4) return false;  // whole 16-byte pieces inside a row
   return true;
 }
 

@@ -142,7 +142,7 @@ def test_workspace_bytes_with_parameters(lib):
     pr = nadmm.make_params(10, 10, 10, 0.0, 0.0, 1e-4, 0.5)
     for other in (fake_problem(n=1375000, p=28, Cc=2),            # thin-data path
                   fake_problem(n=50000, p=3072, Cc=10),           # column-sliced path
-                  fake_problem(n=50000, p=3072, Cc=10, lda=3073)):  # wide rows that are not 16-byte aligned: vector path
+                  fake_problem(n=50000, p=3072, Cc=10, lda=3073)):  # the same on rows that are not 16-byte aligned
         assert lib.nadmm_workspace_bytes(C.byref(other), C.byref(pr)) == lib.nadmm_workspace_bytes(C.byref(other), None)
 
 
@@ -203,8 +203,8 @@ def test_kernel_path_switch(lib):
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem())) == 1
     assert lib.nadmm_set_kernel_path(7) == nadmm.NADMM_EINVAL
     lib.nadmm_set_kernel_path(0)
-    # automatic selection: thin data -> 3, medium width -> 2 (any row stride), wide or many classes -> 4 (rows 16-byte
-    # aligned) or else -> 1
+    # automatic selection: thin data -> 3, medium width -> 2, wide or many classes -> 4 (both for any row stride), rows
+    # shorter than 16 bytes that are not 16-byte aligned -> 1
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=1000, p=20, Cc=3))) == 3
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=60000, p=784, Cc=10))) == 2
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=50000, p=3072, Cc=10))) == 4
@@ -212,8 +212,9 @@ def test_kernel_path_switch(lib):
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=5))) == 2
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=5, A=0x1004))) == 2      # 4-byte aligned A
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=3, Cc=5))) == 1                  # no 16-byte piece in a row
-    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=2001, Cc=5))) == 1               # wide and unaligned
-    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=20))) == 1                # many classes and unaligned
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=2001, Cc=5))) == 4               # wide and unaligned
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=20))) == 4                # many classes and unaligned
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=20, A=0x1002))) == 1      # A not 4-byte aligned
     # a forced path that cannot take the shape is reported, on the host
     lib.nadmm_set_kernel_path(3)
     fake = C.c_void_p(0x3000)

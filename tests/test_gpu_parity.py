@@ -50,6 +50,9 @@ CASES = {
     "fused_4100x36_C17": lambda: workloads.generic(4100, 36, 17, seed=14, x_std=0.2),
     "fused_130x960_C4": lambda: workloads.generic(130, 960, 4, seed=15, x_std=0.05),
     "fused_8200x64_C2": lambda: workloads.generic(8200, 64, 2, seed=16),
+    # rows that are not 16-byte aligned (odd p, lda = p) on the matrix-core paths: their any-stride instantiations
+    "fused_any_3000x785_C10": lambda: workloads.generic(3000, 785, 10, seed=41, x_std=0.03, mean=True),
+    "sliced_any_700x1101_C4": lambda: workloads.generic(700, 1101, 4, seed=42, x_std=0.05),
     # shapes the thin-data kernel takes (p <= 32, p % 4 == 0, C-1 <= 3, contiguous rows)
     "thin_5000x4_C2": lambda: workloads.generic(5000, 4, 2, seed=17),
     "thin_70001x32_C3": lambda: workloads.generic(70001, 32, 3, seed=18, mean=True),
@@ -136,7 +139,8 @@ def test_hessvec(cache, name, path):
 @pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("name", ["tiny", "image_like_3k", "tall_binary_50k", "ragged_1237x45_C5", "ragged_333x130_C12",
                                   "fused_2000x100_C7", "fused_130x960_C4", "thin_5000x4_C2", "thin_256x8_C2", "sliced_1500x1100_C4",
-                                  "sliced_33x1604_C33", "wide_700", "long_vectors_40x70000_C5"])
+                                  "sliced_33x1604_C33", "wide_700", "long_vectors_40x70000_C5", "fused_any_3000x785_C10",
+                                  "sliced_any_700x1101_C4"])
 def test_cg_fixed_iterations(cache, name, path):
     w, gp, op = setup_case(cache, name)
     force_path(gp, path)
@@ -194,6 +198,7 @@ def test_line_search(cache, name, path):
 
 
 NEWTON_CASES = ["tiny", "image_like_3k", "wide_700", "tall_binary_50k", "large_multiclass_900", "ragged_1237x45_C5",
+                "fused_any_3000x785_C10", "sliced_any_700x1101_C4",
                 "single_row_1x7_C4", "fused_9001x260_C10", "fused_4100x36_C17", "thin_70001x32_C3", "thin_300x12_C4", "sliced_3000x100_C26",
                 "sliced_1500x1100_C4", "long_vectors_40x70000_C5"]
 
@@ -328,7 +333,7 @@ def test_vectors_that_are_only_4_byte_aligned(cache, missing):
         assert rel_l2(host(hv), orc.hessvec(op, w.X0, w.V)) <= TOL_PRIMITIVE
 
 
-@pytest.mark.parametrize("stride", [64, 53])   # 64: every matrix-core path applies; 53: the fused one (any stride) and the vector kernels
+@pytest.mark.parametrize("stride", [64, 53])   # rows 16-byte aligned or not: every path applies either way
 def test_row_stride_larger_than_p(cache, stride):
     w = workloads.generic(900, 50, 4, seed=22)
     op = oracle_problem(w)
@@ -339,11 +344,7 @@ def test_row_stride_larger_than_p(cache, stride):
     ran = 0
     for path in PATHS:
         nadmm.nadmm_set_kernel_path(path)
-        try:
-            nadmm.nadmm_query_kernel_path(gp)
-        except nadmm.NadmmError as e:
-            assert e.code == nadmm.NADMM_EUNSUPPORTED and stride % 4 != 0 and path == 4
-            continue
+        nadmm.nadmm_query_kernel_path(gp)
         ran += 1
         loss, grad = nadmm.nadmm_loss_grad(gp, dev(w.X0))
         assert rel_abs(loss.item(), orc.loss(op, w.X0)) <= TOL_PRIMITIVE
@@ -354,7 +355,7 @@ def test_row_stride_larger_than_p(cache, stride):
         st = nadmm.nadmm_local_newton(gp, X, params)
         X_ref, st_ref, _ = oracle_newton_following(op, w.X0, dataclasses.replace(w, max_cg=5), st["alpha"], max_newton=2)
         assert rel_l2(host(X), X_ref) <= TOL_ITERATE
-    assert ran == (4 if stride % 4 == 0 else 3)
+    assert ran == 4
 
 
 @pytest.mark.parametrize("shape", [(400, 30, 5), (400, 32, 5), (700, 32, 3), (300, 1000, 4)])
