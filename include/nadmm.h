@@ -34,8 +34,10 @@
  *         read nothing past column p-1 of a row and are 15-35 % slower (measured: Hessian-vector product at
  *         60000 x 785, C = 10: 57 us against 42 us at 60000 x 784, a local solve 5.3 against 5.1 ms; at 50000 x 3073:
  *         301 against 245 us; at 250000 x 2001, C = 20: 1.02 against 0.89 ms);
- *       rows shorter than 16 bytes (p < 4) that are not 16-byte aligned: the two-pass float32 vector kernels,
- *         correct for every shape but 10 to 20 times slower (2-4 % of the roofline).
+ *       rows of fewer than 48 columns that are not 16-byte aligned (and any A that is not 4-byte aligned): the
+ *         two-pass float32 vector kernels, correct for every shape; on narrow rows they are the faster choice
+ *         (1375000 x 29: 152 us per Hessian-vector product against 260 us), on wide rows 10 to 20 times slower
+ *         than the matrix-core kernels (2-4 % of the roofline).
  *     nadmm_query_kernel_path() tells which path a problem takes.  Labels: int32 in 0..C-1; class C-1 is the reference
  *     class with logit 0 (the paper's class C).  Label values and finiteness
  *     of A are not checked (out-of-range labels are treated as the reference

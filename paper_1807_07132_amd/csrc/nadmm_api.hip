@@ -36,10 +36,16 @@ struct Layout {
   int gen_row_blocks, gen_slabs, gen_chunks, gen_rpc;
   int fused_parts, thin_parts, sliced_parts;
   bool fused_ok, thin_ok, sliced_ok;
+  bool mc_auto;  // the matrix-core paths are also the automatic choice (see kAnyStrideMinP)
   bool sparse;
   int nwin_rows, nwin_cols;
   const float* rho_scale;  // device scalar factor on rho (outer solver with an adaptive penalty), or NULL
 };
+
+// Rows that are not 16-byte aligned take the matrix-core kernels' any-stride variants automatically only from this many
+// columns on: with fewer, most waves of those kernels have no column step and the vector kernels are faster (measured
+// per Hessian-vector product: 1375000 x 29: 260 against 152 us, 200000 x 13: 47 against 37 us, 100000 x 70: 29 against 75 us).
+constexpr int kAnyStrideMinP = 48;
 
 int validate_problem(const nadmm_problem* p, bool need_labels) {
   if (p == nullptr) return NADMM_EINVAL;
@@ -81,6 +87,7 @@ void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg
   L->gen_row_blocks = generic_row_blocks(s.n);
   generic_col_grid(s, &L->gen_slabs, &L->gen_chunks, &L->gen_rpc);
   if (L->sparse) L->gen_chunks = 1;  // the column view gives every element of A^T D whole
+  L->mc_auto = L->sparse || (((p->lda & 3) == 0 && (reinterpret_cast<uintptr_t>(p->d_A) & 15) == 0) || s.p >= kAnyStrideMinP);
   L->fused_ok = !L->sparse && fused_supported(s, p->lda, p->d_A);
   L->fused_parts = L->fused_ok ? fused_num_partials(s) : 0;
   if (wg_cap > 0 && L->fused_parts > wg_cap) L->fused_parts = wg_cap;
@@ -137,7 +144,7 @@ void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg
   }
   L->total_base = off;
   // 2 max_cg n (C-1) floats written and read instead of n p floats read: taken with a margin
-  const bool fused_default = L->fused_ok && (g_path == 2 || (g_path == 0 && !L->thin_ok));
+  const bool fused_default = L->fused_ok && (g_path == 2 || (g_path == 0 && !L->thin_ok && L->mc_auto));
   L->hist_bufs = (!hv_only && fused_default && max_cg >= 1 && max_cg <= kCgHist && (int64_t)3 * max_cg * s.NC <= s.p) ? max_cg : 0;
   L->hist = off; off += (size_t)L->hist_bufs * rows;
   L->total = off;
@@ -207,7 +214,7 @@ int choose_path(const Layout& L, int* path) {
     *path = 4;
     return NADMM_OK;
   }
-  *path = L.thin_ok ? 3 : (L.fused_ok ? 2 : (L.sliced_ok ? 4 : 1));
+  *path = L.thin_ok ? 3 : (L.fused_ok && L.mc_auto ? 2 : (L.sliced_ok && L.mc_auto ? 4 : 1));
   return NADMM_OK;
 }
 

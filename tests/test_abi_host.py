@@ -203,18 +203,25 @@ def test_kernel_path_switch(lib):
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem())) == 1
     assert lib.nadmm_set_kernel_path(7) == nadmm.NADMM_EINVAL
     lib.nadmm_set_kernel_path(0)
-    # automatic selection: thin data -> 3, medium width -> 2, wide or many classes -> 4 (both for any row stride), rows
-    # shorter than 16 bytes that are not 16-byte aligned -> 1
+    # automatic selection: thin data -> 3, medium width -> 2, wide or many classes -> 4; rows that are not 16-byte aligned
+    # take the same from 48 columns on, the vector kernels (1) below that
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=1000, p=20, Cc=3))) == 3
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=60000, p=784, Cc=10))) == 2
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=50000, p=3072, Cc=10))) == 4
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=250000, p=2000, Cc=20))) == 4
-    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=5))) == 2
-    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=5, A=0x1004))) == 2      # 4-byte aligned A
-    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=3, Cc=5))) == 1                  # no 16-byte piece in a row
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=5))) == 1
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=49, Cc=5))) == 2
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=48, Cc=5, A=0x1004))) == 2      # 4-byte aligned A
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=36, Cc=5))) == 2                 # aligned rows: any p
     assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=2001, Cc=5))) == 4               # wide and unaligned
-    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=20))) == 4                # many classes and unaligned
-    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=20, A=0x1002))) == 1      # A not 4-byte aligned
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=49, Cc=20))) == 4                # many classes and unaligned
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=20))) == 1
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=49, Cc=20, A=0x1002))) == 1      # A not 4-byte aligned
+    # forced: the any-stride variants take narrow rows too, down to one 16-byte piece
+    lib.nadmm_set_kernel_path(2)
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=45, Cc=5))) == 2
+    assert lib.nadmm_query_kernel_path(C.byref(fake_problem(n=500, p=3, Cc=5))) == nadmm.NADMM_EUNSUPPORTED
+    lib.nadmm_set_kernel_path(0)
     # a forced path that cannot take the shape is reported, on the host
     lib.nadmm_set_kernel_path(3)
     fake = C.c_void_p(0x3000)
