@@ -230,13 +230,6 @@ def nadmm_workspace_bytes(prob: Problem, params: Optional[nadmm_params] = None) 
     return int(lib().nadmm_workspace_bytes(C.byref(prob.c), C.byref(params) if params is not None else None))
 
 
-def alloc_workspace(prob: Problem) -> torch.Tensor:
-    nbytes = nadmm_workspace_bytes(prob)
-    if nbytes == 0:
-        raise NadmmError(NADMM_EINVAL)
-    return torch.empty(nbytes, dtype=torch.uint8, device=prob.A.device)
-
-
 def nadmm_set_kernel_path(path: int) -> int:
     rc = lib().nadmm_set_kernel_path(int(path))
     if rc < 0:
