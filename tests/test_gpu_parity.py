@@ -234,6 +234,7 @@ def test_local_newton(cache, name, path):
 # iterates leave the float64 oracle's by 1.3e-2 (measured, the same with and without the history); the bound says so.
 HISTORY_CASES = [("image_like_3k", 12, 0.0, TOL_ITERATE), ("image_like_3k", 12, 3e-2, TOL_ITERATE), ("wide_700", 12, 0.0, TOL_ITERATE),
                  ("image_like_3k", 20, 0.0, TOL_ITERATE), ("image_like_3k", 29, 0.0, TOL_ITERATE),
+                 ("fused_130x960_C4", 1, 0.0, TOL_ITERATE), ("fused_130x960_C4", 2, 0.0, TOL_ITERATE),
                  ("fused_130x960_C4", 5, 0.0, TOL_ITERATE), ("fused_130x960_C4", 12, 3e-2, TOL_ITERATE),
                  ("fused_130x960_C4", 16, 0.0, TOL_ITERATE), ("fused_130x960_C4", 32, 0.0, 3e-2)]
 
