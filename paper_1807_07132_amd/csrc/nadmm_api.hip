@@ -27,7 +27,7 @@ struct Layout {
   size_t state, g, pdir, r, dvec, q;
   size_t pdir2, r2, dvec2, pfinal;  // second vector set and final iterate of the deferred CG update (fused path)
   size_t drows, pcache, zx, zp;
-  size_t partial, loss_part, lpart, dotpart, rrpart, zw;
+  size_t partial, loss_part, lpart, dotpart, rrpart, headpart, zw;
   size_t pack, win_rows, win_cols;  // sparse storage: packed dense operand, windows of the two views
   size_t total;       // with the history of directional logits (hist_bufs of them), which comes last
   size_t total_base;  // without it
@@ -127,6 +127,9 @@ void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg
   L->lpart = off; off += hv_only ? 0 : align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
   L->dotpart = off; off += hv_only ? 0 : align256((size_t)2 * reduce_out_blocks(s.d) * sizeof(double));  // two sums per workgroup
   L->rrpart = off; off += hv_only ? 0 : align256((size_t)cg_update_blocks(s.d) * sizeof(double));
+  // partial sums of the penalty terms and of ||g||^2 that a Newton iteration's gradient leaves for its head (apart from dotpart:
+  // the head may run beside the first reduction of the CG solve, which writes that)
+  L->headpart = off; off += hv_only ? 0 : align256((size_t)2 * reduce_out_blocks(s.d) * sizeof(double));
   // per-slice partial logits of the column-sliced path; the logits [Z | W] of the sparse path
   L->zw = off; off += align256(L->sliced_ok ? sliced_zw_bytes(s) : (L->sparse ? (size_t)s.n * 2 * s.NC * sizeof(float) : 0));
   L->pack = off;
@@ -370,7 +373,7 @@ int reduce(const nadmm_problem* prob, const Layout& L, void* ws, int nparts, int
 int hv_apply(const nadmm_problem* prob, const Layout& L, int path, void* ws, const float* X, bool write_pcache,
              const float* v, float* out, double* dot_part, const int32_t* flag, int* nparts_out, hipStream_t st,
              const CgPend* cg = nullptr, const int32_t* red_flag = nullptr, const int32_t* cur = nullptr,
-             const float* v_alt = nullptr, float* w_rows = nullptr) {
+             const float* v_alt = nullptr, float* w_rows = nullptr, const NewtonHeadArgs* head = nullptr) {
   RowArgs ra = blank_rows();
   ra.kind = kRowsHv;
   ra.Z1out = w_rows;  // fused single-pass path only: the directional logits A v, n x (C-1)
@@ -390,6 +393,10 @@ int hv_apply(const nadmm_problem* prob, const Layout& L, int path, void* ws, con
   ReduceArgs r = reduce_args(prob, L, ws, nparts, 0, v, out, dot_part, red_flag != nullptr ? red_flag : flag);
   r.cur = cur;
   r.V_alt = v_alt;
+  if (head != nullptr) {
+    r.has_head = 1;
+    r.head = *head;
+  }
   NADMM_HIP(launch_reduce_out(r, st));
   return NADMM_OK;
 }
@@ -419,15 +426,19 @@ CgPend cg_pend(const Layout& L, void* ws, DevState* ds, int slot_in, bool final_
 // the update is deferred: iteration k's sweep first applies the update of iteration k - 1 (every workgroup for
 // itself), and the update of the last iteration is applied by whatever consumes the iterate (cg_pend(final_p)).
 // w_rows (deferred form only): where the sweep leaves A d_k, or NULL.
+// head (deferred form, k == 0): the work of newton_head_kernel is done by a workgroup of this iteration's reduction; the sweep
+// and the reduction then go by the Newton iteration's flag as the previous head left it (the first direction is the -g that
+// the gradient's reduction wrote; if this head finds the iteration finished, one sweep was made for nothing).
 int cg_iteration(const nadmm_problem* prob, const Layout& L, int path, void* ws, DevState* ds, const float* X,
-                 bool write_pcache, float tol, int k, hipStream_t st, float* w_rows = nullptr) {
+                 bool write_pcache, float tol, int k, hipStream_t st, float* w_rows = nullptr,
+                 const NewtonHeadArgs* head = nullptr) {
   float* dvec = at<float>(ws, L.dvec);
   float* q = at<float>(ws, L.q);
   if (cg_deferred(path)) {
     double* dot = at<double>(ws, L.dotpart);
     if (k == 0)  // nothing pending: d is the first direction, state slot 0 as the initialisation left it
-      return hv_apply(prob, L, path, ws, X, write_pcache, dvec, q, dot, &ds->cgs[0].active, nullptr, st, nullptr, nullptr,
-                      nullptr, nullptr, w_rows);
+      return hv_apply(prob, L, path, ws, X, write_pcache, dvec, q, dot, head != nullptr ? &ds->newton_active : &ds->cgs[0].active,
+                      nullptr, st, nullptr, nullptr, nullptr, nullptr, w_rows, head);
     const CgPend c = cg_pend(L, ws, ds, (k - 1) & 1, false, tol);
     return hv_apply(prob, L, path, ws, nullptr, false, dvec, q, dot, nullptr, nullptr, st, &c, &ds->cgs[k & 1].active,
                     &ds->cgs[k & 1].cur, at<float>(ws, L.dvec2), w_rows);
@@ -516,7 +527,7 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     {
       // gradient; the same kernel leaves the partial sums of the penalty terms and of ||g||^2 and starts CG (p = 0, r = d = -g)
       ReduceArgs rg = reduce_args(prob, L, d_ws, nparts, 1, d_X, g, nullptr, &ds->newton_active);
-      rg.pen_part = at<double>(d_ws, L.dotpart);
+      rg.pen_part = at<double>(d_ws, L.headpart);
       rg.gg_part = rg.pen_part + reduce_out_blocks(L.s.d);
       rg.cg_p = pdir;
       rg.cg_r = r;
@@ -543,18 +554,22 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     nh.iter = t;
     nh.grad_tol = params->grad_tol;
     nh.newton_mode = 1;
-    nh.pen_part = at<double>(d_ws, L.dotpart);
+    nh.pen_part = at<double>(d_ws, L.headpart);
     nh.gg_part = nh.pen_part + reduce_out_blocks(L.s.d);
     nh.npart = reduce_out_blocks(L.s.d);
     nh.rho_scale = L.rho_scale;
-    NADMM_HIP(launch_newton_head(nh, st));
+    // on the fused path the head is one more workgroup of the first CG iteration's reduction instead of a launch of its own
+    const bool head_in_reduce = cg_deferred(path) && params->max_cg >= 1 && L.s.d <= kReduceFinishMax;
+    if (!head_in_reduce) NADMM_HIP(launch_newton_head(nh, st));
 
     // CG on H p = -g with the probabilities of this iterate
     const bool hist = use_hist && cg_deferred(path) && params->max_cg >= 1 && params->max_cg <= L.hist_bufs;
     const size_t hist_stride = align256((size_t)L.s.n * L.s.NC * sizeof(float)) / sizeof(float);
     for (int k = 0; k < params->max_cg; ++k) {
       float* w_rows = hist ? at<float>(d_ws, L.hist) + (size_t)k * hist_stride : nullptr;
-      if ((rc = cg_iteration(prob, L, path, d_ws, ds, nullptr, false, params->cg_tol, k, st, w_rows)) != NADMM_OK) return rc;
+      if ((rc = cg_iteration(prob, L, path, d_ws, ds, nullptr, false, params->cg_tol, k, st, w_rows,
+                             (k == 0 && head_in_reduce) ? &nh : nullptr)) != NADMM_OK)
+        return rc;
     }
 
     // Armijo backtracking on Z(alpha) = A X + alpha A p, then X += alpha p.  With the deferred CG update the sweep

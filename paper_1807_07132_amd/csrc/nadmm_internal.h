@@ -149,6 +149,28 @@ hipError_t launch_generic_cols(const ColArgs& a, int nslabs, int nchunks, hipStr
 hipError_t launch_logit_rows(const RowArgs& a, const float* zw, int nslices, hipStream_t st);
 
 // ---- vector / tail kernels (nadmm_vec.hip) ----
+struct NewtonHeadArgs {
+  DevState* st;
+  const double* loss_part;
+  int32_t nblocks;
+  float scale, lambda, rho;
+  const float* X;
+  const float* z;
+  const float* y;
+  const float* g;
+  float* pdir;
+  float* r;
+  float* dvec;
+  int64_t d;
+  int32_t iter;        // Newton iteration index
+  float grad_tol;
+  int32_t newton_mode; // 1: part of Algorithm 3 (stats, grad_tol); 0: plain CG initialisation from g
+  const double* pen_part;  // optional (with gg_part): partial sums left by the reduction that formed g, which
+  const double* gg_part;   //   has then also written p = 0, r = d = -g
+  int32_t npart;
+  const float* rho_scale;  // optional device scalar factor on rho
+};
+
 struct ReduceArgs {
   const float* partial;
   int32_t nparts;
@@ -176,6 +198,10 @@ struct ReduceArgs {
   const double* lf_loss_part;
   int32_t lf_nblocks;
   double* lf_loss_out;
+  // kind 0, optional (d <= kReduceFinishMax): that workgroup does the work of newton_head_kernel instead (the first
+  // Hessian-vector product of a CG solve needs nothing of it: its direction is the -g that the gradient's reduction left)
+  int32_t has_head;
+  NewtonHeadArgs head;
 };
 constexpr int64_t kReduceFinishMax = 16384;
 int reduce_out_blocks(int64_t d);
@@ -196,27 +222,6 @@ struct LossFinishArgs {
 };
 hipError_t launch_loss_finish(const LossFinishArgs& a, hipStream_t st);
 
-struct NewtonHeadArgs {
-  DevState* st;
-  const double* loss_part;
-  int32_t nblocks;
-  float scale, lambda, rho;
-  const float* X;
-  const float* z;
-  const float* y;
-  const float* g;
-  float* pdir;
-  float* r;
-  float* dvec;
-  int64_t d;
-  int32_t iter;        // Newton iteration index
-  float grad_tol;
-  int32_t newton_mode; // 1: part of Algorithm 3 (stats, grad_tol); 0: plain CG initialisation from g
-  const double* pen_part;  // optional (with gg_part): partial sums left by the reduction that formed g, which
-  const double* gg_part;   //   has then also written p = 0, r = d = -g
-  int32_t npart;
-  const float* rho_scale;  // optional device scalar factor on rho
-};
 hipError_t launch_newton_head(const NewtonHeadArgs& a, hipStream_t st);
 
 struct CgUpdateArgs {

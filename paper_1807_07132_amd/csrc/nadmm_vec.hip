@@ -96,12 +96,16 @@ __device__ __forceinline__ void reduce_loss_finish_role(const ReduceArgs& a) {
 // out[e] = s * sum_k partial[k][e] + linear terms.  A workgroup covers 32 elements; its 8
 // thread groups each sum every 8th partial (independent loads in flight), then the 8 group sums
 // are added in a fixed order, so the result does not depend on scheduling.
-// FINISH: launched with one workgroup more, which finishes the objective (an instantiation of its own: that
-// workgroup's registers would cost the plain kernel its occupancy on long vectors).
+__device__ __forceinline__ void newton_head_body(const NewtonHeadArgs& a);  // defined below
+
+// FINISH: launched with one workgroup more, which finishes the objective after a gradient pass or does the work of
+// newton_head_kernel beside the first reduction of a CG solve (an instantiation of its own: that workgroup's registers
+// would cost the plain kernel its occupancy on long vectors).
 template <bool FINISH>
 __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
   if (FINISH && blockIdx.x == gridDim.x - 1) {  // the workgroup beyond the last 32 elements
-    if (a.flag == nullptr || *a.flag != 0) reduce_loss_finish_role(a);
+    if (a.has_head != 0) newton_head_body(a.head);  // looks at the state's own activity flag
+    else if (a.flag == nullptr || *a.flag != 0) reduce_loss_finish_role(a);
     return;
   }
   __shared__ float sm[8][32];
@@ -323,7 +327,9 @@ __global__ void state_init_kernel(DevState* st, const int32_t* outer_flag) {
 
 // After a gradient evaluation: finish the objective, ||g||, the stopping test of
 // Algorithm 3, and start CG from p = 0, r = d = -g.
-__global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs a) {
+// (a device function: it runs as a kernel of its own or as one workgroup of the reduction that follows the first
+// Hessian-vector sweep of a CG solve, ReduceArgs.has_head; any workgroup size that is a multiple of 64)
+__device__ __forceinline__ void newton_head_body(const NewtonHeadArgs& a) {
   const float rho_ = a.rho_scale != nullptr ? a.rho * *a.rho_scale : a.rho;  // outer solver: common factor on the penalty
   __shared__ double sm[17];
   DevState* st = a.st;
@@ -389,6 +395,8 @@ __global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs
     }
   }
 }
+
+__global__ __launch_bounds__(kTail) void newton_head_kernel(const NewtonHeadArgs a) { newton_head_body(a); }
 
 // One CG iteration's vector work, given q = H d:  a = rr / <d,q>; p += a d; r -= a q;
 // stop on ||r|| <= tol ||g|| (eq. inexact); else d = r + (rr'/rr) d.
@@ -1113,8 +1121,11 @@ hipError_t launch_reduce_out(const ReduceArgs& a, hipStream_t st) {
   const int blocks = reduce_out_blocks(a.d);
   if (a.lf_loss_out != nullptr && (a.kind != 1 || a.d > kReduceFinishMax || a.lf_loss_part == nullptr || a.lf_nblocks < 1))
     return hipErrorInvalidValue;
+  if (a.has_head != 0 && (a.kind != 0 || a.d > kReduceFinishMax || a.lf_loss_out != nullptr || a.head.st == nullptr ||
+                          a.head.gg_part == nullptr || a.head.pen_part == nullptr))
+    return hipErrorInvalidValue;
   if (a.d > kWideFrom) hipLaunchKernelGGL(reduce_out_wide_kernel, dim3(blocks), dim3(256), 0, st, a);
-  else if (a.lf_loss_out != nullptr) hipLaunchKernelGGL(reduce_out_kernel<true>, dim3(blocks + 1), dim3(256), 0, st, a);
+  else if (a.lf_loss_out != nullptr || a.has_head != 0) hipLaunchKernelGGL(reduce_out_kernel<true>, dim3(blocks + 1), dim3(256), 0, st, a);
   else hipLaunchKernelGGL(reduce_out_kernel<false>, dim3(blocks), dim3(256), 0, st, a);
   return hipGetLastError();
 }
