@@ -188,16 +188,6 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
   if (deferred) lds_barrier();  // every wave has picked its operands from LDS: the step slots may be overwritten
 
   u32x4 dhi, dlo;  // D of the current tile as MFMA operand
-  auto phase2_step = [&](int i) {  // out^T[:, step] += D^T (tile held in this step's LDS slot)
-    const char* base = cmw + i * kStepBytes;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int off = cm_offset(16 * h + m, kg);
-      const u32x4 thi = *reinterpret_cast<const u32x4*>(base + off);
-      const u32x4 tlo = *reinterpret_cast<const u32x4*>(base + 2048 + off);
-      acc2[i][h] = mfma3(dhi, dlo, thi, tlo, acc2[i][h]);
-    }
-  };
   for (int64_t row0 = r_begin; row0 < r_end; row0 += kTileRows) {
     // the row this wave handles in the rows stage: e = wave, row = row0 + 4 kg + (e & 3) + 16 (e >> 2)
     const int64_t my_row = row0 + 4 * kg + (wave & 3) + ((wave >> 2) << 4);
@@ -305,10 +295,17 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     float z = 0.f, w = 0.f;
     {
       const float* pr = part + (size_t)(((wave >> 2) * 4 + (wave & 3))) * 64 + lane;
+      float zp[kWaves], wp[kWaves];  // all partials requested before the first is added
 #pragma unroll
       for (int sw = 0; sw < kWaves; ++sw) {
-        if (has0) z += pr[(sw * 16) * 64];
-        if (has1) w += pr[(sw * 16 + 8) * 64];
+        zp[sw] = has0 ? pr[(sw * 16) * 64] : 0.f;
+        wp[sw] = has1 ? pr[(sw * 16 + 8) * 64] : 0.f;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int sw = 0; sw < kWaves; ++sw) {
+        if (has0) z += zp[sw];
+        if (has1) w += wp[sw];
       }
     }
     const size_t my_off = (size_t)my_row * NC + m;
@@ -352,20 +349,51 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     tile_barrier();
 
     // ---------------- phase 2 ----------------
+    // out^T[:, step] += D^T (tile held in the step's LDS slot).  All LDS reads of the stage are requested ahead of their
+    // use: the entries of D together, and the transposed tile of step i + 1 while the products of step i run, the two
+    // column halves of a step taking turns so that no matrix instruction waits for the one before it.
+    u32x4 th[2][2], tl[2][2];
+    auto fetch_step = [&](int i, int b) {
+      const char* base = cmw + i * kStepBytes;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int off = cm_offset(16 * h + m, kg);
+        th[b][h] = *reinterpret_cast<const u32x4*>(base + off);
+        tl[b][h] = *reinterpret_cast<const u32x4*>(base + 2048 + off);
+      }
+    };
     {
-      unsigned h[4], l[4];
+      float d0[4], d1[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {  // k-slot pair (2e, 2e+1) = (row 4kg+e, row 16+4kg+e)
-        const float d0 = dbuf[e * 64 + lane], d1 = dbuf[(4 + e) * 64 + lane];
-        h[e] = pack2(d0, d1);
-        l[e] = pack2(d0 - low_as_float(h[e]), d1 - high_as_float(h[e]));
+        d0[e] = dbuf[e * 64 + lane];
+        d1[e] = dbuf[(4 + e) * 64 + lane];
+      }
+      if (step_exists(0)) fetch_step(0, 0);
+      __builtin_amdgcn_sched_barrier(0);  // keep the requests ahead of the packing below
+      unsigned h[4], l[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        h[e] = pack2(d0[e], d1[e]);
+        l[e] = pack2(d0[e] - low_as_float(h[e]), d1[e] - high_as_float(h[e]));
       }
       dhi = u32x4{h[0], h[1], h[2], h[3]};
       dlo = u32x4{l[0], l[1], l[2], l[3]};
     }
 #pragma unroll
-    for (int i = 0; i < SPW; ++i)
-      if (step_exists(i)) phase2_step(i);
+    for (int i = 0; i < SPW; ++i) {
+      const int b = i & 1;
+      if (i + 1 < SPW && step_exists(i + 1)) fetch_step(i + 1, b ^ 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (step_exists(i)) {  // the three terms of mfma3 for both halves
+        acc2[i][0] = mfma(dlo, th[b][0], acc2[i][0]);
+        acc2[i][1] = mfma(dlo, th[b][1], acc2[i][1]);
+        acc2[i][0] = mfma(dhi, tl[b][0], acc2[i][0]);
+        acc2[i][1] = mfma(dhi, tl[b][1], acc2[i][1]);
+        acc2[i][0] = mfma(dhi, th[b][0], acc2[i][0]);
+        acc2[i][1] = mfma(dhi, th[b][1], acc2[i][1]);
+      }
+    }
   }
 
   // ---- epilogue: per-workgroup partial of A^T rows, and the partial loss ----
