@@ -417,21 +417,45 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
       }
     }
     // LDS operations of one wave execute in order; the slots are private to the wave
+    if (((p * NC) & 3) == 0) {  // every partial starts on a 16-byte boundary
+      // a step's run is at most 32 * 16 floats = 128 pieces of 16 bytes, two per lane: all of them are read back before
+      // the first is stored, so that the stage costs one LDS round trip instead of one per piece
+      f32x4 va[SPW], vb[SPW];
 #pragma unroll
-    for (int i = 0; i < SPW; ++i) {
-      const int s = wave + kWaves * i;
-      if (s < steps) {
-        const float* stage = reinterpret_cast<const float*>(cmw + i * kStepBytes);
+      for (int i = 0; i < SPW; ++i) {
+        const int s = wave + kWaves * i;
         const int cols = p - kStepCols * s < kStepCols ? p - kStepCols * s : kStepCols;
-        const int total = cols * NC;                       // floats of this step's run
-        float* dst = out + (size_t)kStepCols * s * NC;     // 128 (C-1) s bytes into the partial
-        if (((p * NC) & 3) == 0) {                         // every partial starts on a 16-byte boundary
+        const int quads = s < steps ? (cols * NC) >> 2 : 0;
+        const f32x4* stage = reinterpret_cast<const f32x4*>(cmw + i * kStepBytes);
+        const int last = quads > 0 ? quads - 1 : 0;
+        va[i] = stage[lane < last ? lane : last];
+        vb[i] = stage[lane + 64 < last ? lane + 64 : last];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < SPW; ++i) {
+        const int s = wave + kWaves * i;
+        if (s < steps) {
+          const float* stage = reinterpret_cast<const float*>(cmw + i * kStepBytes);
+          const int cols = p - kStepCols * s < kStepCols ? p - kStepCols * s : kStepCols;
+          const int total = cols * NC;                       // floats of this step's run
+          float* dst = out + (size_t)kStepCols * s * NC;     // 128 (C-1) s bytes into the partial
           const int quads = total >> 2;
-          for (int q = lane; q < quads; q += 64)
-            *reinterpret_cast<float4*>(dst + 4 * q) = *reinterpret_cast<const float4*>(stage + 4 * q);
+          if (lane < quads) *reinterpret_cast<f32x4*>(dst + 4 * lane) = va[i];
+          if (lane + 64 < quads) *reinterpret_cast<f32x4*>(dst + 4 * (lane + 64)) = vb[i];
           const int tail = total & 3;
           if (lane < tail) dst[4 * quads + lane] = stage[4 * quads + lane];
-        } else {
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < SPW; ++i) {
+        const int s = wave + kWaves * i;
+        if (s < steps) {
+          const float* stage = reinterpret_cast<const float*>(cmw + i * kStepBytes);
+          const int cols = p - kStepCols * s < kStepCols ? p - kStepCols * s : kStepCols;
+          const int total = cols * NC;
+          float* dst = out + (size_t)kStepCols * s * NC;
           for (int q = lane; q < total; q += 64) dst[q] = stage[q];
         }
       }
