@@ -25,7 +25,7 @@ LG_PER_STEP = 100
 # names the summary it comes from and the digest of the kernel sources it was measured with: if the sources of
 # that kernel path have changed since, the line reports traffic = null instead of a stale figure.
 MEASURED_HV_TRAFFIC = {
-    ("image_like_60000x784_C10", 2): (207.0e6, "profiles/hessvec_fused_image_like_60000x784_C10.md", "946d7fe2491c"),
+    ("image_like_60000x784_C10", 2): (207.0e6, "profiles/hessvec_fused_image_like_60000x784_C10.md", "d2b4392718f9"),
     ("tall_binary_1375000x28_C2", 3): (154.4e6, "profiles/hessvec_thin_tall_binary_1375000x28_C2.md", "ba2935372c83"),
     ("wide_50000x3072_C10", 4): (1286.8e6, "profiles/hessvec_sliced_wide_50000x3072_C10.md", "077d9735aa55"),
     ("large_multiclass_250000x2000_C20", 4): (4435.8e6, "profiles/hessvec_sliced_large_multiclass_250000x2000_C20.md", "077d9735aa55"),
