@@ -315,15 +315,21 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
     }
   };
 
+  // The row range is walked from its last tile to its first: sweep 1 went forward over the same range, so the part of
+  // the matrix it read last is what the memory-side cache still holds (the matrix is larger than that cache), and the
+  // next forward sweep finds the first part there in turn.
+  const int64_t ntiles = r_begin < r_end ? (r_end - r_begin + kTileRows - 1) / kTileRows : 0;
+  const int64_t r_last = r_begin + (ntiles - 1) * kTileRows;  // first row of the last tile
   float4 pf[SPW][2][2];
-  if (r_begin < r_end) {
+  if (ntiles > 0) {
 #pragma unroll
     for (int i = 0; i < SPW; ++i)
-      if (step_exists(i)) load_step_regs<ANY>(a, pf[i], r_begin, r_end, col_of(i), col_max, m);
-    load_d(r_begin);
+      if (step_exists(i)) load_step_regs<ANY>(a, pf[i], r_last, r_end, col_of(i), col_max, m);
+    load_d(r_last);
   }
 
-  for (int64_t row0 = r_begin; row0 < r_end; row0 += kTileRows) {
+  for (int64_t row0 = r_last; row0 >= r_begin; row0 -= kTileRows) {
+    const int64_t row_next = row0 > r_begin ? row0 - kTileRows : r_begin;  // the tile fetched ahead (the first one again at the end)
     // this tile's D operand (rows past the range and padded classes contribute nothing)
     u32x4 dhi[NB], dlo[NB];
 #pragma unroll
@@ -341,7 +347,7 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
       dhi[nb] = u32x4{h[0], h[1], h[2], h[3]};
       dlo[nb] = u32x4{l[0], l[1], l[2], l[3]};
     }
-    load_d(row0 + kTileRows);  // next tile's D (clamped rows)
+    load_d(row_next);  // next tile's D
 
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
@@ -350,7 +356,7 @@ __global__ __launch_bounds__(kThreads) void slice_cols_kernel(const SlicedArgs s
         const int sl = ws.local0 + i;  // step inside the slice
         u32x4 ahi[2], alo[2], unused[2];
         convert_step<false, ANY>(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo, unused);
-        load_step_regs<ANY>(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
+        load_step_regs<ANY>(a, pf[i], row_next, r_end, col, col_max, m);
         char* base = cm + (size_t)sl * kStepBytes;
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
