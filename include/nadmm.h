@@ -179,14 +179,15 @@ int nadmm_hessvec(const nadmm_problem* prob, const float* d_X, const float* d_V,
 /*
  * nadmm_hessvec for callers that cannot allocate device memory or hand over a workspace: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels and
- * same results as nadmm_hessvec, but the scratch memory (rows of D, per-workgroup partial sums, partial
- * logits of the column-sliced path, the sparse path's packed operand and windows) is a buffer built into
+ * same results as nadmm_hessvec, but the scratch memory (rows of D, per-workgroup partial sums, the
+ * sparse path's logits, packed operand and windows) is a buffer built into
  * the library: NADMM_STATIC_SCRATCH_BYTES = 32 MiB of device memory that every GPU the library runs on
  * holds until the process ends.  The call allocates and frees nothing and does not synchronise.
  *   - A problem that needs more (nadmm_hessvec_static_bytes(prob) > nadmm_static_scratch_bytes(); e.g.
- *     n (C-1) beyond about 2 M with dense A) is rejected with NADMM_ESCRATCH before anything is enqueued.
+ *     500000 x 2000, C = 20 with dense A: 49 MB) is rejected with NADMM_ESCRATCH before anything is enqueued.
  *     The headline shape 60000 x 784, C = 10 needs 18 MB (the size covers every kernel path that
- *     nadmm_set_kernel_path could select for the shape), 50000 x 3072, C = 10 needs 24 MB.
+ *     nadmm_set_kernel_path could select for the shape), 50000 x 3072, C = 10 needs 8.5 MB,
+ *     250000 x 2000, C = 20 needs 30.5 MB.
  *   - Every call on one GPU shares that GPU's buffer, whatever the stream or thread: calls that overlap
  *     in time on one GPU race.  Order them on one stream (or with events).  Nothing in the buffer has to
  *     survive between calls and nothing has to start at zero.

@@ -34,7 +34,7 @@ struct Layout {
   size_t hist;
   int hist_bufs;
   int gen_row_blocks, gen_slabs, gen_chunks, gen_rpc;
-  int fused_parts, thin_parts, sliced_parts;
+  int fused_parts, thin_parts, sliced_parts, sliced_loss;
   bool fused_ok, thin_ok, sliced_ok;
   bool mc_auto;  // the matrix-core paths are also the automatic choice (see kAnyStrideMinP)
   bool sparse;
@@ -113,9 +113,11 @@ void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg
   L->zp = off; off += rows_solver;
   L->sliced_ok = !L->sparse && sliced_supported(s, p->lda, p->d_A);
   L->sliced_parts = 0;
+  L->sliced_loss = 0;
   if (L->sliced_ok) {
     int sps = 0, S2 = 0;
     sliced_grid(s, &S2, &sps, &L->sliced_parts);  // partial sums per row group
+    L->sliced_loss = sliced_loss_blocks(s);       // partial row losses per workgroup of sweep 1
   }
   int parts = L->gen_chunks > L->fused_parts ? L->gen_chunks : L->fused_parts;
   if (L->sliced_parts > parts) parts = L->sliced_parts;
@@ -123,6 +125,7 @@ void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg
   L->partial = off; off += align256((size_t)parts * s.d * sizeof(float));
   int lblocks = L->gen_row_blocks > L->fused_parts ? L->gen_row_blocks : L->fused_parts;
   if (L->thin_parts > lblocks) lblocks = L->thin_parts;
+  if (L->sliced_loss > lblocks) lblocks = L->sliced_loss;
   L->loss_part = off; off += hv_only ? 0 : align256((size_t)lblocks * sizeof(double));
   L->lpart = off; off += hv_only ? 0 : align256((size_t)ls_eval_blocks(s.n) * kCandSlots * sizeof(double));
   L->dotpart = off; off += hv_only ? 0 : align256((size_t)2 * reduce_out_blocks(s.d) * sizeof(double));  // two sums per workgroup
@@ -130,8 +133,8 @@ void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg
   // partial sums of the penalty terms and of ||g||^2 that a Newton iteration's gradient leaves for its head (apart from dotpart:
   // the head may run beside the first reduction of the CG solve, which writes that)
   L->headpart = off; off += hv_only ? 0 : align256((size_t)2 * reduce_out_blocks(s.d) * sizeof(double));
-  // per-slice partial logits of the column-sliced path; the logits [Z | W] of the sparse path
-  L->zw = off; off += align256(L->sliced_ok ? sliced_zw_bytes(s) : (L->sparse ? (size_t)s.n * 2 * s.NC * sizeof(float) : 0));
+  // the logits [Z | W] of the sparse path
+  L->zw = off; off += align256(L->sparse ? (size_t)s.n * 2 * s.NC * sizeof(float) : 0);
   L->pack = off;
   L->win_rows = off;
   L->win_cols = off;
@@ -222,7 +225,7 @@ int choose_path(const Layout& L, int* path) {
 }
 
 int loss_blocks(const Layout& L, int path) {
-  return path == 3 ? L.thin_parts : (path == 2 ? L.fused_parts : L.gen_row_blocks);  // paths 1 and 4: row blocks
+  return path == 3 ? L.thin_parts : (path == 2 ? L.fused_parts : (path == 4 ? L.sliced_loss : L.gen_row_blocks));
 }
 
 SparseView row_view(const nadmm_problem* prob) {
@@ -307,9 +310,7 @@ int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArg
     return NADMM_OK;
   }
   if (path == 4) {
-    int nslices = 0;
-    NADMM_HIP(launch_sliced_logits(ra, at<float>(ws, L.zw), &nslices, st));
-    NADMM_HIP(launch_logit_rows(ra, at<float>(ws, L.zw), nslices, st));
+    NADMM_HIP(launch_sliced_logits(ra, st));
     if (with_cols) {
       NADMM_HIP(launch_sliced_cols(ra, ra.rows_out, at<float>(ws, L.partial), st));
       *nparts = L.sliced_parts;

@@ -10,6 +10,7 @@
 // chunk of samples; chunk partials are summed in a fixed order afterwards.
 #include "nadmm_internal.h"
 #include "nadmm_mfma.h"
+#include "nadmm_rows16.h"
 
 namespace nadmm {
 namespace {
@@ -175,13 +176,10 @@ __global__ __launch_bounds__(kRowsPerBlock) void rows_kernel(const RowArgs a) {
 constexpr int kLogitThreads = 1024;  // 16 waves x 16 rows = the kRowsPerBlock rows of one partial loss
 
 // Lane (g, m) of a wave holds classes m, 16 + m, ... of row 4 it + g: the loads and stores of a wave
-// cover whole rows of the n x (C-1) arrays back to back, and the sums over a row's classes are
-// rotations inside 16 lanes.
+// cover whole rows of the n x (C-1) arrays back to back; the rows are finished by rows16::finish.
 template <int NB>
 __global__ __launch_bounds__(kLogitThreads) void logit_rows_kernel(const RowArgs a, const float* __restrict__ zw,
                                                                    int nslices) {
-  using mfma_detail::row16_max;
-  using mfma_detail::row16_sum;
   if (a.flag != nullptr && *a.flag == 0) return;
   __shared__ double red[kLogitThreads / 64];
   constexpr int kIters = 4;
@@ -195,14 +193,7 @@ __global__ __launch_bounds__(kLogitThreads) void logit_rows_kernel(const RowArgs
   const bool with_loss = a.kind == kRowsGrad || a.kind == kRowsLoss;
   const int nmat = (has0 ? 1 : 0) + (has1 ? 1 : 0);  // matrices held per slice and row: [Z][W], [Z] or [W]
   const int woff = has0 ? NC : 0;
-
-  int cl[NB];
-  bool cv[NB];
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    cv[nb] = 16 * nb + m < NC;
-    cl[nb] = cv[nb] ? 16 * nb + m : NC - 1;
-  }
+  const rows16::LaneClasses<NB> lc(m, NC);
 
   float z[kIters][NB], w[kIters][NB], aux[kIters][NB];
   int label[kIters];
@@ -215,7 +206,7 @@ __global__ __launch_bounds__(kLogitThreads) void logit_rows_kernel(const RowArgs
     for (int nb = 0; nb < NB; ++nb) {
       z[it][nb] = 0.f;
       w[it][nb] = 0.f;
-      aux[it][nb] = (!has0 && a.kind == kRowsHv) ? a.Pin[(size_t)rowc * NC + cl[nb]] : 0.f;
+      aux[it][nb] = (!has0 && a.kind == kRowsHv) ? a.Pin[(size_t)rowc * NC + lc.cl[nb]] : 0.f;
     }
   }
   for (int s = 0; s < nslices; ++s) {  // slices are added in order
@@ -226,74 +217,16 @@ __global__ __launch_bounds__(kLogitThreads) void logit_rows_kernel(const RowArgs
       const float* src = zw + ((size_t)s * a.n + rowc) * nmat * NC;
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        if (has0) z[it][nb] += src[cl[nb]];
-        if (has1) w[it][nb] += src[woff + cl[nb]];
+        if (has0) z[it][nb] += src[lc.cl[nb]];
+        if (has1) w[it][nb] += src[woff + lc.cl[nb]];
       }
     }
   }
 
   double ell = 0.0;
 #pragma unroll
-  for (int it = 0; it < kIters; ++it) {
-    const int64_t row = wrow0 + 4 * it + g;
-    const bool valid = row < a.n;
-    const size_t ro = (size_t)(valid ? row : a.n - 1) * NC;
-    if (a.kind == kRowsLogits) {
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-        if (valid && cv[nb]) {
-          if (has0 && a.Z0out) a.Z0out[ro + cl[nb]] = z[it][nb];
-          if (has1 && a.Z1out) a.Z1out[ro + cl[nb]] = w[it][nb];
-        }
-      continue;
-    }
-    float P[NB];
-    float M = 0.f, alpha = 1.f;
-    if (has0) {
-      float mx = 0.f;  // the reference class has logit 0
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) mx = fmaxf(mx, cv[nb] ? z[it][nb] : 0.f);
-      M = row16_max(mx);
-      float es = 0.f;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        P[nb] = cv[nb] ? expf(z[it][nb] - M) : 0.f;
-        es += P[nb];
-      }
-      alpha = row16_sum(es) + expf(-M);
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) P[nb] = P[nb] / alpha;
-    } else {
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) P[nb] = cv[nb] ? aux[it][nb] : 0.f;
-    }
-    if (a.kind == kRowsHv) {
-      float t = 0.f;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) t = fmaf(P[nb], w[it][nb], t);
-      t = row16_sum(t);
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-        if (valid && cv[nb]) {
-          a.rows_out[ro + cl[nb]] = P[nb] * (w[it][nb] - t);
-          if (a.Pout) a.Pout[ro + cl[nb]] = P[nb];
-        }
-      continue;
-    }
-    float zb = 0.f;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const bool mine = cv[nb] && 16 * nb + m == label[it];
-      zb += mine ? z[it][nb] : 0.f;
-      if (valid && cv[nb]) {
-        if (a.kind == kRowsGrad && a.rows_out) a.rows_out[ro + cl[nb]] = P[nb] - (mine ? 1.f : 0.f);
-        if (a.Pout) a.Pout[ro + cl[nb]] = P[nb];
-        if (a.Z0out) a.Z0out[ro + cl[nb]] = z[it][nb];
-      }
-    }
-    zb = row16_sum(zb);
-    if (valid && m == 0) ell += (double)M + (double)logf(alpha) - (double)zb;
-  }
+  for (int it = 0; it < kIters; ++it)
+    ell += rows16::finish<NB>(a, wrow0 + 4 * it + g, m, lc, has0, has1, z[it], w[it], aux[it], label[it]);
   if (!with_loss) return;
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) ell += __shfl_down(ell, off, 64);

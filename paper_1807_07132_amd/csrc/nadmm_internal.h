@@ -351,9 +351,10 @@ hipError_t launch_thin(const RowArgs& a, float* partial, int nparts, hipStream_t
 // ---- column-sliced two-sweep matrix-core path (nadmm_sliced.hip): any p, C-1 <= 32, lda % 4 == 0 ----
 bool sliced_supported(const Shape& s, int64_t lda, const void* A);
 void sliced_grid(const Shape& s, int* nslices, int* steps_per_slice, int* row_groups);
-size_t sliced_zw_bytes(const Shape& s);
-// writes zw[slice][row][Z|W][C-1] for *nslices column slices (at most the count sliced_zw_bytes() is sized for)
-hipError_t launch_sliced_logits(const RowArgs& a, float* zw, int* nslices, hipStream_t st);
+// sweep 1 and the rows stage in one kernel (the logits never leave the compute unit); partial row losses: one per
+// workgroup, sliced_loss_blocks() of them
+int sliced_loss_blocks(const Shape& s);
+hipError_t launch_sliced_logits(const RowArgs& a, hipStream_t st);
 hipError_t launch_sliced_cols(const RowArgs& a, const float* rows_in, float* partial, hipStream_t st);
 
 // ---- sparse storage of A (nadmm_sparse.hip) ----

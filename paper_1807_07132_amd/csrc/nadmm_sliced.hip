@@ -3,15 +3,16 @@
 // When the p x (C-1) operands and accumulators of a whole row no longer fit one compute unit
 // (p > 960 or C-1 > 16), the columns are cut into slices of at most 24 steps of 32 columns and the
 // Hessian-vector product of Section 2.6 (or the gradient A^T (P - Y)) is taken in two sweeps over A:
-//   sweep 1  every workgroup (slice, row range) forms its slice's share of the logits
-//            Z|W = A[:, slice] [X|V][slice, :] with bf16-split MFMAs and writes it per slice, the
-//            rows of several tiles gathered in LDS and stored as one contiguous run;
-//   rows     a small kernel adds the slices and forms P, D, the row losses (nadmm_generic.hip);
+//   sweep 1  every workgroup owns a range of rows and takes the slices in turn: the slice's share of the
+//            logits Z|W = A[:, slice] [X|V][slice, :] with bf16-split MFMAs is added to the rows' logits,
+//            which stay in LDS (the range is chosen so that they fit); after the last slice the
+//            workgroup finishes its rows: P, D, the row losses (nadmm_rows16.h);
 //   sweep 2  every workgroup forms out^T[:, slice] += D^T A[:, slice] for its row range; the tile is
 //            transposed through a wave-private swizzled LDS copy; no workgroup barrier is needed.
 // Operand layouts, the bf16 high/low split and the three-term product are those of the fused kernel.
 #include "nadmm_internal.h"
 #include "nadmm_mfma.h"
+#include "nadmm_rows16.h"
 
 namespace nadmm {
 namespace {
@@ -24,11 +25,14 @@ constexpr int kTileRows = 32;
 constexpr int kStepCols = 32;
 constexpr int kSliceSteps = 24;   // at most 3 steps per wave
 constexpr int kStepBytes = 4096;
-constexpr int kLogitBatchFloats = 8192;  // sweep 1: output rows gathered in LDS between stores (8 or 4 tiles)
+constexpr size_t kLogitLdsBytes = 159 * 1024;  // sweep 1: K-split partials + the logits of the workgroup's rows
 
 struct SlicedArgs {
   RowArgs r;
-  float* zw;             // sweep 1 out: [slice][n][Z|W][NC], only the matrices whose operand is given
+  int32_t nslices;            // column slices
+  int32_t logit_rows_per_wg;  // sweep 1: rows per workgroup (their logits fit the LDS)
+  int32_t logit_tile_rows;    // sweep 1: rows per tile, <= 32: the range is cut into equal tiles, so that no workgroup ends on
+                              //   a tile of a few rows that costs as much as a full one
   const float* rows_in;  // sweep 2 in:  [n][NC]
   float* partial;        // sweep 2 out: [row group][p*NC]
   int32_t steps_total;   // ceil(p / 32)
@@ -126,143 +130,207 @@ __device__ __forceinline__ void convert_step(const float4 (&pf)[2][2], int col, 
 }
 
 // ------------------------------------------------------------------------------------------------
-// sweep 1: partial logits of one column slice
+// sweep 1 and the rows stage: a workgroup owns a range of rows and keeps their logits in LDS
 // ------------------------------------------------------------------------------------------------
+// LDS: the K-split partials of one tile, [wave][quad (matrix, class block, row block)][component][lane], then the
+// logits of the workgroup's rows, [local row][matrix][class].
+template <int NB, int MATS>
+constexpr size_t logits_part_floats() { return (size_t)kWaves * (MATS * NB * 2) * 4 * 64; }
+
 template <int SPW, int NB, bool HAS0, bool HAS1, bool ANY>
 __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs sa) {
   const RowArgs& a = sa.r;
   if (a.flag != nullptr && *a.flag == 0) return;
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  float* part = reinterpret_cast<float*>(lds);  // [wave][quad (mat, nb, rb)][comp][lane]
-  constexpr int kQuads = 2 * NB * 2;
   constexpr int kMats = (HAS0 ? 1 : 0) + (HAS1 ? 1 : 0);
-  constexpr int kBatch = kLogitBatchFloats / (kTileRows * 2 * 16 * NB);  // tiles per store of the output block
-  float* oblock = part + (size_t)kWaves * kQuads * 4 * 64;  // [row of the batch][matrix][class]
+  constexpr int kQuads = kMats * NB * 2;
+  constexpr int kMatW = HAS0 ? 1 : 0;  // index of W among the matrices held
+  float* part = reinterpret_cast<float*>(lds);
+  float* zres = part + logits_part_floats<NB, kMats>();
+  // kWaves doubles behind the logits (a multiple of 32 rows, so 8-byte aligned) for the sum of the row losses: the kernel
+  // has no static LDS, its whole allowance is dynamic
+  const size_t alloc_rows = ((size_t)sa.logit_rows_per_wg + kTileRows - 1) / kTileRows * kTileRows;
+  double* red = reinterpret_cast<double*>(zres + alloc_rows * kMats * a.NC);
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m = lane & 15, kg = lane >> 4;
   const int NC = a.NC, p = a.p;
-  const int slice = blockIdx.x;
-  const WaveSteps ws = wave_steps(sa, slice, wave);
   const int col_max = ANY ? p - 4 : ((p + 3) & ~3) - 4;  // no load goes past element 4 ceil(p/4) of a row (ANY: past column p - 1)
 
-  const int64_t r_begin = (int64_t)blockIdx.y * sa.rows_per_wg;
-  int64_t r_end = r_begin + sa.rows_per_wg;
+  const int64_t r_begin = (int64_t)blockIdx.x * sa.logit_rows_per_wg;
+  int64_t r_end = r_begin + sa.logit_rows_per_wg;
   if (r_end > a.n) r_end = a.n;
   if (r_begin >= r_end) return;
 
-  auto step_exists = [&](int i) { return i < SPW - 1 || i < ws.count; };
-  auto col_of = [&](int i) { return kStepCols * (ws.step0 + i) + 8 * kg; };
-
+  // Workgroup b takes the slices in the order b, b + 1, ... (mod their number): when the sweep ends, the part of the matrix
+  // that the memory-side cache still holds is spread evenly over the slices, and so over the workgroups of sweep 2.
+  auto slice_at = [&](int k) { return (int)((blockIdx.x + (unsigned)k) % (unsigned)sa.nslices); };
+  // rows of a tile past its end are not fetched: the loads repeat the tile's last row, and what is computed from them is dropped
+  const int th = sa.logit_tile_rows;
+  auto tile_end = [&](int64_t row0) { return row0 + th < r_end ? row0 + th : r_end; };
   float4 pf[SPW][2][2];
+  {  // first tile of the first slice
+    const WaveSteps w0 = wave_steps(sa, slice_at(0), wave);
 #pragma unroll
-  for (int i = 0; i < SPW; ++i)
-    if (step_exists(i)) load_step_regs<ANY>(a, pf[i], r_begin, r_end, col_of(i), col_max, m);
+    for (int i = 0; i < SPW; ++i)
+      if (i < SPW - 1 || i < w0.count)
+        load_step_regs<ANY>(a, pf[i], r_begin, tile_end(r_begin), kStepCols * (w0.step0 + i) + 8 * kg, col_max, m);
+  }
 
-  // operands [X|V] of this wave's steps: hi / lo, per class block; X in three parts (full-accuracy logits)
-  u32x4 bx_hi[SPW][NB], bx_lo[SPW][NB], bx_lo2[SPW][NB], bv_hi[SPW][NB], bv_lo[SPW][NB];
+  // Entries of X and V of one slice's steps as they lie in memory (indices clamped into the arrays; what does not
+  // exist is zeroed when the operands are formed).  Where the registers allow it, those of the next slice are
+  // requested during the last tile of the current one.
+  constexpr bool kOperandsAhead = kMats * NB * SPW * 8 <= 24;
+  float raw_x[HAS0 ? SPW : 1][NB][8], raw_v[HAS1 ? SPW : 1][NB][8];
+  auto fetch_operands = [&](const WaveSteps& w) {
 #pragma unroll
-  for (int i = 0; i < SPW; ++i)
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int cls = 16 * nb + m;
-      const bool cvn = cls < NC;
-      const int clc = cvn ? cls : NC - 1;
-      float x[8], v[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int j = col_of(i) + e;
-        const size_t idx = (size_t)(j < p ? j : p - 1) * NC + clc;
-        const bool ok = cvn && j < p && i < ws.count;
-        const float xv = HAS0 ? a.B0[idx] : 0.f;
-        const float vv = HAS1 ? a.B1[idx] : 0.f;
-        x[e] = ok ? xv : 0.f;
-        v[e] = ok ? vv : 0.f;
-      }
-      split8_3(x, bx_hi[i][nb], bx_lo[i][nb], bx_lo2[i][nb]);
-      split8(v, bv_hi[i][nb], bv_lo[i][nb]);
-    }
-
-  int gathered = 0;  // tiles in the output block
-  int64_t flush_row0 = r_begin;
-  for (int64_t row0 = r_begin; row0 < r_end; row0 += kTileRows) {
-    f32x4 accZ[NB][2], accW[NB][2];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      accZ[nb][0] = accZ[nb][1] = accW[nb][0] = accW[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) {
-      if (step_exists(i)) {
-        const int col = col_of(i);
-        u32x4 ahi[2], alo[2], alo2[2];
-        convert_step<HAS0, ANY>(pf[i], col, col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo, alo2);
-        load_step_regs<ANY>(a, pf[i], row0 + kTileRows, r_end, col, col_max, m);
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-          for (int rb = 0; rb < 2; ++rb) {
-            if (HAS0)
-              accZ[nb][rb] = mfma6(ahi[rb], alo[rb], alo2[rb], bx_hi[i][nb], bx_lo[i][nb], bx_lo2[i][nb], accZ[nb][rb]);
-            if (HAS1) accW[nb][rb] = mfma3(ahi[rb], alo[rb], bv_hi[i][nb], bv_lo[i][nb], accW[nb][rb]);
-          }
-      }
-    }
-    // K-split partials: quad index = (mat * NB + nb) * 2 + rb
-    {
-      float* pw = part + (size_t)(wave * kQuads * 4) * 64 + lane;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            if (HAS0) pw[(((0 * NB + nb) * 2 + rb) * 4 + e) * 64] = accZ[nb][rb][e];
-            if (HAS1) pw[(((1 * NB + nb) * 2 + rb) * 4 + e) * 64] = accW[nb][rb][e];
-          }
-    }
-    __syncthreads();
-    // wave e adds the 8 partials of rows row0 + 4 kg + (e & 3) + 16 (e >> 2) and puts them into the output
-    // block, laid out as in memory: [row][Z|W][C-1] (only the matrices that are computed)
-    {
-      const int rb = wave >> 2, comp = wave & 3;
-      const int r_local = kTileRows * gathered + 4 * kg + comp + 16 * rb;
+    for (int i = 0; i < SPW; ++i)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         const int cls = 16 * nb + m;
-        float z = 0.f, w = 0.f;
+        const int clc = cls < NC ? cls : NC - 1;
 #pragma unroll
-        for (int sw = 0; sw < kWaves; ++sw) {
-          const float* pr = part + (size_t)(sw * kQuads * 4) * 64 + lane;
-          if (HAS0) z += pr[(((0 * NB + nb) * 2 + rb) * 4 + comp) * 64];
-          if (HAS1) w += pr[(((1 * NB + nb) * 2 + rb) * 4 + comp) * 64];
-        }
-        if (cls < NC) {
-          if (HAS0) oblock[(r_local * kMats + 0) * NC + cls] = z;
-          if (HAS1) oblock[(r_local * kMats + (HAS0 ? 1 : 0)) * NC + cls] = w;
+        for (int e = 0; e < 8; ++e) {
+          const int j = kStepCols * (w.step0 + i) + 8 * kg + e;
+          const size_t idx = (size_t)(j < p ? j : p - 1) * NC + clc;
+          if (HAS0) raw_x[i][nb][e] = a.B0[idx];
+          if (HAS1) raw_v[i][nb][e] = a.B1[idx];
         }
       }
-    }
-    __syncthreads();
-    // The rows gathered so far are one contiguous run in memory.  They are written once per kBatch
-    // tiles: every store event holds up the loads of the compute unit for about a microsecond,
-    // however little it writes.
-    ++gathered;
-    if (gathered == kBatch || row0 + kTileRows >= r_end) {
-      const int64_t left = r_end - flush_row0;
-      const int rows = (int)(left < kTileRows * gathered ? left : kTileRows * gathered);
-      const int total = rows * kMats * NC;
-      float* dst = sa.zw + ((size_t)slice * a.n + flush_row0) * kMats * NC;
+  };
+  if (kOperandsAhead) fetch_operands(wave_steps(sa, slice_at(0), wave));
+
+  for (int sk = 0; sk < sa.nslices; ++sk) {
+    const WaveSteps ws = wave_steps(sa, slice_at(sk), wave);
+    // the steps of this wave in the slice after this one (none after the last): their first tile is requested
+    // while the last tile of this slice is being multiplied
+    const bool more = sk + 1 < sa.nslices;
+    const WaveSteps wn = more ? wave_steps(sa, slice_at(sk + 1), wave) : WaveSteps{0, 0, 0};
+    auto step_exists = [&](int i) { return i < SPW - 1 || i < ws.count; };
+    auto col_of = [&](int i) { return kStepCols * (ws.step0 + i) + 8 * kg; };
+
+    // operands [X|V] of this wave's steps: hi / lo, per class block; X in three parts (full-accuracy logits)
+    if (!kOperandsAhead) fetch_operands(ws);
+    u32x4 bx_hi[SPW][NB], bx_lo[SPW][NB], bx_lo2[SPW][NB], bv_hi[SPW][NB], bv_lo[SPW][NB];
 #pragma unroll
-      for (int k = 0; k < (kBatch * kTileRows * kMats * 16 * NB) / kThreads; ++k) {
-        int idx = threadIdx.x + k * kThreads;
-        idx = idx < total ? idx : total - 1;  // indices past the block repeat its last element
-        dst[idx] = oblock[idx];
+    for (int i = 0; i < SPW; ++i)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const bool cvn = 16 * nb + m < NC;
+        float x[8], v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const bool ok = cvn && col_of(i) + e < p && i < ws.count;
+          x[e] = (HAS0 && ok) ? raw_x[i][nb][e] : 0.f;
+          v[e] = (HAS1 && ok) ? raw_v[i][nb][e] : 0.f;
+        }
+        split8_3(x, bx_hi[i][nb], bx_lo[i][nb], bx_lo2[i][nb]);
+        split8(v, bv_hi[i][nb], bv_lo[i][nb]);
       }
-      flush_row0 += kTileRows * gathered;
-      gathered = 0;
+
+    for (int64_t row0 = r_begin; row0 < r_end; row0 += th) {
+      // the tile fetched ahead: the next one of this slice, or the first one of the next slice (one place of issue
+      // for both, so that the addresses are formed where they are used and not kept for the whole slice)
+      const bool last_tile = row0 + th >= r_end;
+      const int64_t next_row0 = last_tile ? r_begin : row0 + th;
+      const int next_step0 = last_tile ? wn.step0 : ws.step0;
+      const int next_count = last_tile ? wn.count : ws.count;
+      const bool next_any = !last_tile || more;
+      f32x4 accZ[NB][2], accW[NB][2];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        accZ[nb][0] = accZ[nb][1] = accW[nb][0] = accW[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+#pragma unroll
+      for (int i = 0; i < SPW; ++i) {
+        const bool here = step_exists(i);
+        u32x4 ahi[2], alo[2], alo2[2];
+        if (here)
+          convert_step<HAS0, ANY>(pf[i], col_of(i), col_max, p, kStepCols * (ws.step0 + i + 1) > p, ahi, alo, alo2);
+        if (next_any && (i < SPW - 1 || i < next_count))
+          load_step_regs<ANY>(a, pf[i], next_row0, tile_end(next_row0), kStepCols * (next_step0 + i) + 8 * kg, col_max, m);
+        if (kOperandsAhead && i == SPW - 1 && last_tile && more) fetch_operands(wn);
+        if (here) {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+              if (HAS0)
+                accZ[nb][rb] = mfma6(ahi[rb], alo[rb], alo2[rb], bx_hi[i][nb], bx_lo[i][nb], bx_lo2[i][nb], accZ[nb][rb]);
+              if (HAS1) accW[nb][rb] = mfma3(ahi[rb], alo[rb], bv_hi[i][nb], bv_lo[i][nb], accW[nb][rb]);
+            }
+        }
+      }
+      // K-split partials: quad index = (mat * NB + nb) * 2 + rb
+      {
+        float* pw = part + (size_t)(wave * kQuads * 4) * 64 + lane;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if (HAS0) pw[(((0 * NB + nb) * 2 + rb) * 4 + e) * 64] = accZ[nb][rb][e];
+              if (HAS1) pw[(((kMatW * NB + nb) * 2 + rb) * 4 + e) * 64] = accW[nb][rb][e];
+            }
+      }
+      __syncthreads();
+      // wave e adds the 8 partials of rows row0 + 4 kg + (e & 3) + 16 (e >> 2) and adds the sum to the rows' logits
+      // (the slices in the order this workgroup takes them)
+      {
+        const int rb = wave >> 2, comp = wave & 3;
+        const int r_tile = 4 * kg + comp + 16 * rb;
+        const int r_local = (int)(row0 - r_begin) + r_tile;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const int cls = 16 * nb + m;
+          float z = 0.f, w = 0.f;
+#pragma unroll
+          for (int sw = 0; sw < kWaves; ++sw) {
+            const float* pr = part + (size_t)(sw * kQuads * 4) * 64 + lane;
+            if (HAS0) z += pr[(((0 * NB + nb) * 2 + rb) * 4 + comp) * 64];
+            if (HAS1) w += pr[(((kMatW * NB + nb) * 2 + rb) * 4 + comp) * 64];
+          }
+          if (cls < NC && r_tile < th) {
+            float* zr = zres + (size_t)(r_local * kMats) * NC + cls;
+            if (HAS0) zr[0] = sk == 0 ? z : zr[0] + z;
+            if (HAS1) zr[kMatW * NC] = sk == 0 ? w : zr[kMatW * NC] + w;
+          }
+        }
+      }
+      __syncthreads();
     }
+  }
+
+  // rows stage: lane (g, m) of wave v finishes row 32 pass + 4 v + g of the range
+  const rows16::LaneClasses<NB> lc(m, NC);
+  const bool with_loss = a.kind == kRowsGrad || a.kind == kRowsLoss;
+  double ell = 0.0;
+  for (int64_t row0 = r_begin; row0 < r_end; row0 += 4 * kWaves) {
+    const int64_t row = row0 + 4 * wave + kg;
+    const int64_t rowc = row < r_end ? row : r_end - 1;
+    const float* zr = zres + (size_t)((int)(rowc - r_begin) * kMats) * NC;
+    float z[NB], w[NB], pin[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      z[nb] = HAS0 ? zr[lc.cl[nb]] : 0.f;
+      w[nb] = HAS1 ? zr[kMatW * NC + lc.cl[nb]] : 0.f;
+      pin[nb] = (!HAS0 && a.kind == kRowsHv) ? a.Pin[(size_t)rowc * NC + lc.cl[nb]] : 0.f;
+    }
+    const int label = with_loss ? a.labels[rowc] : 0;
+    // rows past the range belong to another workgroup (or do not exist): a row index of n marks them invalid
+    ell += rows16::finish<NB>(a, row < r_end ? row : a.n, m, lc, HAS0, HAS1, z, w, pin, label);
+  }
+  if (!with_loss) return;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ell += __shfl_down(ell, off, 64);
+  if (lane == 0) red[wave] = ell;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int wv = 0; wv < kWaves; ++wv) t += red[wv];
+    a.loss_part[blockIdx.x] = t;
   }
 }
 
@@ -408,7 +476,10 @@ bool rows_16_byte_aligned(const RowArgs& a) { return (a.lda & 3) == 0 && (reinte
 
 template <int SPW, int NB, bool HAS0, bool HAS1, bool ANY>
 hipError_t launch_logits_a(const SlicedArgs& sa, dim3 grid, hipStream_t st) {
-  const size_t lds = ((size_t)kWaves * (2 * NB * 2) * 4 * 64 + (size_t)kLogitBatchFloats) * sizeof(float);
+  constexpr int kMats = (HAS0 ? 1 : 0) + (HAS1 ? 1 : 0);
+  const size_t alloc_rows = ((size_t)sa.logit_rows_per_wg + kTileRows - 1) / kTileRows * kTileRows;
+  const size_t lds = (logits_part_floats<NB, kMats>() + alloc_rows * kMats * sa.r.NC) * sizeof(float) + kWaves * sizeof(double);
+  if (lds > kLogitLdsBytes) return hipErrorInvalidValue;
   static uint64_t lds_set = 0;  // per device
   hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&slice_logits_kernel<SPW, NB, HAS0, HAS1, ANY>), &lds_set);
   if (e != hipSuccess) return e;
@@ -470,16 +541,39 @@ void sliced_grid(const Shape& s, int* nslices, int* steps_per_slice, int* row_gr
   *row_groups = (int)rg;
 }
 
-size_t sliced_zw_bytes(const Shape& s) {
-  int S, sps, rg;
-  sliced_grid(s, &S, &sps, &rg);
-  return (size_t)S * s.n * 2 * s.NC * sizeof(float);
+// Sweep 1: the fewest row ranges, in multiples of 256 workgroups, whose logits (mats matrices of C-1 columns) fit the
+// LDS beside the K-split partials of a tile.
+void sliced_logit_plan(const Shape& s, int mats, int* groups, int* rows_per_wg) {
+  const int nb = s.NC > 16 ? 2 : 1;
+  const size_t part = (size_t)kWaves * (mats * nb * 2) * 4 * 64 * sizeof(float);
+  const size_t room = kLogitLdsBytes - part - kWaves * sizeof(double);
+  const int64_t tiles = (s.n + kTileRows - 1) / kTileRows;
+  int64_t rows = kTileRows;
+  for (int64_t k = 1;; ++k) {
+    int64_t g = 256 * k;
+    if (g > tiles) g = tiles;
+    if (g < 1) g = 1;
+    rows = (s.n + g - 1) / g;
+    if (rows < 1) rows = 1;
+    const size_t alloc = (size_t)((rows + kTileRows - 1) / kTileRows * kTileRows);
+    if (alloc * mats * s.NC * sizeof(float) <= room || g == tiles || tiles == 0) break;  // one tile always fits
+  }
+  *rows_per_wg = (int)rows;
+  *groups = (int)((s.n + rows - 1) / rows > 0 ? (s.n + rows - 1) / rows : 1);
+}
+
+int sliced_loss_blocks(const Shape& s) {
+  int g, r;
+  sliced_logit_plan(s, 1, &g, &r);  // the calls with a loss have the operand X alone
+  return g;
 }
 
 static SlicedArgs make_args(const RowArgs& a, int S, int sps, int rg) {
   SlicedArgs sa;
   sa.r = a;
-  sa.zw = nullptr;
+  sa.nslices = S;
+  sa.logit_rows_per_wg = 0;
+  sa.logit_tile_rows = kTileRows;
   sa.rows_in = nullptr;
   sa.partial = nullptr;
   sa.steps_total = (a.p + kStepCols - 1) / kStepCols;
@@ -491,14 +585,20 @@ static SlicedArgs make_args(const RowArgs& a, int S, int sps, int rg) {
   return sa;
 }
 
-hipError_t launch_sliced_logits(const RowArgs& a, float* zw, int* nslices, hipStream_t st) {
+hipError_t launch_sliced_logits(const RowArgs& a, hipStream_t st) {
   Shape s{a.n, a.p, a.NC, (int64_t)a.p * a.NC};
   int S, sps, rg;
   sliced_grid(s, &S, &sps, &rg);
-  *nslices = S;
   SlicedArgs sa = make_args(a, S, sps, rg);
-  sa.zw = zw;
-  const dim3 grid(S, rg);
+  const int mats = (a.B0 != nullptr ? 1 : 0) + (a.B1 != nullptr ? 1 : 0);
+  if (mats == 0) return hipErrorInvalidValue;
+  if ((a.kind == kRowsGrad || a.kind == kRowsLoss) && mats != 1) return hipErrorInvalidValue;  // see sliced_loss_blocks
+  int groups = 0, rows = 0;
+  sliced_logit_plan(s, mats, &groups, &rows);
+  sa.logit_rows_per_wg = rows;
+  const int tiles_per_wg = (rows + kTileRows - 1) / kTileRows;
+  sa.logit_tile_rows = (rows + tiles_per_wg - 1) / tiles_per_wg;
+  const dim3 grid(groups);
   const int spw = (sps + kWaves - 1) / kWaves;
   const int nb = a.NC > 16 ? 2 : 1;
   if (nb == 1) {

@@ -241,7 +241,7 @@ def test_static_scratch_entry_point_validates_on_the_host(lib):
     assert lib.nadmm_hessvec_static_bytes(C.byref(head)) < lib.nadmm_workspace_bytes(C.byref(head), None)
     assert lib.nadmm_hessvec_static(C.byref(head), None, fake, fake, None) == nadmm.NADMM_EINVAL
     assert lib.nadmm_hessvec_static(C.byref(head), fake, fake, None, None) == nadmm.NADMM_EINVAL
-    big = fake_problem(n=250000, p=2000, Cc=20)                                     # 146 MB of scratch
+    big = fake_problem(n=500000, p=2000, Cc=20)                                     # 49 MB of scratch
     assert lib.nadmm_hessvec_static_bytes(C.byref(big)) > cap
     assert lib.nadmm_hessvec_static(C.byref(big), fake, fake, fake, None) == nadmm.NADMM_ESCRATCH
     assert b"built-in" in lib.nadmm_status_string(nadmm.NADMM_ESCRATCH)
