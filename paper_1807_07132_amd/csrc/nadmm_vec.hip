@@ -784,10 +784,16 @@ __global__ __launch_bounds__(256) void ls_eval_rows_kernel(const LsEvalArgs a) {
               if (c == b) zb = zz[c];
             }
           }
-          float alpha = expf(-M);
+          float alpha;
+          if constexpr (NCP == 1) {
+            // two classes: one of exp(-M) and exp(z - M) is exp(0), the other exp(-|z|): the same sum with one exponential
+            alpha = 1.f + expf(-fabsf(zz[0]));
+          } else {
+            alpha = expf(-M);
 #pragma unroll
-          for (int c = 0; c < NCP; ++c)
-            if (c < NC) alpha += expf(zz[c] - M);
+            for (int c = 0; c < NCP; ++c)
+              if (c < NC) alpha += expf(zz[c] - M);
+          }
           acc[kk] += (double)M + (double)logf(alpha) - (double)zb;
         }
       }
