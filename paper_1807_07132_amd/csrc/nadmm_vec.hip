@@ -560,54 +560,62 @@ __global__ __launch_bounds__(kCgThreads) void cg_direction_kernel(const CgUpdate
 // Thread t sums the partials k = g, g + G, ... of element e = t mod d (g = t / d, G = 1024 / d groups),
 // the G group sums are added in order.
 __global__ __launch_bounds__(kTail) void cg_reduce_update_kernel(const ReduceArgs ra, const CgUpdateArgs a) {
-  const float rho_ = ra.rho_scale != nullptr ? ra.rho * *ra.rho_scale : ra.rho;  // outer solver: common factor on the penalty
   __shared__ double sm[17];
   __shared__ float gsum[kTail];
   DevState* st = a.st;
-  if (st->cg_active == 0) return;
   const int d = (int)a.d;
   const int groups = kTail / d;
   const int t = threadIdx.x;
   const int e = t % d, g = t / d;
-  float sum = 0.f;
-  if (g < groups) {
-    const float* __restrict__ pp = ra.partial + e;
-    int k = g;
-    for (; k + 7 * groups < ra.nparts; k += 8 * groups) {
-      float v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = pp[(size_t)(k + u * groups) * d];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) sum += v[u];
-    }
-    for (; k < ra.nparts; k += groups) sum += pp[(size_t)k * d];
-  }
-  gsum[t] = sum;
-  __syncthreads();
+  // Everything the update reads is requested before the first value is needed (indices clamped, no load under a
+  // condition): the scalars of the state, this thread's elements of the vectors, then the partials in runs of 16.
+  const int active = st->cg_active;
+  const double rr = st->rr;
+  const double gg = st->gg_cg;
+  const float rho_ = ra.rho_scale != nullptr ? ra.rho * *ra.rho_scale : ra.rho;  // outer solver: common factor on the penalty
   const bool mine = t < d;
+  const int tc = mine ? t : d - 1;
+  const float dv_in = a.dvec[tc], r_in = a.r[tc], p_in = a.pdir[tc];
+  float sum = 0.f;
+  {
+    constexpr int U = 16;
+    const float* __restrict__ pp = ra.partial + e;
+    const int gc = g < groups ? g : groups - 1;
+    for (int k = gc; k < ra.nparts; k += U * groups) {
+      float v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int idx = k + u * groups;
+        v[u] = pp[(size_t)(idx < ra.nparts ? idx : ra.nparts - 1) * d];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) sum += (k + u * groups < ra.nparts) ? v[u] : 0.f;  // in the order of the partials
+    }
+  }
+  if (active == 0) return;  // uniform
+  gsum[t] = g < groups ? sum : 0.f;
+  __syncthreads();
   float dv = 0.f, qv = 0.f;
   if (mine) {
     float s2 = 0.f;
     for (int g2 = 0; g2 < groups; ++g2) s2 += gsum[g2 * d + t];
-    dv = a.dvec[t];
+    dv = dv_in;
     qv = fmaf(ra.lambda + rho_, dv, ra.scale * s2);
   }
   const double dq = block_sum((double)dv * (double)qv, sm);
-  const double rr = st->rr;
-  const double gg = st->gg_cg;
   if (!(dq > 0.0) || !isfinite(dq)) {  // no positive curvature: keep the current iterate
     __syncthreads();
     if (t == 0) st->cg_active = 0;
     return;
   }
   const float al = (float)(rr / dq);
-  const float rn = mine ? fmaf(-al, qv, a.r[t]) : 0.f;
+  const float rn = mine ? fmaf(-al, qv, r_in) : 0.f;
   const double rr_new = block_sum((double)rn * (double)rn, sm);
   const bool stop = sqrt(rr_new) <= (double)a.tol * sqrt(gg);
   const float be = (float)(rr_new / rr);
   if (mine) {
     a.r[t] = rn;
-    a.pdir[t] = fmaf(al, dv, a.pdir[t]);
+    a.pdir[t] = fmaf(al, dv, p_in);
     if (!stop) a.dvec[t] = fmaf(be, dv, rn);
   }
   if (t == 0) {
