@@ -82,6 +82,16 @@ __device__ __forceinline__ float row16_sum(float v) {
   v += row_ror<1>(v);
   return v;
 }
+// Sum over the 64 lanes of a wave, the same value in every lane: rotations inside the four rows of 16 lanes, then the
+// four row totals in a fixed order.  Vector instructions only; a tree of cross-lane shuffles goes through the LDS pipe
+// with its latency at every stage.
+__device__ __forceinline__ float wave64_sum(float v) {
+  v = row16_sum(v);
+  const int b = __float_as_int(v);
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(b, 0)), r1 = __int_as_float(__builtin_amdgcn_readlane(b, 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(b, 48));
+  return (r0 + r1) + (r2 + r3);
+}
 __device__ __forceinline__ float row16_max(float v) {
   v = fmaxf(v, row_ror<8>(v));
   v = fmaxf(v, row_ror<4>(v));

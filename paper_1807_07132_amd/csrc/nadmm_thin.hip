@@ -11,6 +11,7 @@
 // already in flight in registers while the current one is consumed.  Per-lane
 // accumulators are summed over the workgroup once, at the end, in a fixed order.
 #include "nadmm_internal.h"
+#include "nadmm_mfma.h"
 
 namespace nadmm {
 namespace {
@@ -193,19 +194,18 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
     if (row0 + kThinThreads < r_end) process(1, row0 + kThinThreads);
   }
 
-  // ---- workgroup sums: wave shuffles, then the 4 wave results in order ----
+  // ---- workgroup sums: every accumulator over each row of 16 lanes by rotations (no shuffles: 28 trees of six
+  // shuffles each took 5 us here, where nothing overlaps them), then the 16 row sums in a fixed order ----
   __syncthreads();
-  float* wsum = tile;  // [wave][PP*NC]
+  float* wsum = tile;  // [wave][row of 16 lanes][PP*NC]: 16 sums per accumulator (at most 4 KB, the smallest tile)
   const int lane = t & 63, wave = t >> 6;
   if (with_cols) {
 #pragma unroll
     for (int j = 0; j < PP; ++j)
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
-        float v = acc[j][c];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-        if (lane == 0) wsum[wave * (PP * NC) + j * NC + c] = v;
+        const float v = mfma_detail::row16_sum(acc[j][c]);
+        if ((lane & 15) == 0) wsum[(wave * 4 + (lane >> 4)) * (PP * NC) + j * NC + c] = v;
       }
   }
   if (a.loss_part != nullptr) {
@@ -215,8 +215,12 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
   }
   __syncthreads();
   if (with_cols && t < p * NC) {
-    const float v = ((wsum[t] + wsum[PP * NC + t]) + wsum[2 * PP * NC + t]) + wsum[3 * PP * NC + t];
-    ta.partial[(size_t)blockIdx.x * (p * NC) + t] = v;
+    float w4[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      w4[w] = (wsum[(4 * w) * (PP * NC) + t] + wsum[(4 * w + 1) * (PP * NC) + t]) +
+              (wsum[(4 * w + 2) * (PP * NC) + t] + wsum[(4 * w + 3) * (PP * NC) + t]);
+    ta.partial[(size_t)blockIdx.x * (p * NC) + t] = ((w4[0] + w4[1]) + w4[2]) + w4[3];
   }
   if (a.loss_part != nullptr && t == 0) a.loss_part[blockIdx.x] = ((red[0] + red[1]) + red[2]) + red[3];
 }
