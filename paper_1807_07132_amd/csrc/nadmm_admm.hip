@@ -3,6 +3,7 @@
 // O(N d) streaming work; the sums are taken per workgroup and finished in a fixed order by one
 // workgroup, so the result does not depend on scheduling.
 #include "nadmm_internal.h"
+#include "nadmm_mfma.h"
 
 namespace nadmm {
 namespace {
@@ -10,11 +11,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kSums = 5;  // sum_i ||z - x_i||^2, sum_i rho_i^2 ||z - z_prev||^2, sum_i ||x_i||^2, ||z||^2, sum_i ||u_i||^2
 
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-  return v;
-}
+__device__ __forceinline__ double wave_sum(double v) { return mfma_detail::wave64_sum(v); }  // in every lane, fixed order
 
 __global__ __launch_bounds__(kThreads) void admm_init_kernel(AdmmState* st, float* u, float* z, int32_t N, int64_t d) {
   const int64_t stride = (int64_t)gridDim.x * kThreads;

@@ -4,6 +4,7 @@
 #pragma once
 
 #include "nadmm_internal.h"
+#include "nadmm_mfma.h"
 
 namespace nadmm {
 
@@ -17,8 +18,7 @@ __device__ __forceinline__ void lds_barrier() {
 
 template <int THREADS>
 __device__ __forceinline__ double cg_block_sum(double v, double* sm /* THREADS / 64 + 1 doubles */) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  v = mfma_detail::wave64_sum(v);  // rotations inside rows of 16 lanes, the four row totals in a fixed order
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   lds_barrier();  // previous users of sm are done
   if (lane == 0) sm[wave] = v;

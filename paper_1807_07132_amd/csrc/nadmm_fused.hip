@@ -462,8 +462,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs fa) {
     }
   }
   if (KIND == kRowsGrad || KIND == kRowsLoss) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) loss_acc += __shfl_down(loss_acc, off, 64);
+    loss_acc = mfma_detail::wave64_sum(loss_acc);
     double* red = reinterpret_cast<double*>(dbuf);
     __syncthreads();
     if (lane == 0) red[wave] = loss_acc;

@@ -19,8 +19,7 @@ constexpr int kRowsPerBlock = 256;  // 4 waves x 64 rows
 constexpr int kTileCols = 32;
 
 __device__ __forceinline__ double block_sum_double(double v, double* sm /* >= 4 doubles */) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  v = mfma_detail::wave64_sum(v);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   __syncthreads();
   if (lane == 0) sm[wave] = v;
@@ -228,8 +227,7 @@ __global__ __launch_bounds__(kLogitThreads) void logit_rows_kernel(const RowArgs
   for (int it = 0; it < kIters; ++it)
     ell += rows16::finish<NB>(a, wrow0 + 4 * it + g, m, lc, has0, has1, z[it], w[it], aux[it], label[it]);
   if (!with_loss) return;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) ell += __shfl_down(ell, off, 64);
+  ell = mfma_detail::wave64_sum(ell);
   if (lane == 0) red[wave] = ell;
   __syncthreads();
   if (threadIdx.x == 0) {

@@ -92,6 +92,37 @@ __device__ __forceinline__ float wave64_sum(float v) {
   const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(b, 48));
   return (r0 + r1) + (r2 + r3);
 }
+// The same for float64 (two 32-bit rotations per step).
+template <int N>
+__device__ __forceinline__ double row_ror(double v) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), 0x120 + N, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), 0x120 + N, 0xf, 0xf, false);
+  return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned)lo);
+}
+__device__ __forceinline__ double row16_sum(double v) {
+  v += row_ror<8>(v);
+  v += row_ror<4>(v);
+  v += row_ror<2>(v);
+  v += row_ror<1>(v);
+  return v;
+}
+__device__ __forceinline__ double lane_value(double v, int lane) {  // lane: a constant
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_readlane((int)(b & 0xffffffffll), lane);
+  const int hi = __builtin_amdgcn_readlane((int)(b >> 32), lane);
+  return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned)lo);
+}
+__device__ __forceinline__ double wave64_sum(double v) {
+  v = row16_sum(v);
+  return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
+}
+// sums over lanes 0..31 and over lanes 32..63, each returned in its own lanes
+__device__ __forceinline__ double half32_sum(double v) {
+  v = row16_sum(v);
+  const double lo = lane_value(v, 0) + lane_value(v, 16), hi = lane_value(v, 32) + lane_value(v, 48);
+  return (threadIdx.x & 32) ? hi : lo;
+}
 __device__ __forceinline__ float row16_max(float v) {
   v = fmaxf(v, row_ror<8>(v));
   v = fmaxf(v, row_ror<4>(v));

@@ -323,8 +323,7 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
     ell += rows16::finish<NB>(a, row < r_end ? row : a.n, m, lc, HAS0, HAS1, z, w, pin, label);
   }
   if (!with_loss) return;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) ell += __shfl_down(ell, off, 64);
+  ell = mfma_detail::wave64_sum(ell);
   if (lane == 0) red[wave] = ell;
   __syncthreads();
   if (threadIdx.x == 0) {

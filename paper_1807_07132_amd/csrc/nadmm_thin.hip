@@ -209,8 +209,7 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
       }
   }
   if (a.loss_part != nullptr) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) loss_acc += __shfl_down(loss_acc, off, 64);
+    loss_acc = mfma_detail::wave64_sum(loss_acc);
     if (lane == 0) red[wave] = loss_acc;
   }
   __syncthreads();

@@ -13,11 +13,9 @@ namespace {
 
 constexpr int kTail = 1024;
 
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-  return v;
-}
+// Sum over the wave in every lane: rotations inside rows of 16 lanes and the four row totals in a fixed order (a tree of
+// cross-lane shuffles of a double is twelve trips through the LDS pipe, one after the other).
+__device__ __forceinline__ double wave_sum(double v) { return mfma_detail::wave64_sum(v); }
 
 // Sum over the whole workgroup (fixed order); result valid in every thread.
 __device__ __forceinline__ double block_sum(double v, double* sm /* >= 17 doubles */) {
@@ -176,13 +174,11 @@ __global__ __launch_bounds__(256) void reduce_out_kernel(const ReduceArgs a) {
   // the 32 values of this workgroup, summed in a fixed order by lane 0
   double* first = a.kind == 0 ? a.dot_part : a.gg_part;
   if (first != nullptr) {
-#pragma unroll
-    for (int off = 16; off > 0; off >>= 1) prod += __shfl_down(prod, off, 64);
+    prod = mfma_detail::half32_sum(prod);
     if (el == 0) first[blockIdx.x] = prod;
   }
   if (a.kind != 0 && a.pen_part != nullptr) {
-#pragma unroll
-    for (int off = 16; off > 0; off >>= 1) pen += __shfl_down(pen, off, 64);
+    pen = mfma_detail::half32_sum(pen);
     if (el == 0) a.pen_part[blockIdx.x] = pen;
   }
 }
@@ -750,11 +746,11 @@ __global__ __launch_bounds__(256) void ls_eval_kernel(const LsEvalArgs a) {
 template <int NCP>
 __global__ __launch_bounds__(256) void ls_eval_rows_kernel(const LsEvalArgs a) {
   if (a.flag != nullptr && *a.flag == 0) return;
-  __shared__ double sm[17];
+  constexpr int G = 16;  // candidates per pass over the cached logits (the usual 12 take one pass)
+  __shared__ double smk[G][4];
   __shared__ float cgal[kCgHist];
   const int NC = a.NC;
   const int64_t stride = (int64_t)gridDim.x * 256;
-  constexpr int G = 16;  // candidates per pass over the cached logits (the usual 12 take one pass)
   const bool from_hist = a.Zp == nullptr;
   int nused = 0;
   if (from_hist) {
@@ -806,13 +802,19 @@ __global__ __launch_bounds__(256) void ls_eval_rows_kernel(const LsEvalArgs a) {
         }
       }
     }
+    // the candidates' sums over the workgroup share one pair of barriers: per wave first, then the four waves in order
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
     for (int kk = 0; kk < G; ++kk) {
-      if (k0 + kk < a.ncand) {  // uniform
-        const double t = block_sum(acc[kk], sm);
-        if (threadIdx.x == 0) a.lpart[(size_t)(k0 + kk) * gridDim.x + blockIdx.x] = t;
-      }
+      const double t = wave_sum(acc[kk]);
+      if (lane == 0) smk[kk][wave] = t;
     }
+    __syncthreads();
+    if (threadIdx.x < G && k0 + (int)threadIdx.x < a.ncand) {
+      const int kk = threadIdx.x;
+      a.lpart[(size_t)(k0 + kk) * gridDim.x + blockIdx.x] = ((smk[kk][0] + smk[kk][1]) + smk[kk][2]) + smk[kk][3];
+    }
+    __syncthreads();  // the next pass writes smk again
   }
 }
 
