@@ -303,24 +303,40 @@ __global__ __launch_bounds__(kThreads) void slice_logits_kernel(const SlicedArgs
     }
   }
 
-  // rows stage: lane (g, m) of wave v finishes row 32 pass + 4 v + g of the range
+  // rows stage: lane (g, m) of wave v finishes row 32 pass + 4 v + g of the range.  Nothing overlaps this stage, so the
+  // memory round trips in it are kept few: the cached probabilities and labels of several passes are requested together.
   const rows16::LaneClasses<NB> lc(m, NC);
   const bool with_loss = a.kind == kRowsGrad || a.kind == kRowsLoss;
+  const bool use_pin = !HAS0 && a.kind == kRowsHv;
+  constexpr int RG = NB == 1 ? 8 : 4;  // passes per group
   double ell = 0.0;
-  for (int64_t row0 = r_begin; row0 < r_end; row0 += 4 * kWaves) {
-    const int64_t row = row0 + 4 * wave + kg;
-    const int64_t rowc = row < r_end ? row : r_end - 1;
-    const float* zr = zres + (size_t)((int)(rowc - r_begin) * kMats) * NC;
-    float z[NB], w[NB], pin[NB];
+  for (int64_t g0 = r_begin; g0 < r_end; g0 += 4 * kWaves * RG) {
+    float pin[RG][NB];
+    int label[RG];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      z[nb] = HAS0 ? zr[lc.cl[nb]] : 0.f;
-      w[nb] = HAS1 ? zr[kMatW * NC + lc.cl[nb]] : 0.f;
-      pin[nb] = (!HAS0 && a.kind == kRowsHv) ? a.Pin[(size_t)rowc * NC + lc.cl[nb]] : 0.f;
+    for (int u = 0; u < RG; ++u) {
+      const int64_t row = g0 + 4 * kWaves * u + 4 * wave + kg;
+      const int64_t rowc = row < r_end ? row : r_end - 1;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) pin[u][nb] = use_pin ? a.Pin[(size_t)rowc * NC + lc.cl[nb]] : 0.f;
+      label[u] = with_loss ? a.labels[rowc] : 0;
     }
-    const int label = with_loss ? a.labels[rowc] : 0;
-    // rows past the range belong to another workgroup (or do not exist): a row index of n marks them invalid
-    ell += rows16::finish<NB>(a, row < r_end ? row : a.n, m, lc, HAS0, HAS1, z, w, pin, label);
+#pragma unroll
+    for (int u = 0; u < RG; ++u) {
+      if (g0 + 4 * kWaves * u < r_end) {  // uniform
+        const int64_t row = g0 + 4 * kWaves * u + 4 * wave + kg;
+        const int64_t rowc = row < r_end ? row : r_end - 1;
+        const float* zr = zres + (size_t)((int)(rowc - r_begin) * kMats) * NC;
+        float z[NB], w[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          z[nb] = HAS0 ? zr[lc.cl[nb]] : 0.f;
+          w[nb] = HAS1 ? zr[kMatW * NC + lc.cl[nb]] : 0.f;
+        }
+        // rows past the range belong to another workgroup (or do not exist): a row index of n marks them invalid
+        ell += rows16::finish<NB>(a, row < r_end ? row : a.n, m, lc, HAS0, HAS1, z, w, pin[u], label[u]);
+      }
+    }
   }
   if (!with_loss) return;
   ell = mfma_detail::wave64_sum(ell);
