@@ -67,6 +67,10 @@ CASES = {
     # several tiles per workgroup and column slice in sweep 1 (row ranges of 79 and 36 rows cut into equal tiles of 27 and 18)
     "sliced_20000x1100_C4": lambda: workloads.generic(20000, 1100, 4, seed=43, x_std=0.05),
     "sliced_9000x200_C20": lambda: workloads.generic(9000, 200, 20, seed=44, x_std=0.1),
+    # the same with rows that are only 4-byte aligned, and a shape whose logits Z and W of 1/256 of the rows do not fit the LDS
+    # together (32 free classes, 100000 rows: sweep 1 then runs on 512 row ranges)
+    "sliced_any_9000x1101_C4": lambda: workloads.generic(9000, 1101, 4, seed=45, x_std=0.05),
+    "sliced_100000x36_C33": lambda: workloads.generic(100000, 36, 33, seed=46, x_std=0.2),
     # d = p (C-1) = 280000: the long-vector forms of the reduction, the CG update and the line-search tail
     "long_vectors_40x70000_C5": lambda: workloads.generic(40, 70000, 5, seed=29, x_std=0.01, mean=True),
 }
@@ -203,7 +207,8 @@ def test_line_search(cache, name, path):
 NEWTON_CASES = ["tiny", "image_like_3k", "wide_700", "tall_binary_50k", "large_multiclass_900", "ragged_1237x45_C5",
                 "fused_any_3000x785_C10", "sliced_any_700x1101_C4",
                 "single_row_1x7_C4", "fused_9001x260_C10", "fused_4100x36_C17", "thin_70001x32_C3", "thin_300x12_C4", "sliced_3000x100_C26",
-                "sliced_1500x1100_C4", "sliced_20000x1100_C4", "sliced_9000x200_C20", "long_vectors_40x70000_C5"]
+                "sliced_1500x1100_C4", "sliced_20000x1100_C4", "sliced_9000x200_C20", "sliced_any_9000x1101_C4", "sliced_100000x36_C33",
+                "long_vectors_40x70000_C5"]
 
 
 @pytest.mark.parametrize("path", PATHS)
