@@ -32,7 +32,7 @@ MEASURED_HV_TRAFFIC = {
     # sparse storage: bytes between the L2 caches and the memory side, most of them operand rows served by the Infinity Cache
     ("e18_like_40628x279998_C20_sparse", 5): (12480.0e6, "profiles/hessvec_sparse_e18_like_40628x279998_C20.md", "8090591d36f9"),
 }
-PATH_SOURCES = {1: ["nadmm_generic.hip", "nadmm_rows16.h"], 2: ["nadmm_fused.hip", "nadmm_cgstep.h"], 3: ["nadmm_thin.hip"],
+PATH_SOURCES = {1: ["nadmm_generic.hip", "nadmm_rows16.h"], 2: ["nadmm_fused.hip", "nadmm_cgstep.h"], 3: ["nadmm_thin.hip", "nadmm_cgstep.h"],
                 4: ["nadmm_sliced.hip", "nadmm_rows16.h"], 5: ["nadmm_sparse.hip", "nadmm_generic.hip", "nadmm_rows16.h"]}
 DTYPE = "f32 data and results; products on bf16 MFMA with split operands (3 terms, 6 for the logits A X), f32 accumulate; f64 scalar sums"
 

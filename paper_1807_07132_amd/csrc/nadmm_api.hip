@@ -27,7 +27,7 @@ struct Layout {
   size_t state, g, pdir, r, dvec, q;
   size_t pdir2, r2, dvec2, pfinal;  // second vector set and final iterate of the deferred CG update (fused path)
   size_t drows, pcache, zx, zp;
-  size_t partial, loss_part, lpart, dotpart, rrpart, headpart, zw;
+  size_t partial, partial2, loss_part, lpart, dotpart, rrpart, headpart, zw;
   size_t pack, win_rows, win_cols;  // sparse storage: packed dense operand, windows of the two views
   size_t total;       // with the history of directional logits (hist_bufs of them), which comes last
   size_t total_base;  // without it
@@ -103,10 +103,11 @@ void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg
   L->r = off; off += vec;
   L->dvec = off; off += vec;
   L->q = off; off += vec;
-  L->pdir2 = off; off += L->fused_ok ? vec : 0;
-  L->r2 = off; off += L->fused_ok ? vec : 0;
-  L->dvec2 = off; off += L->fused_ok ? vec : 0;
-  L->pfinal = off; off += L->fused_ok ? vec : 0;
+  const bool two_sets = L->fused_ok || L->thin_ok;  // the paths with a deferred CG update
+  L->pdir2 = off; off += two_sets ? vec : 0;
+  L->r2 = off; off += two_sets ? vec : 0;
+  L->dvec2 = off; off += two_sets ? vec : 0;
+  L->pfinal = off; off += two_sets ? vec : 0;
   L->drows = off; off += rows;
   L->pcache = off; off += rows_solver;
   L->zx = off; off += rows_solver;
@@ -123,6 +124,8 @@ void make_layout(const nadmm_problem* p, Layout* L, bool hv_only = false, int wg
   if (L->sliced_parts > parts) parts = L->sliced_parts;
   if (L->thin_parts > parts) parts = L->thin_parts;
   L->partial = off; off += align256((size_t)parts * s.d * sizeof(float));
+  // thin-data path: the sweeps of a CG solve write their partial sums to two buffers in turn (each reads the previous one's)
+  L->partial2 = off; off += (L->thin_ok && !hv_only) ? align256((size_t)L->thin_parts * s.d * sizeof(float)) : 0;
   int lblocks = L->gen_row_blocks > L->fused_parts ? L->gen_row_blocks : L->fused_parts;
   if (L->thin_parts > lblocks) lblocks = L->thin_parts;
   if (L->sliced_loss > lblocks) lblocks = L->sliced_loss;
@@ -246,9 +249,13 @@ int sparse_plan(const nadmm_problem* prob, const Layout& L, void* ws, hipStream_
 }
 
 // One sweep over A: rows pass, and (if with_cols) partial sums of A^T rows_out.
+// cg: the sweep applies a pending CG update first (fused and thin-data kernels); on the thin-data path prev names the
+// previous sweep's partial sums, which that kernel adds up itself, and partial_out where this sweep's go.
 int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArgs ra, bool with_cols,
-          int* nparts, hipStream_t st, const CgPend* cg = nullptr) {
-  if (cg != nullptr && path != 2) return NADMM_EINVAL;  // the deferred CG update lives in the fused kernel only
+          int* nparts, hipStream_t st, const CgPend* cg = nullptr, const ReduceArgs* prev = nullptr,
+          float* partial_out = nullptr) {
+  if (cg != nullptr && path != 2 && path != 3) return NADMM_EINVAL;
+  if ((prev != nullptr || partial_out != nullptr) && path != 3) return NADMM_EINVAL;
   ra.A = prob->d_A;
   ra.n = prob->n;
   ra.p = prob->p;
@@ -305,7 +312,8 @@ int sweep(const nadmm_problem* prob, const Layout& L, int path, void* ws, RowArg
     return NADMM_OK;
   }
   if (path == 3) {
-    NADMM_HIP(launch_thin(ra, with_cols ? at<float>(ws, L.partial) : nullptr, L.thin_parts, st));
+    float* pout = partial_out != nullptr ? partial_out : at<float>(ws, L.partial);
+    NADMM_HIP(launch_thin(ra, with_cols ? pout : nullptr, L.thin_parts, st, cg, prev));
     *nparts = L.thin_parts;
     return NADMM_OK;
   }
@@ -423,6 +431,16 @@ CgPend cg_pend(const Layout& L, void* ws, DevState* ds, int slot_in, bool final_
   return c;
 }
 
+// Thin-data path inside a Newton iteration: the CG update is deferred as on the fused path, and the reduction of the partial
+// sums with it: sweep k writes partial buffer k & 1 and first applies update k - 1 from buffer (k - 1) & 1.
+bool thin_deferred(int path) { return path == 3; }
+float* thin_partial(const Layout& L, void* ws, int k) { return at<float>(ws, (k & 1) ? L.partial2 : L.partial); }
+ReduceArgs thin_prev(const nadmm_problem* prob, const Layout& L, void* ws, int k_prev) {
+  ReduceArgs r = reduce_args(prob, L, ws, L.thin_parts, 0, nullptr, nullptr, nullptr, nullptr);
+  r.partial = thin_partial(L, ws, k_prev);
+  return r;
+}
+
 // CG iteration k after the initialisation: q = H d, then the update of p, r, d (Section 2.4).  On the fused path
 // the update is deferred: iteration k's sweep first applies the update of iteration k - 1 (every workgroup for
 // itself), and the update of the last iteration is applied by whatever consumes the iterate (cg_pend(final_p)).
@@ -432,9 +450,25 @@ CgPend cg_pend(const Layout& L, void* ws, DevState* ds, int slot_in, bool final_
 // the gradient's reduction wrote; if this head finds the iteration finished, one sweep was made for nothing).
 int cg_iteration(const nadmm_problem* prob, const Layout& L, int path, void* ws, DevState* ds, const float* X,
                  bool write_pcache, float tol, int k, hipStream_t st, float* w_rows = nullptr,
-                 const NewtonHeadArgs* head = nullptr) {
+                 const NewtonHeadArgs* head = nullptr, bool thin_def = false) {
   float* dvec = at<float>(ws, L.dvec);
   float* q = at<float>(ws, L.q);
+  if (thin_def) {  // cached probabilities, no reduction kernel: see thin_deferred
+    if (!thin_deferred(path) || X != nullptr) return NADMM_EINVAL;
+    RowArgs ra = blank_rows();
+    ra.kind = kRowsHv;
+    ra.B1 = dvec;  // k == 0: the first direction; later the kernel takes the direction from the update it applies
+    ra.Pin = at<float>(ws, L.pcache);
+    ra.rows_out = at<float>(ws, L.drows);
+    int nparts = 0;
+    if (k == 0) {
+      ra.flag = &ds->cgs[0].active;
+      return sweep(prob, L, path, ws, ra, true, &nparts, st, nullptr, nullptr, thin_partial(L, ws, 0));
+    }
+    const CgPend c = cg_pend(L, ws, ds, (k - 1) & 1, false, tol);
+    const ReduceArgs prev = thin_prev(prob, L, ws, k - 1);
+    return sweep(prob, L, path, ws, ra, true, &nparts, st, &c, &prev, thin_partial(L, ws, k));
+  }
   if (cg_deferred(path)) {
     double* dot = at<double>(ws, L.dotpart);
     if (k == 0)  // nothing pending: d is the first direction, state slot 0 as the initialisation left it
@@ -564,18 +598,19 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
     if (!head_in_reduce) NADMM_HIP(launch_newton_head(nh, st));
 
     // CG on H p = -g with the probabilities of this iterate
+    const bool thin_def = thin_deferred(path) && params->max_cg >= 1;
     const bool hist = use_hist && cg_deferred(path) && params->max_cg >= 1 && params->max_cg <= L.hist_bufs;
     const size_t hist_stride = align256((size_t)L.s.n * L.s.NC * sizeof(float)) / sizeof(float);
     for (int k = 0; k < params->max_cg; ++k) {
       float* w_rows = hist ? at<float>(d_ws, L.hist) + (size_t)k * hist_stride : nullptr;
       if ((rc = cg_iteration(prob, L, path, d_ws, ds, nullptr, false, params->cg_tol, k, st, w_rows,
-                             (k == 0 && head_in_reduce) ? &nh : nullptr)) != NADMM_OK)
+                             (k == 0 && head_in_reduce) ? &nh : nullptr, thin_def)) != NADMM_OK)
         return rc;
     }
 
     // Armijo backtracking on Z(alpha) = A X + alpha A p, then X += alpha p.  With the deferred CG update the sweep
     // that forms A p applies the last update first and leaves p in its own buffer.
-    const bool pend = cg_deferred(path) && params->max_cg > 0;
+    const bool pend = (cg_deferred(path) || thin_def) && params->max_cg > 0;
     float* pstep = pend ? at<float>(d_ws, L.pfinal) : pdir;
     RowArgs rz = blank_rows();
     rz.kind = kRowsLogits;
@@ -588,7 +623,12 @@ static int local_newton_enqueue(const nadmm_problem* prob, float* d_X, const nad
         NADMM_HIP(launch_cg_pending_finish(cg_pend(L, d_ws, ds, (params->max_cg - 1) & 1, true, params->cg_tol), st));
     } else if (pend) {
       const CgPend c = cg_pend(L, d_ws, ds, (params->max_cg - 1) & 1, true, params->cg_tol);
-      if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st, &c)) != NADMM_OK) return rc;
+      if (thin_def) {  // the last sweep's partial sums are added up by this pass as well
+        const ReduceArgs prev = thin_prev(prob, L, d_ws, params->max_cg - 1);
+        if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st, &c, &prev)) != NADMM_OK) return rc;
+      } else if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st, &c)) != NADMM_OK) {
+        return rc;
+      }
     } else if ((rc = sweep(prob, L, path, d_ws, rz, false, &nparts, st)) != NADMM_OK) {
       return rc;
     }

@@ -346,7 +346,10 @@ hipError_t launch_cg_pending_finish(const CgPend& c, hipStream_t st);
 // ---- thin-data single-pass path (nadmm_thin.hip): p <= 32, p % 4 == 0, C-1 <= 3, lda == p ----
 bool thin_supported(const Shape& s, int64_t lda, const void* A);
 int thin_num_partials(const Shape& s);
-hipError_t launch_thin(const RowArgs& a, float* partial, int nparts, hipStream_t st);
+// cg, prev (both or neither): the sweep first applies the pending CG update, forming q = H d from the previous sweep's
+// partial sums prev->partial (prev also carries scale, lambda, rho of the linear terms); see ThinArgs in nadmm_thin.hip
+hipError_t launch_thin(const RowArgs& a, float* partial, int nparts, hipStream_t st, const CgPend* cg = nullptr,
+                       const ReduceArgs* prev = nullptr);
 
 // ---- column-sliced two-sweep matrix-core path (nadmm_sliced.hip): any p, C-1 <= 32, lda % 4 == 0 ----
 bool sliced_supported(const Shape& s, int64_t lda, const void* A);

@@ -10,7 +10,10 @@
 // accumulates a_i^T D into its private p x (C-1) registers.  The next chunk is
 // already in flight in registers while the current one is consumed.  Per-lane
 // accumulators are summed over the workgroup once, at the end, in a fixed order.
+#include <cstring>
+
 #include "nadmm_internal.h"
+#include "nadmm_cgstep.h"
 #include "nadmm_mfma.h"
 
 namespace nadmm {
@@ -26,10 +29,19 @@ struct ThinArgs {
   int32_t lds_stride;  // floats per row in LDS
   int32_t q1024;       // 1024 / p
   int32_t r1024;       // 1024 % p
+  // Deferred CG update (kernels instantiated with CG): the sweep of the previous CG iteration left only its per-workgroup
+  // partial sums of A^T D.  Every workgroup of this sweep adds them up (fixed order), forms q = H d, applies the update of
+  // Section 2.4 and takes its operand, the new direction (or, for the line search's pass, the final iterate), from there;
+  // workgroup 0 stores the new vectors and state.  No reduction kernel and no CG kernel run between two sweeps.
+  CgPend cg;           // cg.q and cg.dot_part are not used: this kernel forms both itself
+  const float* prev;   // the previous sweep's partial sums, nprev x (p*NC)
+  int32_t nprev;
+  float scale, lambda, rho;
+  const float* rho_scale;
 };
 
 // NQ = p / 4: float4 per row, which is also the float4 per lane in a chunk of 256 rows
-template <int NQ, int NC>
+template <int NQ, int NC, bool CG>
 __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
   constexpr int PP = 4 * NQ;
   constexpr int kMaxQuads = NQ;
@@ -41,8 +53,8 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
   const int t = threadIdx.x;
   constexpr int p = PP;
   constexpr int PS = (PP % 8 == 0) ? PP + 4 : PP;  // LDS row stride, off the bank period
-  const bool has0 = a.B0 != nullptr;
-  const bool has1 = a.B1 != nullptr;
+  const bool has0 = !CG && a.B0 != nullptr;
+  const bool has1 = CG || a.B1 != nullptr;
   const bool with_cols = ta.partial != nullptr;
 
   const int64_t r_begin = (int64_t)blockIdx.x * ta.rows_per_wg;
@@ -53,13 +65,74 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
 
   // X and V are the same for every lane: keep them as wave-uniform (scalar) registers
   float xs[PP][NC], vs[PP][NC];
+  if constexpr (CG) {
+    constexpr int D = PP * NC;      // length of the vectors, a multiple of 4
+    constexpr int NQV = D / 4;      // quads per partial
+    constexpr int GROUPS = kThinThreads / NQV;
+    constexpr int U = 24;           // partials per thread and memory round trip
+    __shared__ __attribute__((aligned(16))) float cgv[D];
+    __shared__ __attribute__((aligned(16))) float cgq[D];
+    __shared__ double cgdot[1];
+    __shared__ double cgsm[kThinThreads / 64 + 1];
+    const CgPend& c = ta.cg;
+    const int cur = c.st->cgs[c.slot_in].cur & 1;
+    const float* __restrict__ d_in = cur ? c.d[1] : c.d[0];
+    const float rho_ = ta.rho_scale != nullptr ? ta.rho * *ta.rho_scale : ta.rho;
+    const float dv = d_in[t < D ? t : D - 1];
+    // thread (group g, quad qd) adds the partials g, g + GROUPS, ... of its quad, in that order
+    const int qd = t % NQV, g = t / NQV;
+    const int gc = g < GROUPS ? g : GROUPS - 1;
+    const f32x4* __restrict__ pq = reinterpret_cast<const f32x4*>(ta.prev) + qd;
+    f32x4 s4 = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int k = gc; k < ta.nprev; k += U * GROUPS) {
+      f32x4 v[U];
 #pragma unroll
-  for (int j = 0; j < PP; ++j)
+      for (int u = 0; u < U; ++u) {
+        const int idx = k + u * GROUPS;
+        v[u] = pq[(size_t)(idx < ta.nprev ? idx : ta.nprev - 1) * NQV];
+      }
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      xs[j][c] = has0 ? __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.B0[j * NC + c]))) : 0.f;
-      vs[j][c] = has1 ? __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.B1[j * NC + c]))) : 0.f;
+      for (int u = 0; u < U; ++u)
+        if (k + u * GROUPS < ta.nprev) s4 += v[u];
     }
+    f32x4* gs = reinterpret_cast<f32x4*>(tile);  // [group][quad]: at most 256 quads, the smallest tile holds them
+    if (g < GROUPS) gs[g * NQV + qd] = s4;
+    __syncthreads();
+    if (t < 64) {  // the vectors fit one wave
+      double prod = 0.0;
+      if (t < D) {
+        float s2 = 0.f;
+        for (int g2 = 0; g2 < GROUPS; ++g2) s2 += tile[(g2 * NQV + (t >> 2)) * 4 + (t & 3)];
+        const float qv = fmaf(ta.lambda + rho_, dv, ta.scale * s2);
+        cgq[t] = qv;
+        prod = (double)dv * (double)qv;
+      }
+      prod = mfma_detail::wave64_sum(prod);
+      if (t == 0) cgdot[0] = prod;
+    }
+    __syncthreads();
+    CgPend c2 = c;
+    c2.q = cgq;
+    c2.dot_part = cgdot;
+    c2.ndot = 1;
+    if (!cg_pending_update<kThinThreads, 1>(c2, blockIdx.x == 0, cgv, cgsm, [] {})) return;
+#pragma unroll
+    for (int j = 0; j < PP; ++j)
+#pragma unroll
+      for (int c1 = 0; c1 < NC; ++c1) {
+        xs[j][c1] = 0.f;
+        vs[j][c1] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(cgv[j * NC + c1])));
+      }
+    __syncthreads();  // the tile is about to be overwritten by the first chunk
+  } else {
+#pragma unroll
+    for (int j = 0; j < PP; ++j)
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        xs[j][c] = has0 ? __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.B0[j * NC + c]))) : 0.f;
+        vs[j][c] = has1 ? __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.B1[j * NC + c]))) : 0.f;
+      }
+  }
 
   float acc[PP][NC];
 #pragma unroll
@@ -227,18 +300,19 @@ __global__ __launch_bounds__(kThinThreads) void thin_kernel(const ThinArgs ta) {
 int lds_stride_of(int p) { return (p % 8 == 0) ? p + 4 : p; }
 
 template <int NQ, int NC>
-hipError_t launch_thin_t(const ThinArgs& ta, int grid, hipStream_t st) {
+hipError_t launch_thin_t(const ThinArgs& ta, int grid, bool cg, hipStream_t st) {
   const size_t lds = (size_t)kThinThreads * ta.lds_stride * sizeof(float);
-  hipLaunchKernelGGL((thin_kernel<NQ, NC>), dim3(grid), dim3(kThinThreads), lds, st, ta);
+  if (cg) hipLaunchKernelGGL((thin_kernel<NQ, NC, true>), dim3(grid), dim3(kThinThreads), lds, st, ta);
+  else hipLaunchKernelGGL((thin_kernel<NQ, NC, false>), dim3(grid), dim3(kThinThreads), lds, st, ta);
   return hipGetLastError();
 }
 
 template <int NQ>
-hipError_t launch_thin_nq(const ThinArgs& ta, int grid, hipStream_t st) {
+hipError_t launch_thin_nq(const ThinArgs& ta, int grid, bool cg, hipStream_t st) {
   switch (ta.r.NC) {
-    case 1: return launch_thin_t<NQ, 1>(ta, grid, st);
-    case 2: return launch_thin_t<NQ, 2>(ta, grid, st);
-    case 3: return launch_thin_t<NQ, 3>(ta, grid, st);
+    case 1: return launch_thin_t<NQ, 1>(ta, grid, cg, st);
+    case 2: return launch_thin_t<NQ, 2>(ta, grid, cg, st);
+    case 3: return launch_thin_t<NQ, 3>(ta, grid, cg, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -261,8 +335,9 @@ int thin_num_partials(const Shape& s) {
   return (int)((chunks + per - 1) / per);
 }
 
-hipError_t launch_thin(const RowArgs& a, float* partial, int nparts, hipStream_t st) {
+hipError_t launch_thin(const RowArgs& a, float* partial, int nparts, hipStream_t st, const CgPend* cg, const ReduceArgs* prev) {
   ThinArgs ta;
+  std::memset(&ta, 0, sizeof(ta));
   ta.r = a;
   ta.partial = partial;
   const int64_t chunks = (a.n + kThinThreads - 1) / kThinThreads;
@@ -270,15 +345,29 @@ hipError_t launch_thin(const RowArgs& a, float* partial, int nparts, hipStream_t
   ta.lds_stride = lds_stride_of(a.p);  // must equal the kernel's compile-time stride
   ta.q1024 = 1024 / a.p;
   ta.r1024 = 1024 % a.p;
+  const bool with_cg = cg != nullptr;
+  if (with_cg) {
+    // the pending update of a CG iteration on cached probabilities (or the line search's logits pass on the final iterate)
+    if (prev == nullptr || prev->partial == nullptr || prev->nparts < 1 || prev->d != (int64_t)a.p * a.NC) return hipErrorInvalidValue;
+    if (a.B0 != nullptr || (a.kind != kRowsHv && a.kind != kRowsLogits) || cg->dlen != prev->d || cg->st == nullptr) return hipErrorInvalidValue;
+    if (prev->partial == partial) return hipErrorInvalidValue;  // the sweep reads the previous partials while it writes its own
+    ta.cg = *cg;
+    ta.prev = prev->partial;
+    ta.nprev = prev->nparts;
+    ta.scale = prev->scale;
+    ta.lambda = prev->lambda;
+    ta.rho = prev->rho;
+    ta.rho_scale = prev->rho_scale;
+  }
   switch (a.p >> 2) {
-    case 1: return launch_thin_nq<1>(ta, nparts, st);
-    case 2: return launch_thin_nq<2>(ta, nparts, st);
-    case 3: return launch_thin_nq<3>(ta, nparts, st);
-    case 4: return launch_thin_nq<4>(ta, nparts, st);
-    case 5: return launch_thin_nq<5>(ta, nparts, st);
-    case 6: return launch_thin_nq<6>(ta, nparts, st);
-    case 7: return launch_thin_nq<7>(ta, nparts, st);
-    case 8: return launch_thin_nq<8>(ta, nparts, st);
+    case 1: return launch_thin_nq<1>(ta, nparts, with_cg, st);
+    case 2: return launch_thin_nq<2>(ta, nparts, with_cg, st);
+    case 3: return launch_thin_nq<3>(ta, nparts, with_cg, st);
+    case 4: return launch_thin_nq<4>(ta, nparts, with_cg, st);
+    case 5: return launch_thin_nq<5>(ta, nparts, with_cg, st);
+    case 6: return launch_thin_nq<6>(ta, nparts, with_cg, st);
+    case 7: return launch_thin_nq<7>(ta, nparts, with_cg, st);
+    case 8: return launch_thin_nq<8>(ta, nparts, with_cg, st);
     default: return hipErrorInvalidValue;
   }
 }
