@@ -26,7 +26,7 @@ LG_PER_STEP = 100
 # that kernel path have changed since, the line reports traffic = null instead of a stale figure.
 MEASURED_HV_TRAFFIC = {
     ("image_like_60000x784_C10", 2): (207.1e6, "profiles/hessvec_fused_image_like_60000x784_C10.md", "d910ee797784"),
-    ("tall_binary_1375000x28_C2", 3): (154.4e6, "profiles/hessvec_thin_tall_binary_1375000x28_C2.md", "50df7e6d0973"),
+    ("tall_binary_1375000x28_C2", 3): (154.4e6, "profiles/hessvec_thin_tall_binary_1375000x28_C2.md", "e5e4ee407ae4"),
     ("wide_50000x3072_C10", 4): (1259.6e6, "profiles/hessvec_sliced_wide_50000x3072_C10.md", "fc83e16f100a"),
     ("large_multiclass_250000x2000_C20", 4): (4220.8e6, "profiles/hessvec_sliced_large_multiclass_250000x2000_C20.md", "fc83e16f100a"),
     # sparse storage: bytes between the L2 caches and the memory side, most of them operand rows served by the Infinity Cache

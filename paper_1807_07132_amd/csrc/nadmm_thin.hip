@@ -10,6 +10,9 @@
 // accumulates a_i^T D into its private p x (C-1) registers.  The next chunk is
 // already in flight in registers while the current one is consumed.  Per-lane
 // accumulators are summed over the workgroup once, at the end, in a fixed order.
+// Inside a Newton iteration the sweep of CG iteration k also does what lies between
+// two sweeps (Section 2.4): it adds up the partial sums of sweep k - 1, forms q = H d
+// and applies the CG update before it reads its operand (instantiations with CG).
 #include <cstring>
 
 #include "nadmm_internal.h"
