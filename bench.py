@@ -111,7 +111,8 @@ def cpu_baseline(w, seconds):
 
 
 def other_configs(nadmm, workloads, torch, np, skip):
-    """Hessian-vector time and HBM fraction of the other dense benchmark configurations (outside the timed steps)."""
+    """Hessian-vector and local-solve times with their HBM fractions for the other dense benchmark configurations
+    (outside the timed steps)."""
     out = {}
     for name in ("wide", "tall_binary", "large_multiclass"):
         if name == skip:
@@ -141,6 +142,22 @@ def other_configs(nadmm, workloads, torch, np, skip):
             nbytes = 4.0 * w.n * w.p + 12.0 * w.p * (w.C - 1)
             out[w.name] = {"hv_us": us, "hv_hbm_frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                            "kernel_path": nadmm.nadmm_query_kernel_path(gp)}
+            # one local Newton-CG solve at the workload's iteration budget (after one untimed solve), against the HBM
+            # time of the method's passes over A, as extra.local_solve_hbm_frac does for the headline workload
+            params = nadmm.make_params(w.max_newton, w.max_cg, w.max_ls, 0.0, 0.0, w.beta, w.gamma)
+            ws = gp.workspace(params)
+            X0 = torch.from_numpy(w.X0).cuda()
+            Xs = X0.clone()
+            nadmm.nadmm_local_newton(gp, Xs, params, want_stats=False, ws=ws)
+            Xs.copy_(X0)
+            e0.record()
+            nadmm.nadmm_local_newton(gp, Xs, params, want_stats=False, ws=ws)
+            e1.record()
+            torch.cuda.synchronize()
+            solve_s = e0.elapsed_time(e1) / 1e3
+            passes = w.max_newton * (w.max_cg + 2)
+            out[w.name].update({"local_solve_seconds": solve_s, "local_solve_passes_over_A": passes,
+                                "local_solve_hbm_frac": passes * 4.0 * w.n * w.p / solve_s / 1e9 / HBM_PEAK_GBS})
             del gp, ws, w
             torch.cuda.empty_cache()
         except Exception as e:  # never lose the headline line over an extra
